@@ -1,0 +1,200 @@
+/*
+ * exflow_moe.h — C ABI of the MI355X (gfx950) library for the single-GPU hot path of
+ * context-coherent Mixture-of-Experts inference with inter-layer expert affinity
+ * (arXiv 2401.08383).
+ *
+ * Two groups of calls:
+ *   MoE expert layer : moe_gate_topk -> moe_dispatch -> moe_expert_ffn -> moe_combine
+ *   affinity statistic: affinity_histogram, placement_locality
+ *
+ * Conventions that hold for every call
+ *   - Returns EXF_OK (0) or a negative EXF_ERR_* code; exf_last_error() gives the text of the
+ *     last failure on the calling thread.  No exception crosses the boundary.
+ *   - All argument validation happens on the host BEFORE anything is enqueued, so a call that
+ *     returns an error has launched nothing and touched no buffer.
+ *   - Pointers are DEVICE pointers unless a comment says "host".  The caller owns every
+ *     buffer; the library allocates nothing, frees nothing and keeps no pointer after the
+ *     call returns.  Scratch memory is the caller's `workspace` (size from the matching
+ *     *_workspace_bytes function, 256-byte aligned).
+ *   - Arrays are dense row-major.  Activation / weight pointers must be 16-byte aligned and
+ *     the reduction dimension is contiguous for every weight matrix.
+ *   - Calls enqueue on `stream` (a hipStream_t passed as void*, NULL = the default stream)
+ *     and return without synchronising; results are valid once the stream has been
+ *     synchronised.  Data-dependent sizes (tokens per expert) never return to the host.
+ *   - T == 0 / N == 0 is valid: nothing is read, counters and offsets are still written.
+ *   - dt selects the storage type of activations and weights together: EXF_F32 or EXF_BF16.
+ *     Accumulation is always fp32.
+ *   - Expert ids that fall outside [0,E) in topk_idx or trace cannot be rejected on the host;
+ *     the kernels skip them (see each call).
+ */
+#ifndef EXFLOW_MOE_H
+#define EXFLOW_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EXF_OK 0
+#define EXF_ERR_NULL_PTR (-1)
+#define EXF_ERR_BAD_SHAPE (-2)
+#define EXF_ERR_BAD_DTYPE (-3)
+#define EXF_ERR_WORKSPACE_TOO_SMALL (-4)
+#define EXF_ERR_HIP (-5)
+#define EXF_ERR_NOT_IMPLEMENTED (-6)
+#define EXF_ERR_MISALIGNED (-7)
+
+#define EXF_F32 0
+#define EXF_BF16 1
+
+#define EXF_ACT_GELU_ERF 0  /* z/2 * (1 + erf(z/sqrt 2)) */
+#define EXF_ACT_GELU_TANH 1 /* z/2 * (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) */
+
+#define EXF_MAX_EXPERTS 64   /* gate width E, local experts E_local and trace alphabet E */
+#define EXF_MAX_TOPK 2
+#define EXF_MAX_TRACE_LAYERS 256
+
+/* Library version (major*10000 + minor*100 + patch). */
+int exf_version(void);
+
+/* Text of the last error raised on this thread ("" if none).  Host pointer, owned by the
+ * library, valid until the next failing call on the same thread. */
+const char* exf_last_error(void);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_gate_topk — gate GEMM, softmax and top-k routing of one MoE layer.
+ * (Background, "Gating Strategies and Optimizations": softmax-based gating; Challenges,
+ *  "Data Locality": the gate decides each token's destination expert; Experimental setup:
+ *  top-1 gating with variable token capacity — no token is dropped or padded.  Table 1
+ *  carries the top-2 case.)
+ *
+ *   logits[t][e] = sum_c x[t][c] * w_gate[e][c]          (fp32 accumulation)
+ *   p[t][:]      = softmax(logits[t][:])                 (fp32)
+ *   slot j of token t = the j-th largest logit, ties to the LOWEST expert id; slot 0 is best
+ *   topk_w[t][j] = p[t][e_j]                             if k == 1 or renormalize == 0
+ *                = p[t][e_j] / sum_j' p[t][e_j']         otherwise
+ *
+ *   x        [T,d]  dt          w_gate [E,d] dt
+ *   logits_out [T,E] fp32, may be NULL
+ *   topk_idx [T,k] int32        topk_w [T,k] fp32
+ * Shapes: T >= 0, 1 <= E <= EXF_MAX_EXPERTS, 1 <= k <= min(E, EXF_MAX_TOPK),
+ *         d >= 8 and d % 8 == 0 (bf16) / d % 4 == 0 (fp32).  Inputs must be finite.
+ * ------------------------------------------------------------------------------------- */
+int moe_gate_topk(const void* x, const void* w_gate, int64_t T, int d, int E, int k,
+                  int renormalize, int dt, float* logits_out, int32_t* topk_idx, float* topk_w,
+                  void* stream);
+
+/* Selection and weights only, from given fp32 logits [T,E] (same rule as above).  Because
+ * it starts from stored logits its indices are a pure function of its input. */
+int moe_topk_from_logits(const float* logits, int64_t T, int E, int k, int renormalize,
+                         int32_t* topk_idx, float* topk_w, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_dispatch — group the token-to-expert assignments by expert ("token dispatch",
+ * Challenges, "Data Locality") as a STABLE counting sort, and gather the token rows into
+ * expert-contiguous order.
+ *
+ * Assignment a = t*k + j carries global expert id g = topk_idx[a].
+ *   local id e = expert_map ? expert_map[g] : g.
+ *   g outside [0,E), e < 0 (expert lives on another GPU) or e >= E_local: the assignment is
+ *   not kept, sorted_of_src[a] = -1.
+ * Kept assignments are ordered by (e, a).  With S = number kept = expert_offsets[E_local]:
+ *   expert_counts  [E_local]    tokens per local expert
+ *   expert_offsets [E_local+1]  exclusive scan of the counts
+ *   src_of_sorted  [A]          sorted position s -> a           (entries s >= S untouched)
+ *   sorted_of_src  [A]          a -> sorted position or -1
+ *   x_sorted       [A,d] dt     x_sorted[s] = x[src_of_sorted[s] / k]   (rows s >= S untouched);
+ *                               may be NULL to skip the row gather (then x may be NULL too)
+ * Shapes: A = T*k < 2^31, 1 <= k <= EXF_MAX_TOPK, 1 <= E_local <= EXF_MAX_EXPERTS, E >= 1,
+ *         d % 8 == 0 (bf16) / d % 4 == 0 (fp32).
+ * expert_map [E] int32 or NULL (identity: e = g, so an id >= E_local is not kept).
+ * workspace: moe_dispatch_workspace_bytes(T, k, E_local) bytes.
+ * ------------------------------------------------------------------------------------- */
+size_t moe_dispatch_workspace_bytes(int64_t T, int k, int E_local);
+int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* expert_map, int64_t T, int d,
+                 int k, int E, int E_local, int dt, void* x_sorted, int32_t* src_of_sorted,
+                 int32_t* sorted_of_src, int32_t* expert_counts, int32_t* expert_offsets,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_expert_ffn — every local expert applies its feed-forward network to the rows routed
+ * to it (Introduction and Challenges: experts are context-free FFNs).
+ *
+ * For sorted row s with expert_offsets[e] <= s < expert_offsets[e+1]:
+ *   h[u] = act( sum_c x_sorted[s][c] * w1[e][u][c] + b1[e][u] )     u < f
+ *   y[s][v] =   sum_u h[u] * w2[e][v][u] + b2[e][v]                 v < d
+ * Rows s >= expert_offsets[E_local] are not written.  expert_offsets is read on the device;
+ * the host never learns the per-expert sizes.  A must be an upper bound on
+ * expert_offsets[E_local] (normally T*k).
+ *
+ *   x_sorted [A,d] dt;  w1 [E_local,f,d] dt;  w2 [E_local,d,f] dt;
+ *   b1 [E_local,f] dt or NULL;  b2 [E_local,d] dt or NULL;  y_sorted [A,d] dt.
+ * bf16: the hidden activations are rounded to bf16 once, between the two contractions.
+ * Shapes: d, f multiples of 64 (bf16) / 4 (fp32); 1 <= E_local <= EXF_MAX_EXPERTS.
+ * workspace: moe_expert_ffn_workspace_bytes(A, d, f, E_local, dt) bytes (the [A,f] hidden).
+ * ------------------------------------------------------------------------------------- */
+size_t moe_expert_ffn_workspace_bytes(int64_t A, int d, int f, int E_local, int dt);
+int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offsets, const void* w1, const void* b1,
+                   const void* w2, const void* b2, int64_t A, int d, int f, int E_local, int act,
+                   int dt, void* y_sorted, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_combine — gate-weighted combination of the expert outputs (Background, "Expert
+ * Model": a soft gate combines the experts' outputs).
+ *   out[t][:] = sum_{j<k} topk_w[t][j] * y_sorted[ sorted_of_src[t*k+j] ][:]   (j ascending,
+ *   fp32 accumulation, one rounding to dt); assignments with position -1 contribute nothing.
+ *   y_sorted [A,d] dt; sorted_of_src [T*k] int32; topk_w [T,k] fp32; out [T,d] dt.
+ * ------------------------------------------------------------------------------------- */
+int moe_combine(const void* y_sorted, const int32_t* sorted_of_src, const float* topk_w, int64_t T,
+                int d, int k, int dt, void* out, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * affinity_histogram — inter-layer expert affinity from a routing trace (Design, "Modeling
+ * Inter-layer Expert Affinity", the conditional-probability equation; the heat-map figure).
+ *
+ *   trace [L,N] int32, layer-major: trace[l][n] = expert of token n at MoE layer l (top-1).
+ *   counts[l][i][p] = #{ n : trace[l][n] = i and trace[l+1][n] = p }       int64 [L-1,E,E]
+ *   loads [l][i]    = #{ n : trace[l][n] = i }                             int64 [L,E], may be NULL
+ *   cond_prob[l][i][p] = counts[l][i][p] / sum_p' counts[l][i][p'], 0 for an empty row
+ *                        — P(expert p at layer l+1 | expert i at layer l)  fp32 [L-1,E,E], may be NULL
+ *   n_invalid[0]    = number of trace entries outside [0,E)                int64 [1], may be NULL
+ * A transition with an invalid id at either end is not counted.  Outputs are overwritten,
+ * not accumulated.  Shapes: 1 <= L <= EXF_MAX_TRACE_LAYERS, N >= 0, 1 <= E <= EXF_MAX_EXPERTS.
+ * workspace: affinity_histogram_workspace_bytes(L, N, E) bytes.
+ * ------------------------------------------------------------------------------------- */
+size_t affinity_histogram_workspace_bytes(int L, int64_t N, int E);
+int affinity_histogram(const int32_t* trace, int L, int64_t N, int E, int64_t* counts, int64_t* loads,
+                       float* cond_prob, int64_t* n_invalid, void* workspace, size_t workspace_bytes,
+                       void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * placement_locality — how many layer-to-layer transitions stay on the device that holds
+ * the token, for a given expert-to-device placement (Design, "Solving Affinity's duality by
+ * Integer Programming": the objective sums the crossing indicators R over tokens and the
+ * L-1 transitions; Evaluation, "Reduced Cross-GPU Token Routing": the share of tokens routed
+ * to experts on their current GPU).
+ *
+ *   placement [L,E] int32: device (GPU or node) of expert e at layer l, any value in [0,G).
+ *   local_per_pair[l] = #{ n : placement[l][trace[l][n]] == placement[l+1][trace[l+1][n]] }
+ *                                                                           int64 [L-1]
+ * so the objective equals N*(L-1) - sum(local_per_pair) and the locality fraction is
+ * sum(local_per_pair) / (N*(L-1)), both formed by the caller.  Transitions with an invalid
+ * expert id are not counted.  The map is scored as given; exf_check_placement tests the
+ * load-balance and exclusivity constraints.
+ * workspace: placement_locality_workspace_bytes(L, N) bytes.
+ * ------------------------------------------------------------------------------------- */
+size_t placement_locality_workspace_bytes(int L, int64_t N);
+int placement_locality(const int32_t* trace, const int32_t* placement, int L, int64_t N, int E, int G,
+                       int64_t* local_per_pair, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Host helper: placement is a HOST array [L,E].  Returns EXF_OK iff every entry is in [0,G)
+ * and every device holds exactly E/G experts of every layer (the load-balance and
+ * exclusivity constraints of the integer program); EXF_ERR_BAD_SHAPE otherwise. */
+int exf_check_placement(const int32_t* placement_host, int L, int E, int G);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EXFLOW_MOE_H */

@@ -1,0 +1,235 @@
+"""Thin ctypes binding of ``libexflow_moe.so`` (the C ABI declared in ``include/exflow_moe.h``).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch
+is used for device memory (``torch.empty(..., device="cuda")``, ``.data_ptr()``) and for the
+current HIP stream.  There is no CPU fallback: if the library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libexflow_moe.so")
+
+EXF_OK = 0
+EXF_ERR_NULL_PTR = -1
+EXF_ERR_BAD_SHAPE = -2
+EXF_ERR_BAD_DTYPE = -3
+EXF_ERR_WORKSPACE_TOO_SMALL = -4
+EXF_ERR_HIP = -5
+EXF_ERR_NOT_IMPLEMENTED = -6
+EXF_ERR_MISALIGNED = -7
+EXF_F32 = 0
+EXF_BF16 = 1
+EXF_ACT_GELU_ERF = 0
+EXF_ACT_GELU_TANH = 1
+
+_vp, _i, _i64, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+
+# name -> (restype, argtypes); mirrors include/exflow_moe.h one to one
+SIGNATURES = {
+    "exf_version": (_i, []),
+    "exf_last_error": (ctypes.c_char_p, []),
+    "exf_check_placement": (_i, [_vp, _i, _i, _i]),
+    "moe_gate_topk": (_i, [_vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "moe_topk_from_logits": (_i, [_vp, _i64, _i, _i, _i, _vp, _vp, _vp]),
+    "moe_dispatch_workspace_bytes": (_sz, [_i64, _i, _i]),
+    "moe_dispatch": (_i, [_vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_expert_ffn_workspace_bytes": (_sz, [_i64, _i, _i, _i, _i]),
+    "moe_expert_ffn": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]),
+    "moe_combine": (_i, [_vp, _vp, _vp, _i64, _i, _i, _i, _vp, _vp]),
+    "affinity_histogram_workspace_bytes": (_sz, [_i, _i64, _i]),
+    "affinity_histogram": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "placement_locality_workspace_bytes": (_sz, [_i, _i64]),
+    "placement_locality": (_i, [_vp, _vp, _i, _i64, _i, _i, _vp, _vp, _sz, _vp]),
+}
+
+_lib = None
+
+
+class ExflowError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"exflow_moe error {code}: {message}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2401_08383_amd.build` (there is no fallback path)")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def last_error() -> str:
+    return lib().exf_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != EXF_OK:
+        raise ExflowError(rc, last_error())
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return EXF_F32
+    if t.dtype == torch.bfloat16:
+        return EXF_BF16
+    raise ExflowError(EXF_ERR_BAD_DTYPE, f"unsupported dtype {t.dtype}")
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# ----------------------------------------------------------------------------------------------
+def moe_gate_topk(x, w_gate, k, renormalize=False, want_logits=False):
+    """-> (topk_idx int32 [T,k], topk_w fp32 [T,k], logits fp32 [T,E] or None)."""
+    T, d = x.shape
+    E = w_gate.shape[0]
+    assert w_gate.shape[1] == d and x.is_contiguous() and w_gate.is_contiguous() and x.dtype == w_gate.dtype
+    idx = torch.empty((T, k), dtype=torch.int32, device=x.device)
+    w = torch.empty((T, k), dtype=torch.float32, device=x.device)
+    logits = torch.empty((T, E), dtype=torch.float32, device=x.device) if want_logits else None
+    _check(lib().moe_gate_topk(_ptr(x), _ptr(w_gate), T, d, E, k, int(bool(renormalize)), dtype_code(x), _ptr(logits),
+                               _ptr(idx), _ptr(w), _stream()))
+    return idx, w, logits
+
+
+def moe_topk_from_logits(logits, k, renormalize=False):
+    T, E = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    idx = torch.empty((T, k), dtype=torch.int32, device=logits.device)
+    w = torch.empty((T, k), dtype=torch.float32, device=logits.device)
+    _check(lib().moe_topk_from_logits(_ptr(logits), T, E, k, int(bool(renormalize)), _ptr(idx), _ptr(w), _stream()))
+    return idx, w
+
+
+class DispatchResult:
+    __slots__ = ("x_sorted", "src_of_sorted", "sorted_of_src", "expert_counts", "expert_offsets")
+
+    def __init__(self, x_sorted, src_of_sorted, sorted_of_src, expert_counts, expert_offsets):
+        self.x_sorted = x_sorted
+        self.src_of_sorted = src_of_sorted
+        self.sorted_of_src = sorted_of_src
+        self.expert_counts = expert_counts
+        self.expert_offsets = expert_offsets
+
+
+def moe_dispatch(x, topk_idx, E, E_local=None, expert_map=None, out=None, workspace=None, gather=True):
+    """Stable dispatch of the assignments; returns a DispatchResult of device tensors.
+
+    Entries of ``src_of_sorted`` / rows of ``x_sorted`` at or beyond ``expert_offsets[E_local]``
+    are left untouched by the library.  ``out`` may carry a previous DispatchResult to reuse.
+    """
+    T, k = topk_idx.shape
+    d = x.shape[1]
+    E_local = E if E_local is None else E_local
+    A = T * k
+    dev = topk_idx.device
+    assert topk_idx.dtype == torch.int32 and topk_idx.is_contiguous() and x.is_contiguous()
+    if out is None:
+        out = DispatchResult(
+            torch.empty((A, d), dtype=x.dtype, device=dev) if gather else None,
+            torch.empty(A, dtype=torch.int32, device=dev),
+            torch.empty(A, dtype=torch.int32, device=dev),
+            torch.empty(E_local, dtype=torch.int32, device=dev),
+            torch.empty(E_local + 1, dtype=torch.int32, device=dev),
+        )
+    nbytes = lib().moe_dispatch_workspace_bytes(T, k, E_local)
+    if workspace is None:
+        workspace = _workspace(nbytes, dev)
+    _check(lib().moe_dispatch(_ptr(x), _ptr(topk_idx), _ptr(expert_map), T, d, k, E, E_local, dtype_code(x),
+                              _ptr(out.x_sorted), _ptr(out.src_of_sorted), _ptr(out.sorted_of_src),
+                              _ptr(out.expert_counts), _ptr(out.expert_offsets), _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def moe_expert_ffn(x_sorted, expert_offsets, w1, w2, b1=None, b2=None, act=EXF_ACT_GELU_ERF, out=None, workspace=None):
+    A, d = x_sorted.shape
+    E_local, f, d2 = w1.shape
+    assert d2 == d and tuple(w2.shape) == (E_local, d, f) and expert_offsets.numel() == E_local + 1
+    assert x_sorted.is_contiguous() and w1.is_contiguous() and w2.is_contiguous()
+    assert expert_offsets.dtype == torch.int32
+    dt = dtype_code(x_sorted)
+    if out is None:
+        out = torch.empty((A, d), dtype=x_sorted.dtype, device=x_sorted.device)
+    nbytes = lib().moe_expert_ffn_workspace_bytes(A, d, f, E_local, dt)
+    if workspace is None:
+        workspace = _workspace(nbytes, x_sorted.device)
+    _check(lib().moe_expert_ffn(_ptr(x_sorted), _ptr(expert_offsets), _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), A, d, f,
+                                E_local, act, dt, _ptr(out), _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def moe_combine(y_sorted, sorted_of_src, topk_w, out=None):
+    T, k = topk_w.shape
+    d = y_sorted.shape[1]
+    assert sorted_of_src.numel() == T * k and y_sorted.is_contiguous() and topk_w.dtype == torch.float32
+    if out is None:
+        out = torch.empty((T, d), dtype=y_sorted.dtype, device=y_sorted.device)
+    _check(lib().moe_combine(_ptr(y_sorted), _ptr(sorted_of_src), _ptr(topk_w), T, d, k, dtype_code(y_sorted), _ptr(out),
+                             _stream()))
+    return out
+
+
+def affinity_histogram(trace, E, want_loads=True, want_prob=True, want_invalid=True, workspace=None, out=None):
+    """trace int32 [L,N] on the device -> dict(counts, loads, cond_prob, n_invalid) of device tensors."""
+    L, N = trace.shape
+    assert trace.dtype == torch.int32 and trace.is_contiguous()
+    dev = trace.device
+    if out is None:
+        out = dict(
+            counts=torch.empty((max(L - 1, 0), E, E), dtype=torch.int64, device=dev),
+            loads=torch.empty((L, E), dtype=torch.int64, device=dev) if want_loads else None,
+            cond_prob=torch.empty((max(L - 1, 0), E, E), dtype=torch.float32, device=dev) if want_prob else None,
+            n_invalid=torch.empty(1, dtype=torch.int64, device=dev) if want_invalid else None,
+        )
+    nbytes = lib().affinity_histogram_workspace_bytes(L, N, E)
+    if workspace is None:
+        workspace = _workspace(nbytes, dev)
+    _check(lib().affinity_histogram(_ptr(trace), L, N, E, _ptr(out["counts"]), _ptr(out["loads"]), _ptr(out["cond_prob"]),
+                                    _ptr(out["n_invalid"]), _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def placement_locality(trace, placement, G, workspace=None, out=None):
+    """-> local_per_pair int64 [L-1] (device); fraction = sum / (N*(L-1))."""
+    L, N = trace.shape
+    E = placement.shape[1]
+    assert placement.shape[0] == L and placement.dtype == torch.int32 and trace.dtype == torch.int32
+    assert trace.is_contiguous() and placement.is_contiguous()
+    if out is None:
+        out = torch.empty(max(L - 1, 0), dtype=torch.int64, device=trace.device)
+    nbytes = lib().placement_locality_workspace_bytes(L, N)
+    if workspace is None:
+        workspace = _workspace(nbytes, trace.device)
+    _check(lib().placement_locality(_ptr(trace), _ptr(placement), L, N, E, G, _ptr(out), _ptr(workspace), workspace.numel(),
+                                    _stream()))
+    return out
+
+
+def check_placement(placement_host, G) -> bool:
+    """Load-balance and exclusivity constraints of a HOST placement (torch CPU int32 [L,E])."""
+    assert placement_host.device.type == "cpu" and placement_host.dtype == torch.int32 and placement_host.is_contiguous()
+    L, E = placement_host.shape
+    return lib().exf_check_placement(placement_host.data_ptr(), L, E, G) == EXF_OK

@@ -1,0 +1,118 @@
+// Shared host/device helpers of the gfx950 library: error reporting, bf16 conversion,
+// wavefront primitives.  Nothing here is used by the CPU checker.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "exflow_moe.h"
+
+namespace exf {
+
+// ---- host side ---------------------------------------------------------------------------
+// Records a formatted message for exf_last_error() on this thread and returns `code`.
+int fail(int code, const char* fmt, ...);
+// Maps the pending HIP launch error (if any) to EXF_ERR_HIP.
+int check_launch(const char* what);
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+#define EXF_REQUIRE_PTR(p)                                                        \
+    do {                                                                          \
+        if ((p) == nullptr) return ::exf::fail(EXF_ERR_NULL_PTR, "%s: %s is NULL", __func__, #p); \
+    } while (0)
+#define EXF_REQUIRE_ALIGNED(p)                                                    \
+    do {                                                                          \
+        if (!::exf::aligned16(p))                                                 \
+            return ::exf::fail(EXF_ERR_MISALIGNED, "%s: %s is not 16-byte aligned", __func__, #p); \
+    } while (0)
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+// ---- device side -------------------------------------------------------------------------
+typedef uint16_t bf16_t;  // storage only; arithmetic is fp32
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+
+// Round-to-nearest-even; inputs are finite by contract (NaN is quieted).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<bf16_t>(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+__device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & (kWave - 1); }
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v)
+{
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Inclusive prefix sum across the 64 lanes of a wavefront.
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        int n = __shfl_up(v, off, kWave);
+        if (lane >= off) v += n;
+    }
+    return v;
+}
+
+// Which expert owns row-tile `tile` when every expert's rows [off[e], off[e+1]) are cut into
+// tiles of `mt` rows (tiles never straddle experts)?  Every lane of the calling wavefront
+// returns the same answer.  e = -1 if `tile` is beyond the last tile.  E_local <= 64;
+// max_rows is the row capacity of the activation buffers.
+struct TileRef {
+    int expert;     // local expert id or -1
+    int row_begin;  // first sorted row of the tile
+    int row_end;    // one past the last valid sorted row of the tile
+    int total;      // total number of row tiles over all experts
+};
+
+__device__ __forceinline__ TileRef locate_row_tile(const int32_t* __restrict__ offsets, int E_local, int mt, int tile,
+                                                   int max_rows)
+{
+    const int lane = lane_id();
+    int lo = 0, hi = 0;
+    if (lane < E_local) {  // clamped so that a corrupt offsets array can never index past the buffers
+        lo = min(max(offsets[lane], 0), max_rows);
+        hi = min(max(offsets[lane + 1], lo), max_rows);
+    }
+    const int cnt = hi - lo;
+    const int tiles = cnt > 0 ? (cnt + mt - 1) / mt : 0;
+    const int incl = wave_inclusive_scan(tiles);
+    const int excl = incl - tiles;
+    const bool mine = (lane < E_local) && (tile >= excl) && (tile < incl);
+    const unsigned long long m = __ballot(mine);
+    TileRef r;
+    r.total = __shfl(incl, kWave - 1, kWave);
+    if (m == 0ull) {
+        r.expert = -1;
+        r.row_begin = 0;
+        r.row_end = 0;
+        return r;
+    }
+    const int src = __ffsll(static_cast<long long>(m)) - 1;
+    const int e_lo = __shfl(lo, src, kWave);
+    const int e_hi = __shfl(hi, src, kWave);
+    const int e_excl = __shfl(excl, src, kWave);
+    r.expert = src;
+    r.row_begin = e_lo + (tile - e_excl) * mt;
+    r.row_end = min(r.row_begin + mt, e_hi);
+    return r;
+}
+
+}  // namespace exf

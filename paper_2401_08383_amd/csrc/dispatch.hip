@@ -1,0 +1,210 @@
+// moe_dispatch: stable counting sort of the token-to-expert assignments + row gather.
+//
+//   1. count   : every workgroup histograms its chunk of CH consecutive assignments into LDS
+//                and stores one row of per-expert counts.
+//   2. scan    : one workgroup turns the [blocks x E_local] count matrix into per-chunk start
+//                positions (exclusive scan down each expert column) and writes expert_counts /
+//                expert_offsets.
+//   3. scatter : every workgroup ranks its chunk again — rank inside a wavefront from a ballot
+//                per expert (lanes with a lower id and the same expert), wavefronts ordered
+//                through LDS — which keeps equal experts in ascending assignment order
+//                (stable, hence a unique permutation), and writes both index maps.
+//   4. gather  : x_sorted[s] = x[src_of_sorted[s] / k] as 16-byte vector copies.
+// No step needs the host to know a data-dependent size.
+#include "common.hpp"
+
+namespace exf {
+
+constexpr int kDispThreads = 256;
+constexpr int kDispWaves = kDispThreads / kWave;
+constexpr int kDispChunk = 1024;  // assignments per workgroup in count / scatter
+
+__device__ __forceinline__ int local_expert(const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ expert_map,
+                                            int64_t a, int E, int E_local)
+{
+    const int g = topk_idx[a];
+    if (g < 0 || g >= E) return -1;
+    const int e = expert_map != nullptr ? expert_map[g] : g;
+    return (e >= 0 && e < E_local) ? e : -1;
+}
+
+__global__ __launch_bounds__(kDispThreads) void dispatch_count_kernel(const int32_t* __restrict__ topk_idx,
+                                                                       const int32_t* __restrict__ expert_map, int64_t A,
+                                                                       int E, int E_local,
+                                                                       int32_t* __restrict__ block_counts)
+{
+    __shared__ int cnt[EXF_MAX_EXPERTS];
+    if (threadIdx.x < EXF_MAX_EXPERTS) cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kDispChunk;
+    for (int i = threadIdx.x; i < kDispChunk; i += kDispThreads) {
+        const int64_t a = base + i;
+        if (a < A) {
+            const int e = local_expert(topk_idx, expert_map, a, E, E_local);
+            if (e >= 0) atomicAdd(&cnt[e], 1);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < E_local) block_counts[static_cast<int64_t>(blockIdx.x) * E_local + threadIdx.x] = cnt[threadIdx.x];
+}
+
+// One workgroup of 64 threads: thread e walks down column e of block_counts.
+__global__ __launch_bounds__(kWave) void dispatch_scan_kernel(int32_t* __restrict__ block_counts, int n_blocks, int E_local,
+                                                               int32_t* __restrict__ expert_counts,
+                                                               int32_t* __restrict__ expert_offsets)
+{
+    const int e = threadIdx.x;
+    int total = 0;
+    if (e < E_local) {
+        for (int b = 0; b < n_blocks; ++b) {
+            const int64_t i = static_cast<int64_t>(b) * E_local + e;
+            const int c = block_counts[i];
+            block_counts[i] = total;  // start of this chunk inside expert e's bucket
+            total += c;
+        }
+        expert_counts[e] = total;
+    }
+    const int incl = wave_inclusive_scan(e < E_local ? total : 0);
+    if (e < E_local) expert_offsets[e] = incl - total;
+    if (e == E_local - 1) expert_offsets[E_local] = incl;
+}
+
+__global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
+    const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ expert_map, int64_t A, int E, int E_local,
+    const int32_t* __restrict__ block_base, const int32_t* __restrict__ expert_offsets, int32_t* __restrict__ src_of_sorted,
+    int32_t* __restrict__ sorted_of_src)
+{
+    __shared__ int cursor[EXF_MAX_EXPERTS];               // next free sorted position per expert
+    __shared__ int wave_cnt[kDispWaves][EXF_MAX_EXPERTS];  // per-round, per-wavefront counts
+    const int lane = lane_id();
+    const int wave = threadIdx.x / kWave;
+    if (threadIdx.x < E_local)
+        cursor[threadIdx.x] = expert_offsets[threadIdx.x] + block_base[static_cast<int64_t>(blockIdx.x) * E_local + threadIdx.x];
+    __syncthreads();
+
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kDispChunk;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int round = 0; round < kDispChunk / kDispThreads; ++round) {
+        const int64_t a = base + round * kDispThreads + threadIdx.x;
+        const int e = a < A ? local_expert(topk_idx, expert_map, a, E, E_local) : -1;
+        int rank = 0;
+        for (int q = 0; q < E_local; ++q) {
+            const unsigned long long m = __ballot(e == q);
+            if (e == q) rank = __popcll(m & below);
+            if (lane == q) wave_cnt[wave][q] = __popcll(m);
+        }
+        __syncthreads();
+        if (e >= 0) {
+            int pos = cursor[e] + rank;
+            for (int w = 0; w < wave; ++w) pos += wave_cnt[w][e];
+            src_of_sorted[pos] = static_cast<int32_t>(a);
+            sorted_of_src[a] = pos;
+        } else if (a < A) {
+            sorted_of_src[a] = -1;
+        }
+        __syncthreads();
+        if (threadIdx.x < E_local) {
+            int add = 0;
+            for (int w = 0; w < kDispWaves; ++w) add += wave_cnt[w][threadIdx.x];
+            cursor[threadIdx.x] += add;
+        }
+        __syncthreads();
+    }
+}
+
+// 16-byte chunks of the kept rows; `vec_per_row` = row bytes / 16.
+__global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ src_of_sorted,
+                                                               const int32_t* __restrict__ expert_offsets, int E_local, int k,
+                                                               int vec_per_row, int64_t A, uint4* __restrict__ x_sorted)
+{
+    const int64_t kept = min(static_cast<int64_t>(max(expert_offsets[E_local], 0)), A);
+    const int64_t total = kept * vec_per_row;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < total; i += 4 * stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t j = i + u * stride;
+            const int64_t s = j / vec_per_row;
+            const int c = static_cast<int>(j - s * vec_per_row);
+            v[u] = x[static_cast<int64_t>(src_of_sorted[s] / k) * vec_per_row + c];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x_sorted[i + u * stride] = v[u];
+    }
+    for (; i < total; i += stride) {
+        const int64_t s = i / vec_per_row;
+        const int c = static_cast<int>(i - s * vec_per_row);
+        x_sorted[i] = x[static_cast<int64_t>(src_of_sorted[s] / k) * vec_per_row + c];
+    }
+}
+
+static int64_t dispatch_blocks(int64_t A) { return (A + kDispChunk - 1) / kDispChunk; }
+
+}  // namespace exf
+
+extern "C" size_t moe_dispatch_workspace_bytes(int64_t T, int k, int E_local)
+{
+    if (T < 0 || k < 1 || E_local < 1) return 0;
+    const int64_t blocks = exf::dispatch_blocks(T * k);
+    return exf::align_up(static_cast<size_t>(blocks > 0 ? blocks : 1) * static_cast<size_t>(E_local) * sizeof(int32_t), 256);
+}
+
+extern "C" int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* expert_map, int64_t T, int d, int k, int E,
+                            int E_local, int dt, void* x_sorted, int32_t* src_of_sorted, int32_t* sorted_of_src,
+                            int32_t* expert_counts, int32_t* expert_offsets, void* workspace, size_t workspace_bytes,
+                            void* stream)
+{
+    using namespace exf;
+    if (dt != EXF_F32 && dt != EXF_BF16) return fail(EXF_ERR_BAD_DTYPE, "moe_dispatch: dt = %d", dt);
+    if (T < 0) return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch: T = %lld < 0", static_cast<long long>(T));
+    if (k < 1 || k > EXF_MAX_TOPK) return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch: k = %d outside [1,%d]", k, EXF_MAX_TOPK);
+    if (E < 1) return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch: E = %d < 1", E);
+    if (E_local < 1 || E_local > EXF_MAX_EXPERTS)
+        return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch: E_local = %d outside [1,%d]", E_local, EXF_MAX_EXPERTS);
+    const int64_t A = T * k;
+    if (A >= (1ll << 31)) return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch: T*k must be below 2^31");
+    const int gran = dt == EXF_BF16 ? 8 : 4;
+    if (x_sorted != nullptr && (d < gran || d % gran != 0))
+        return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch: d = %d must be a positive multiple of %d", d, gran);
+    EXF_REQUIRE_PTR(expert_counts);
+    EXF_REQUIRE_PTR(expert_offsets);
+    EXF_REQUIRE_PTR(workspace);
+    if (workspace_bytes < moe_dispatch_workspace_bytes(T, k, E_local))
+        return fail(EXF_ERR_WORKSPACE_TOO_SMALL, "moe_dispatch: workspace %zu < %zu bytes", workspace_bytes,
+                    moe_dispatch_workspace_bytes(T, k, E_local));
+    if (A > 0) {
+        EXF_REQUIRE_PTR(topk_idx);
+        EXF_REQUIRE_PTR(src_of_sorted);
+        EXF_REQUIRE_PTR(sorted_of_src);
+        if (x_sorted != nullptr) {
+            EXF_REQUIRE_PTR(x);
+            EXF_REQUIRE_ALIGNED(x);
+            EXF_REQUIRE_ALIGNED(x_sorted);
+        }
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t* block_counts = static_cast<int32_t*>(workspace);
+    const int n_blocks = static_cast<int>(dispatch_blocks(A));
+    if (n_blocks > 0)
+        hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E, E_local,
+                           block_counts);
+    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(kWave), 0, s, block_counts, n_blocks, E_local, expert_counts,
+                       expert_offsets);
+    if (n_blocks > 0) {
+        hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E,
+                           E_local, block_counts, expert_offsets, src_of_sorted, sorted_of_src);
+        if (x_sorted != nullptr) {
+            const int vec_per_row = d * (dt == EXF_BF16 ? 2 : 4) / 16;
+            const int64_t vecs = A * vec_per_row;
+            int64_t blocks = (vecs + 256 * 4 - 1) / (256 * 4);
+            if (blocks > 256 * 16) blocks = 256 * 16;
+            if (blocks < 1) blocks = 1;
+            hipLaunchKernelGGL(dispatch_gather_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
+                               static_cast<const uint4*>(x), src_of_sorted, expert_offsets, E_local, k, vec_per_row, A,
+                               static_cast<uint4*>(x_sorted));
+        }
+    }
+    return check_launch("moe_dispatch");
+}

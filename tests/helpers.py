@@ -1,0 +1,87 @@
+"""Helpers shared by the GPU parity tests: host <-> device conversion and comparison rules."""
+import numpy as np
+import torch
+
+import synth_inputs as syn
+
+DEV = "cuda:0"
+
+# Output tolerances (relative to max |reference|) fixed by the task: bf16 2e-2, fp32 1e-5.
+OUT_RTOL = {"bf16": 2e-2, "f32": 1e-5}
+# Gate logits / weights: identical stored inputs, fp32 accumulation in a different order than
+# the fp64 reference: |delta| <= tol * max(1, |ref|).
+GATE_TOL = {"bf16": 1e-4, "f32": 1e-5}
+
+
+def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
+    """fp32 host array holding storage-exact values -> device tensor of the storage dtype."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)  # exact: the values are already bf16-representable
+    return t.to(DEV)
+
+
+def dev_i32(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> host array; bf16 is widened exactly to fp32."""
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy()
+    return t.cpu().numpy()
+
+
+def assert_close_max(got, ref, rtol, what=""):
+    """max |got - ref| <= rtol * max |ref|, plus the per-element report."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    scale = np.abs(ref).max()
+    err = np.abs(got - ref).max()
+    assert np.isfinite(got).all(), what
+    assert err <= rtol * max(scale, 1e-30), f"{what}: max err {err:.3e} > {rtol:.1e} * {scale:.3e}"
+    rms = np.sqrt((ref ** 2).mean())
+    bad = (np.abs(got - ref) > rtol * (np.abs(ref) + rms)).sum()
+    assert bad == 0, f"{what}: {bad} elements outside rtol*(|ref|+rms)"
+
+
+def assert_gate_close(got, ref, tol, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape
+    if ref.size:
+        lim = tol * np.maximum(1.0, np.abs(ref))
+        assert (np.abs(got - ref) <= lim).all(), f"{what}: max excess {(np.abs(got - ref) - lim).max():.3e}"
+
+
+def check_routing_against_fp64(idx_gpu, logits64, k, tol):
+    """End-to-end routing check: tokens whose fp64 decision margins exceed `tol` must match the
+    fp64 choice exactly; for the others the GPU's pick must be one of the near-tied experts.
+    Returns the number of ambiguous tokens."""
+    T, E = logits64.shape
+    order = np.argsort(-logits64, axis=1, kind="stable")  # ties -> lowest id first
+    srt = np.take_along_axis(logits64, order, axis=1)
+    scale = np.maximum(1.0, np.abs(srt[:, 0]))
+    ambiguous = np.zeros(T, dtype=bool)
+    for j in range(k):
+        if j + 1 < E:
+            ambiguous |= (srt[:, j] - srt[:, j + 1]) < tol * scale
+    clear = ~ambiguous
+    assert (idx_gpu[clear] == order[clear, :k]).all(), "routing differs from fp64 on a clear-margin token"
+    for t in np.nonzero(ambiguous)[0]:
+        for j in range(k):
+            chosen = logits64[t, idx_gpu[t, j]]
+            assert abs(chosen - srt[t, j]) < 4 * tol * scale[t], (t, j)
+        assert len(set(idx_gpu[t].tolist())) == k
+    return int(ambiguous.sum())
+
+
+def expected_dispatch_compare(res_gpu, ref, A):
+    kept = ref["kept"]
+    np.testing.assert_array_equal(res_gpu.expert_counts.cpu().numpy(), ref["counts"])
+    np.testing.assert_array_equal(res_gpu.expert_offsets.cpu().numpy(), ref["offsets"])
+    np.testing.assert_array_equal(res_gpu.src_of_sorted.cpu().numpy()[:kept], ref["src_of_sorted"])
+    np.testing.assert_array_equal(res_gpu.sorted_of_src.cpu().numpy(), ref["sorted_of_src"])

@@ -1,0 +1,114 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before anything could be launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2401_08383_amd as exf
+from paper_2401_08383_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "exflow_moe.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(?:int|size_t|const char\*)\s+(\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"moe_gate_topk", "moe_dispatch", "moe_expert_ffn", "moe_combine", "affinity_histogram",
+            "placement_locality"} <= set(names)
+    lib = exf.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.SIGNATURES) == names  # the binding covers exactly the header
+    assert lib.exf_version() >= 100
+
+
+def test_host_validation_rejects_before_launch():
+    lib = exf.lib()
+    one = ctypes.c_void_p(4096)  # a non-null, 16-byte aligned dummy; never dereferenced on these paths
+    odd = ctypes.c_void_p(4100)
+    cases = [
+        (lambda: lib.moe_gate_topk(one, one, 4, 64, 8, 1, 0, 7, None, one, one, None), B.EXF_ERR_BAD_DTYPE),
+        (lambda: lib.moe_gate_topk(one, one, 4, 60, 8, 1, 0, B.EXF_BF16, None, one, one, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_gate_topk(one, one, 4, 64, 65, 1, 0, B.EXF_BF16, None, one, one, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_gate_topk(one, one, 4, 64, 8, 3, 0, B.EXF_BF16, None, one, one, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_gate_topk(one, one, 4, 64, 1, 2, 0, B.EXF_BF16, None, one, one, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_gate_topk(one, one, -1, 64, 8, 1, 0, B.EXF_BF16, None, one, one, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_gate_topk(None, one, 4, 64, 8, 1, 0, B.EXF_BF16, None, one, one, None), B.EXF_ERR_NULL_PTR),
+        (lambda: lib.moe_gate_topk(odd, one, 4, 64, 8, 1, 0, B.EXF_BF16, None, one, one, None), B.EXF_ERR_MISALIGNED),
+        (lambda: lib.moe_topk_from_logits(None, 4, 8, 1, 0, one, one, None), B.EXF_ERR_NULL_PTR),
+        (lambda: lib.moe_dispatch(one, one, None, 4, 64, 1, 8, 8, B.EXF_BF16, one, one, one, one, one, one, 0, None),
+         B.EXF_ERR_WORKSPACE_TOO_SMALL),
+        (lambda: lib.moe_dispatch(one, one, None, 4, 64, 3, 8, 8, B.EXF_BF16, one, one, one, one, one, one, 1 << 20, None),
+         B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_dispatch(one, one, None, 4, 64, 1, 8, 65, B.EXF_BF16, one, one, one, one, one, one, 1 << 20, None),
+         B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_dispatch(one, None, None, 4, 64, 1, 8, 8, B.EXF_BF16, one, one, one, one, one, one, 1 << 20, None),
+         B.EXF_ERR_NULL_PTR),
+        (lambda: lib.moe_expert_ffn(one, one, one, None, one, None, 4, 96, 256, 8, 0, B.EXF_BF16, one, one, 1 << 20, None),
+         B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_expert_ffn(one, one, one, None, one, None, 4, 64, 256, 8, 5, B.EXF_BF16, one, one, 1 << 20, None),
+         B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_expert_ffn(one, one, one, None, one, None, 4, 64, 256, 8, 0, B.EXF_BF16, one, one, 16, None),
+         B.EXF_ERR_WORKSPACE_TOO_SMALL),
+        (lambda: lib.moe_expert_ffn(one, None, one, None, one, None, 4, 64, 256, 8, 0, B.EXF_F32, one, one, 1 << 20, None),
+         B.EXF_ERR_NULL_PTR),
+        (lambda: lib.moe_combine(one, one, one, 4, 64, 3, B.EXF_BF16, one, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_combine(one, one, one, 4, 63, 1, B.EXF_F32, one, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_combine(one, one, None, 4, 64, 1, B.EXF_F32, one, None), B.EXF_ERR_NULL_PTR),
+        (lambda: lib.affinity_histogram(one, 0, 8, 4, one, None, None, None, one, 1 << 20, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.affinity_histogram(one, 3, 8, 65, one, None, None, None, one, 1 << 20, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.affinity_histogram(one, 3, 8, 4, None, None, None, None, one, 1 << 20, None), B.EXF_ERR_NULL_PTR),
+        (lambda: lib.affinity_histogram(one, 3, 8, 4, one, None, None, None, one, 8, None), B.EXF_ERR_WORKSPACE_TOO_SMALL),
+        (lambda: lib.placement_locality(one, None, 3, 8, 4, 2, one, one, 1 << 20, None), B.EXF_ERR_NULL_PTR),
+        (lambda: lib.placement_locality(one, one, 3, 8, 4, 0, one, one, 1 << 20, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.placement_locality(one, one, 3, 8, 4, 2, one, one, 0, None), B.EXF_ERR_WORKSPACE_TOO_SMALL),
+    ]
+    for i, (call, expect) in enumerate(cases):
+        rc = call()
+        assert rc == expect, (i, rc, exf.last_error())
+        assert exf.last_error() != ""
+
+
+def test_empty_inputs_are_ok_without_a_gpu():
+    lib = exf.lib()
+    one = ctypes.c_void_p(4096)
+    assert lib.moe_gate_topk(None, None, 0, 64, 8, 1, 0, B.EXF_BF16, None, None, None, None) == B.EXF_OK
+    assert lib.moe_topk_from_logits(None, 0, 8, 1, 0, None, None, None) == B.EXF_OK
+    assert lib.moe_expert_ffn(None, None, None, None, None, None, 0, 64, 256, 8, 0, B.EXF_BF16, None, None, 0, None) == B.EXF_OK
+    assert lib.moe_combine(None, None, None, 0, 64, 1, B.EXF_BF16, None, None) == B.EXF_OK
+    assert lib.placement_locality(None, None, 1, 100, 8, 2, None, one, 0, None) == B.EXF_OK  # L = 1: no pair
+
+
+def test_workspace_sizes():
+    lib = exf.lib()
+    assert lib.moe_dispatch_workspace_bytes(0, 1, 8) >= 32
+    assert lib.moe_dispatch_workspace_bytes(32768, 1, 8) % 256 == 0
+    assert lib.moe_expert_ffn_workspace_bytes(8192, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2
+    assert lib.moe_expert_ffn_workspace_bytes(512, 64, 256, 8, B.EXF_F32) == 512 * 256 * 4
+    ws = lib.affinity_histogram_workspace_bytes(24, 1 << 20, 64)
+    assert 0 < ws < 64 << 20  # partial histograms stay far below the 100 MB trace
+    assert lib.placement_locality_workspace_bytes(24, 1 << 20) > 0
+
+
+def test_check_placement_constraints():
+    import synth_inputs as syn
+
+    pl = torch.from_numpy(syn.balanced_random_placement(6, 16, 4, seed=9))
+    assert exf.check_placement(pl, 4)
+    bad = pl.clone()
+    bad[2, 0] = (bad[2, 0] + 1) % 4  # one device now holds 5 experts, another 3
+    assert not exf.check_placement(bad, 4)
+    bad = pl.clone()
+    bad[0, 0] = 7
+    assert not exf.check_placement(bad, 4)
+    assert "device" in exf.last_error()

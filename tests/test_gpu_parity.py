@@ -1,0 +1,325 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element, at
+sizes that span several tiles and a ragged tail, plus the edge cases of each step."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2401_08383_amd as exf
+import synth_inputs as syn
+from helpers import (DEV, GATE_TOL, OUT_RTOL, assert_close_max, assert_gate_close, check_routing_against_fp64, dev_i32,
+                     expected_dispatch_compare, to_dev, to_host)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ----------------------------------------------------------------------------- top-k from logits
+@pytest.mark.parametrize("T,E,k,renorm", [(1, 1, 1, 0), (777, 8, 1, 0), (1000, 64, 2, 1), (513, 33, 2, 0), (4096, 32, 1, 0)])
+def test_topk_from_logits_bit_exact(oracle, T, E, k, renorm):
+    _say(f"topk_from_logits T={T} E={E} k={k} renorm={renorm}")
+    g = syn.rng(100 + T)
+    logits = g.standard_normal((T, E), dtype=np.float32)
+    logits[::3] = np.round(logits[::3])  # many exact ties: the lowest id must win
+    idx_ref, w_ref = oracle.topk(logits.astype(np.float64), k, renorm)
+    idx, w = exf.moe_topk_from_logits(torch.from_numpy(logits).to(DEV), k, renorm)
+    np.testing.assert_array_equal(idx.cpu().numpy(), idx_ref)
+    assert_gate_close(w.cpu().numpy(), w_ref, 1e-6, "topk weights")
+
+
+# ----------------------------------------------------------------------------- gate
+GATE_CASES = [
+    ("f32", 512, 64, 8, 1, 0), ("f32", 100, 100, 5, 2, 1),
+    ("bf16", 512, 64, 8, 1, 0), ("bf16", 1000, 1024, 8, 1, 0), ("bf16", 300, 200, 17, 2, 1),
+    ("bf16", 2500, 512, 32, 1, 0), ("bf16", 999, 1024, 64, 2, 1), ("bf16", 16, 4096, 64, 2, 1),
+    ("bf16", 33000, 256, 48, 2, 0), ("bf16", 16500, 128, 64, 1, 0),
+]
+
+
+@pytest.mark.parametrize("dtype,T,d,E,k,renorm", GATE_CASES)
+def test_gate_topk_parity(oracle, dtype, T, d, E, k, renorm):
+    _say(f"gate {dtype} T={T} d={d} E={E} k={k} renorm={renorm}")
+    g = syn.rng(200 + T + E)
+    x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), dtype)
+    wg = syn.quantize(g.standard_normal((E, d), dtype=np.float32) * np.float32(1.0 / np.sqrt(d)), dtype)
+    idx, w, logits = exf.moe_gate_topk(to_dev(x, dtype), to_dev(wg, dtype), k, renorm, want_logits=True)
+    idx, w, logits = idx.cpu().numpy(), w.cpu().numpy(), logits.cpu().numpy()
+    logits64 = oracle.gate_logits(x, wg)
+    assert_gate_close(logits, logits64, GATE_TOL[dtype], "logits")
+    # the decision in the kernel's own precision: oracle selection on the GPU's fp32 logits
+    idx_k, w_k = oracle.topk(logits.astype(np.float64), k, renorm)
+    np.testing.assert_array_equal(idx, idx_k)
+    assert_gate_close(w, w_k, 1e-6, "weights vs own logits")
+    # end to end against fp64 logits
+    n_amb = check_routing_against_fp64(idx, logits64, k, GATE_TOL[dtype])
+    assert n_amb <= max(3, T // 500)
+    _, w64 = oracle.topk(logits64, k, renorm)
+    clear = (idx == oracle.topk(logits64, k, renorm)[0]).all(axis=1)
+    assert_gate_close(w[clear], w64[clear], GATE_TOL[dtype], "weights")
+    # without the optional logits output the routing is the same
+    idx2, w2, none = exf.moe_gate_topk(to_dev(x, dtype), to_dev(wg, dtype), k, renorm, want_logits=False)
+    assert none is None
+    np.testing.assert_array_equal(idx2.cpu().numpy(), idx)
+    np.testing.assert_array_equal(w2.cpu().numpy(), w)
+
+
+def test_gate_all_equal_logits_pick_lowest_ids():
+    x = torch.zeros((64, 128), dtype=torch.bfloat16, device=DEV)
+    wg = torch.ones((32, 128), dtype=torch.bfloat16, device=DEV)
+    idx, w, _ = exf.moe_gate_topk(x, wg, 2, True)
+    assert (idx.cpu().numpy() == np.array([0, 1])).all()
+    assert (w.cpu().numpy() == 0.5).all()
+    idx, w, _ = exf.moe_gate_topk(x, wg, 1, False)
+    assert (idx.cpu().numpy() == 0).all() and (w.cpu().numpy() == np.float32(1 / 32)).all()
+
+
+# ----------------------------------------------------------------------------- dispatch
+def _run_dispatch(oracle, x, idx, E, E_local, expert_map, dtype):
+    T, k = idx.shape
+    ref = oracle.dispatch(idx, expert_map, E, E_local)
+    res = exf.moe_dispatch(to_dev(x, dtype), dev_i32(idx), E, E_local, None if expert_map is None else dev_i32(expert_map))
+    expected_dispatch_compare(res, ref, T * k)
+    kept = ref["kept"]
+    xs = to_host(res.x_sorted)[:kept]
+    np.testing.assert_array_equal(xs, x[ref["src_of_sorted"] // k])  # a pure copy: bit-exact
+    return res, ref
+
+
+@pytest.mark.parametrize("dtype,T,d,k,E", [("f32", 512, 64, 1, 8), ("bf16", 1, 64, 1, 8), ("bf16", 1023, 128, 1, 8),
+                                           ("bf16", 5000, 256, 2, 64), ("bf16", 3333, 64, 1, 32), ("f32", 2049, 32, 2, 5)])
+def test_dispatch_parity(oracle, dtype, T, d, k, E):
+    _say(f"dispatch {dtype} T={T} d={d} k={k} E={E}")
+    g = syn.rng(300 + T)
+    x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), dtype)
+    idx = g.integers(0, E, size=(T, k)).astype(np.int32)
+    _run_dispatch(oracle, x, idx, E, E, None, dtype)
+
+
+def test_dispatch_expert_map_invalid_and_degenerate(oracle):
+    g = syn.rng(310)
+    T, d, E, E_local = 4000, 64, 64, 8
+    x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), "bf16")
+    expert_map = np.full(E, -1, dtype=np.int32)
+    resident = g.permutation(E)[:E_local]
+    expert_map[resident] = np.arange(E_local)
+    idx = g.integers(0, E, size=(T, 1)).astype(np.int32)  # 7/8 of the tokens are not local
+    idx[3] = -1
+    idx[1999] = E
+    idx[2000] = 1 << 30
+    res, ref = _run_dispatch(oracle, x, idx, E, E_local, expert_map, "bf16")
+    assert ref["n_invalid"] == 3 and ref["kept"] < T // 4
+    # everything to one expert: identity permutation
+    idx = np.full((1500, 2), 5, dtype=np.int32)
+    x = syn.quantize(g.standard_normal((1500, 64), dtype=np.float32), "bf16")
+    res, ref = _run_dispatch(oracle, x, idx, 8, 8, None, "bf16")
+    np.testing.assert_array_equal(res.src_of_sorted.cpu().numpy(), np.arange(3000))
+    # nothing local at all
+    res, ref = _run_dispatch(oracle, x, idx, 8, 8, np.full(8, -1, dtype=np.int32), "bf16")
+    assert ref["kept"] == 0 and (res.sorted_of_src.cpu().numpy() == -1).all()
+    # skewed (Zipf) loads
+    tr, _ = syn.planted_trace(1, 6000, 32, 0.0, seed=311, marginal="zipf")
+    x = syn.quantize(g.standard_normal((6000, 64), dtype=np.float32), "bf16")
+    _run_dispatch(oracle, x, tr[0].reshape(-1, 1).copy(), 32, 32, None, "bf16")
+
+
+def test_dispatch_empty_batch():
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
+    idx = torch.empty((0, 1), dtype=torch.int32, device=DEV)
+    res = exf.moe_dispatch(x, idx, 8)
+    assert (res.expert_counts.cpu().numpy() == 0).all() and (res.expert_offsets.cpu().numpy() == 0).all()
+
+
+# ----------------------------------------------------------------------------- expert FFN
+def _ffn_case(oracle, dtype, counts, d, f, act, bias, seed, rows=None):
+    g = syn.rng(seed)
+    E = len(counts)
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    A = int(offsets[-1])
+    cap = A + 5  # buffers larger than the kept rows: the tail must stay untouched
+    xs = syn.quantize(g.standard_normal((cap, d), dtype=np.float32), dtype)
+    w1 = syn.quantize(g.standard_normal((E, f, d), dtype=np.float32) * np.float32(0.05), dtype)
+    w2 = syn.quantize(g.standard_normal((E, d, f), dtype=np.float32) * np.float32(0.05), dtype)
+    b1 = syn.quantize(g.standard_normal((E, f), dtype=np.float32) * np.float32(0.1), dtype) if bias else None
+    b2 = syn.quantize(g.standard_normal((E, d), dtype=np.float32) * np.float32(0.1), dtype) if bias else None
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    y = torch.full((cap, d), 7.0, dtype=tdt, device=DEV)
+    exf.moe_expert_ffn(to_dev(xs, dtype), dev_i32(offsets), to_dev(w1, dtype), to_dev(w2, dtype),
+                       None if b1 is None else to_dev(b1, dtype), None if b2 is None else to_dev(b2, dtype), act, out=y)
+    y = to_host(y)
+    assert (y[A:] == 7.0).all(), "rows beyond expert_offsets[E_local] were written"
+    rows = np.arange(A) if rows is None else rows
+    ref = oracle.expert_ffn_rows(xs, offsets, w1, b1, w2, b2, act, rows)
+    assert_close_max(y[rows], ref, OUT_RTOL[dtype], f"ffn {dtype}")
+
+
+@pytest.mark.parametrize("act", [0, 1])
+@pytest.mark.parametrize("bias", [False, True])
+def test_ffn_f32_parity(oracle, act, bias):
+    _say(f"ffn f32 act={act} bias={bias}")
+    _ffn_case(oracle, "f32", [70, 0, 129, 1, 64, 3], 64, 256, act, bias, seed=400 + act)
+    _ffn_case(oracle, "f32", [5], 36, 20, act, bias, seed=402)  # tiles with ragged N and K tails
+
+
+@pytest.mark.parametrize("act", [0, 1])
+@pytest.mark.parametrize("bias", [False, True])
+def test_ffn_bf16_parity(oracle, act, bias):
+    _say(f"ffn bf16 act={act} bias={bias}")
+    _ffn_case(oracle, "bf16", [130, 0, 257, 1, 128, 31], 128, 320, act, bias, seed=410 + act)
+    _ffn_case(oracle, "bf16", [300], 64, 64, act, bias, seed=412)
+
+
+def test_ffn_bf16_many_experts_skewed(oracle):
+    _say("ffn bf16 skewed 32 experts")
+    tr, _ = syn.planted_trace(1, 3000, 32, 0.0, seed=420, marginal="zipf")
+    counts = np.bincount(tr[0], minlength=32)
+    _ffn_case(oracle, "bf16", counts.tolist(), 256, 512, 0, False, seed=421)
+
+
+def test_ffn_identity_expert_returns_input(oracle):
+    # gelu(z) - gelu(-z) = z: W1 = [I; -I], W2 = [I, -I] makes every expert the identity
+    d, f = 64, 128
+    w1 = np.zeros((2, f, d), dtype=np.float32)
+    w2 = np.zeros((2, d, f), dtype=np.float32)
+    for e in range(2):
+        w1[e, :d], w1[e, d:] = np.eye(d), -np.eye(d)
+        w2[e, :, :d], w2[e, :, d:] = np.eye(d), -np.eye(d)
+    xs = syn.quantize(syn.rng(430).standard_normal((200, d), dtype=np.float32), "bf16")
+    off = dev_i32(np.array([0, 77, 200]))
+    y = to_host(exf.moe_expert_ffn(to_dev(xs, "bf16"), off, to_dev(w1, "bf16"), to_dev(w2, "bf16")))
+    assert_close_max(y, xs, 2e-2, "identity expert")
+
+
+# ----------------------------------------------------------------------------- combine
+@pytest.mark.parametrize("dtype,T,d,k", [("f32", 512, 64, 1), ("bf16", 1000, 128, 1), ("bf16", 777, 256, 2), ("f32", 50, 36, 2)])
+def test_combine_parity(oracle, dtype, T, d, k):
+    _say(f"combine {dtype} T={T} d={d} k={k}")
+    g = syn.rng(500 + T)
+    A = T * k
+    y = syn.quantize(g.standard_normal((A, d), dtype=np.float32), dtype)
+    inv = g.permutation(A).astype(np.int32)
+    inv[g.random(A) < 0.1] = -1  # some assignments are not local
+    w = g.random((T, k), dtype=np.float32)
+    out = exf.moe_combine(to_dev(y, dtype), dev_i32(inv), torch.from_numpy(w).to(DEV))
+    ref = oracle.combine(y, inv, w)
+    got = to_host(out)
+    # one rounding to the storage type on top of an fp32 accumulation of k terms: the error is
+    # bounded relative to sum_j |w_j y_j| (the terms may cancel)
+    mag = oracle.combine(np.abs(y), inv, np.abs(w))
+    eps = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -22
+    assert (np.abs(got - ref) <= eps * mag + 1e-30).all()
+
+
+# ----------------------------------------------------------------------------- whole layer, small
+@pytest.mark.parametrize("cfg_id,dtype,T,d,f,E,k,renorm", [(1, "f32", 512, 64, 256, 8, 1, False), (0, "bf16", 700, 128, 256, 8, 2, True)])
+def test_layer_small_end_to_end(oracle, cfg_id, dtype, T, d, f, E, k, renorm):
+    _say(f"layer end-to-end {dtype} T={T} d={d} f={f} E={E} k={k}")
+    if cfg_id == 1:
+        cfg = syn.CONFIGS[1]
+        x, wg = syn.tokens(cfg), syn.gate_weight(cfg)
+        w1, w2 = syn.expert_weights(cfg)
+    else:
+        g = syn.rng(600)
+        x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), dtype)
+        wg = syn.quantize(g.standard_normal((E, d), dtype=np.float32) * np.float32(0.1), dtype)
+        w1 = syn.quantize(g.standard_normal((E, f, d), dtype=np.float32) * np.float32(0.05), dtype)
+        w2 = syn.quantize(g.standard_normal((E, d, f), dtype=np.float32) * np.float32(0.05), dtype)
+    xd = to_dev(x, dtype)
+    idx, w, logits = exf.moe_gate_topk(xd, to_dev(wg, dtype), k, renorm, want_logits=True)
+    disp = exf.moe_dispatch(xd, idx, E)
+    y = exf.moe_expert_ffn(disp.x_sorted, disp.expert_offsets, to_dev(w1, dtype), to_dev(w2, dtype))
+    out = exf.moe_combine(y, disp.sorted_of_src, w)
+    # oracle chain, fed with the GPU's own routing decision so that a near-tie cannot cascade
+    idx_h = idx.cpu().numpy()
+    logits64 = oracle.gate_logits(x, wg)
+    check_routing_against_fp64(idx_h, logits64, k, GATE_TOL[dtype])
+    p = oracle.softmax(logits64)
+    w_ref = np.take_along_axis(p, idx_h.astype(np.int64), axis=1)
+    if renorm and k > 1:
+        w_ref = w_ref / w_ref.sum(axis=1, keepdims=True)
+    assert_gate_close(w.cpu().numpy(), w_ref, GATE_TOL[dtype], "gate weights")
+    ref_d = oracle.dispatch(idx_h, None, E, E)
+    expected_dispatch_compare(disp, ref_d, T * k)
+    xs_ref = oracle.gather_rows(x, ref_d["src_of_sorted"], k)
+    y_ref = oracle.expert_ffn(xs_ref, ref_d["offsets"], w1, None, w2, None, 0)
+    assert_close_max(to_host(y)[: ref_d["kept"]], y_ref, OUT_RTOL[dtype], "y_sorted")
+    out_ref = oracle.combine(y_ref, ref_d["sorted_of_src"], w_ref)
+    assert_close_max(to_host(out), out_ref, OUT_RTOL[dtype], "layer output")
+
+
+# ----------------------------------------------------------------------------- affinity / locality
+def _affinity_case(oracle, trace, E, placement=None, G=1):
+    L, N = trace.shape
+    res = exf.affinity_histogram(dev_i32(trace).reshape(L, N), E)
+    counts, loads, n_inv = oracle.affinity_counts(trace, E)
+    np.testing.assert_array_equal(res["counts"].cpu().numpy(), counts)
+    np.testing.assert_array_equal(res["loads"].cpu().numpy(), loads)
+    assert int(res["n_invalid"].cpu()) == n_inv
+    prob = oracle.cond_prob(counts).astype(np.float32)
+    got = res["cond_prob"].cpu().numpy()
+    assert (np.abs(got - prob) <= np.spacing(prob)).all()  # <= 1 ulp
+    if placement is not None and L > 1:
+        loc = exf.placement_locality(dev_i32(trace).reshape(L, N), dev_i32(placement), G)
+        np.testing.assert_array_equal(loc.cpu().numpy(), oracle.placement_locality(trace, placement))
+
+
+@pytest.mark.parametrize("L,N,E,G", [(2, 512, 8, 4), (12, 8192, 8, 4), (12, 16384, 32, 8), (5, 100001, 64, 8), (3, 70003, 16, 2),
+                                     (2, 1, 1, 1), (7, 40000, 33, 3), (24, 131072, 64, 8)])
+def test_affinity_and_locality_parity(oracle, L, N, E, G):
+    _say(f"affinity L={L} N={N} E={E} G={G}")
+    trace, perms = syn.planted_trace(L, N, E, 0.7, seed=700 + L + E, marginal="zipf" if E == 32 else "uniform")
+    if E % G == 0:
+        pl = syn.balanced_random_placement(L, E, G, seed=701)
+    else:
+        pl = syn.rng(702).integers(0, G, size=(L, E)).astype(np.int32)
+    _affinity_case(oracle, trace, E, pl, G)
+
+
+def test_affinity_invalid_ids_and_degenerate(oracle):
+    _say("affinity invalid ids / degenerate shapes")
+    L, N, E = 6, 30000, 16
+    trace, _ = syn.planted_trace(L, N, E, 0.5, seed=710)
+    g = syn.rng(711)
+    bad = g.random((L, N)) < 0.01
+    trace[bad] = g.choice(np.array([-1, E, 1 << 20, -(1 << 31)]), size=int(bad.sum())).astype(np.int32)
+    pl = syn.balanced_random_placement(L, E, 4, seed=712)
+    _affinity_case(oracle, trace, E, pl, 4)
+    # a single layer: loads only
+    t1, _ = syn.planted_trace(1, 5000, 8, 0.0, seed=713)
+    t1[0, 17] = 99
+    _affinity_case(oracle, t1, 8)
+    # no tokens
+    res = exf.affinity_histogram(torch.empty((4, 0), dtype=torch.int32, device=DEV), 8)
+    assert (res["counts"].cpu().numpy() == 0).all() and (res["loads"].cpu().numpy() == 0).all()
+    assert (res["cond_prob"].cpu().numpy() == 0).all() and int(res["n_invalid"].cpu()) == 0
+    loc = exf.placement_locality(torch.empty((4, 0), dtype=torch.int32, device=DEV), dev_i32(np.zeros((4, 8))), 1)
+    assert (loc.cpu().numpy() == 0).all()
+    # deterministic routing: one hot column per row, and an aligned placement keeps every token local
+    tr, perms = syn.planted_trace(5, 9999, 8, 1.0, seed=714)
+    pl = syn.aligned_placement(perms, 8, 4)
+    loc = exf.placement_locality(dev_i32(tr).reshape(5, 9999), dev_i32(pl), 4)
+    assert (loc.cpu().numpy() == 9999).all()
+    _affinity_case(oracle, tr, 8, pl, 4)
+
+
+def test_locality_paper_worked_example_on_gpu():
+    # the 3-layer MoE-8 walk-through: default placement gpu = e // 2 keeps 2 of 4 transitions local
+    trace = np.array([[0, 5], [4, 5], [2, 4]], dtype=np.int32)
+    pl = syn.contiguous_placement(3, 8, 4)
+    loc = exf.placement_locality(dev_i32(trace), dev_i32(pl), 4).cpu().numpy()
+    assert loc.sum() == 2 and loc.tolist() == [1, 1]
+    assert exf.check_placement(torch.from_numpy(pl), 4)
+
+
+def test_repeat_calls_are_deterministic():
+    trace, _ = syn.planted_trace(6, 50000, 64, 0.7, seed=720)
+    t = dev_i32(trace).reshape(6, 50000)
+    a = exf.affinity_histogram(t, 64)
+    b = exf.affinity_histogram(t, 64)
+    assert torch.equal(a["counts"], b["counts"]) and torch.equal(a["cond_prob"], b["cond_prob"])
+    idx = dev_i32(trace[0].reshape(-1, 1).copy())
+    x = torch.randn((50000, 64), device=DEV).to(torch.bfloat16)
+    r1 = exf.moe_dispatch(x, idx, 64)
+    r2 = exf.moe_dispatch(x, idx, 64)
+    assert torch.equal(r1.src_of_sorted, r2.src_of_sorted) and torch.equal(r1.x_sorted, r2.x_sorted)
