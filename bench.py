@@ -1,0 +1,288 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch of the GPT-MoE-350M-shaped
+configuration (d_model 1024, d_ff 4096, 8 experts, top-1, 8192 tokens, bf16, fp32 accumulation):
+gate+top-k -> dispatch -> grouped expert FFN -> combine, then affinity_histogram and
+placement_locality over the configuration's 12-layer x 8192-token routing trace.
+Inputs are resident in HBM before the timed region; no allocation happens inside it.
+
+Prints ONE JSON line: tokens/s of the whole step, the roofline of the dominant kernel (the
+grouped expert GEMM, measured with HIP events on the launch stream), per-entry-point timings,
+HBM-bound entry points at the larger shapes of the one-GPU-share configuration, achieved copy
+and MFMA rates of the box, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+# HBM bytes per moe_expert_ffn call at the benchmark configuration, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs scaled by the copy-kernel calibration (see profiles/); None
+# until measured.
+FFN_TRAFFIC_BYTES = None
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def _time_call(fn, iters, warmup=3):
+    """Average milliseconds of `fn` (enqueued on the current stream) over `iters` launches."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    a, b = _events(2)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def _time_rotating(make_fn, n_sets, iters):
+    """Like _time_call, but cycles over `n_sets` distinct buffer sets so that neither L2 nor the
+    256 MB Infinity Cache can serve the reads."""
+    import torch
+    fns = [make_fn(i) for i in range(n_sets)]
+    for f in fns:
+        f()
+    a, b = _events(2)
+    torch.cuda.synchronize()
+    a.record()
+    for i in range(iters):
+        fns[i % n_sets]()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def cpu_baseline(cfg, x, wg, w1, w2, trace, placement, sample_rows_per_expert=96):
+    """The CPU oracle as it stands, timed on this host: every step in full except the expert
+    FFN, which runs on a sample of rows of every expert and is extrapolated linearly."""
+    import oracle
+    oracle.build()
+    t = {}
+    t0 = time.perf_counter()
+    logits = oracle.gate_logits(x, wg)
+    idx, w = oracle.topk(logits, cfg.k, cfg.renormalize)
+    t["gate"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    disp = oracle.dispatch(idx, None, cfg.E, cfg.E_local)
+    xs = oracle.gather_rows(x, disp["src_of_sorted"], cfg.k)
+    t["dispatch"] = time.perf_counter() - t0
+    rows = []
+    for e in range(cfg.E_local):
+        lo, hi = int(disp["offsets"][e]), int(disp["offsets"][e + 1])
+        rows.extend(range(lo, min(hi, lo + sample_rows_per_expert)))
+    rows = np.array(rows, dtype=np.int64)
+    t0 = time.perf_counter()
+    y = oracle.expert_ffn_rows(xs, disp["offsets"], w1, None, w2, None, 0, rows)
+    t_ffn_sample = time.perf_counter() - t0
+    t["ffn"] = t_ffn_sample * (disp["kept"] / max(len(rows), 1))
+    y_full = np.zeros((disp["kept"], cfg.d))
+    y_full[rows] = y
+    t0 = time.perf_counter()
+    oracle.combine(y_full, disp["sorted_of_src"], w)
+    t["combine"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    counts, loads, _ = oracle.affinity_counts(trace, cfg.trace_E)
+    oracle.cond_prob(counts)
+    t["affinity"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.placement_locality(trace, placement)
+    t["locality"] = time.perf_counter() - t0
+    total = sum(t.values())
+    return {
+        "value": cfg.T / total,
+        "unit": "tokens/s",
+        "cores": oracle.threads(),
+        "kind": "oracle",
+        "sample": f"expert FFN on {len(rows)} of {disp['kept']} rows ({sample_rows_per_expert} per expert, measured "
+                  f"{t_ffn_sample:.2f} s, extrapolated linearly); gate, dispatch, combine, affinity, locality in full",
+        "seconds_per_step_extrapolated": total,
+        "seconds": {k: round(v, 4) for k, v in t.items()},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel and large-shape measurements")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives, no sharding)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth_inputs as syn
+    from paper_2401_08383_amd import binding as B
+    from paper_2401_08383_amd.pipeline import AffinityRun, MoELayerRun
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    lib = B.lib()
+
+    cfg = syn.CONFIGS[2]
+    x_h, wg_h = syn.tokens(cfg), syn.gate_weight(cfg)
+    w1_h, w2_h = syn.expert_weights(cfg)
+    trace_h, _ = syn.config_trace(cfg)
+    pl_h = syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(cfg.index, 5))
+
+    def dev_bf16(a):
+        return torch.from_numpy(a).to(torch.bfloat16).to(dev)
+
+    layer = MoELayerRun(dev_bf16(x_h), dev_bf16(wg_h), dev_bf16(w1_h), dev_bf16(w2_h), cfg.k, cfg.renormalize)
+    aff = AffinityRun(torch.from_numpy(trace_h).to(dev), torch.from_numpy(pl_h).to(dev), cfg.trace_E, cfg.G)
+
+    def step():
+        layer.step()
+        aff.step()
+
+    for _ in range(args.warmup):
+        step()
+    ffn_ev = [_events(2) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        layer.gate()
+        layer.dispatch()
+        ffn_ev[i][0].record()
+        layer.ffn()
+        ffn_ev[i][1].record()
+        layer.combine()
+        aff.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    ffn_ms = float(np.mean([a.elapsed_time(b) for a, b in ffn_ev]))
+
+    A = cfg.T * cfg.k
+    ffn_flops = 4.0 * A * cfg.d * cfg.f
+    achieved = ffn_flops / (ffn_ms * 1e-3) / 1e12
+    result = {
+        "metric": "MoE-layer tokens/s (gate+dispatch+expert FFN+combine+affinity statistic per step)",
+        "value": cfg.T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1] GPT-MoE-350M-shaped: d_model=1024 d_ff=4096 E=8 top-1 T=8192 bf16; "
+                               "affinity on a 12-layer x 8192-token trace, placement G=4",
+                   "tokens": cfg.T, "d_model": cfg.d, "d_ff": cfg.f, "experts": cfg.E, "top_k": cfg.k,
+                   "trace_layers": cfg.trace_L, "trace_tokens": cfg.trace_N},
+        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel (moe_expert_ffn: both contractions)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": FFN_TRAFFIC_BYTES, "ms_per_launch": ffn_ms, "flops_per_launch": ffn_flops},
+    }
+
+    if not args.no_extra:
+        # per-entry-point averages at the benchmark configuration
+        per = {}
+        per["gate_ms"] = _time_call(layer.gate, 50)
+        per["dispatch_ms"] = _time_call(layer.dispatch, 50)
+        per["ffn_ms"] = _time_call(layer.ffn, 30)
+        per["combine_ms"] = _time_call(layer.combine, 50)
+        per["affinity_histogram_ms"] = _time_call(aff.histogram, 50)
+        per["placement_locality_ms"] = _time_call(aff.locality, 50)
+        layer_ms = per["gate_ms"] + per["dispatch_ms"] + per["ffn_ms"] + per["combine_ms"]
+        per["layer_tokens_per_s"] = cfg.T / (layer_ms * 1e-3)
+        result["per_call"] = per
+
+        # achieved rates of this machine
+        nbytes = 1 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        ms = _time_call(lambda: lib.exf_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, B._stream()), 20)
+        copy_gbs = 2 * nbytes / (ms * 1e-3) / 1e9
+        del src, dst
+        wgs, iters = 256 * 8, 2000
+        sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+        ms = _time_call(lambda: lib.exf_probe_mfma(wgs, iters, sink.data_ptr(), B._stream()), 5)
+        mfma_tflops = wgs * 4 * 4 * iters * 32768.0 / (ms * 1e-3) / 1e12
+        result["box"] = {"copy_GBps": copy_gbs, "mfma_loop_TFLOPs": mfma_tflops}
+        result["roofline"]["frac_of_measured_mfma_loop"] = achieved / mfma_tflops
+
+        # HBM-bound entry points at the shapes of the one-GPU-share configuration (rotating buffers)
+        c4 = syn.CONFIGS[4]
+        hbm = {}
+        T4, d4 = c4.T, c4.d
+        sets = 5  # 5 x (67 MB in + 67 MB out) > 256 MB
+        xs4 = [torch.randn((T4, d4), device=dev).to(torch.bfloat16) for _ in range(sets)]
+        idx4_h, map4_h = syn.local_routing(c4, syn.seed_for(4, 4, 1))
+        idx4 = torch.from_numpy(idx4_h).to(dev)
+        map4 = torch.from_numpy(map4_h).to(dev)
+        outs = [B.moe_dispatch(xs4[i], idx4, c4.E, c4.E_local, map4) for i in range(sets)]
+        ws = torch.empty(max(lib.moe_dispatch_workspace_bytes(T4, 1, c4.E_local), 256), dtype=torch.uint8, device=dev)
+        ms = _time_rotating(lambda i: (lambda: B.moe_dispatch(xs4[i], idx4, c4.E, c4.E_local, map4, out=outs[i], workspace=ws)),
+                            sets, 40)
+        bytes_disp = T4 * d4 * 2 * 2 + T4 * 16
+        hbm["dispatch"] = {"ms": ms, "GBps": bytes_disp / (ms * 1e-3) / 1e9, "frac": bytes_disp / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                           "bytes": bytes_disp}
+        w4 = torch.rand((T4, 1), device=dev)
+        couts = [torch.empty((T4, d4), dtype=torch.bfloat16, device=dev) for _ in range(sets)]
+        ms = _time_rotating(lambda i: (lambda: B.moe_combine(outs[i].x_sorted, outs[i].sorted_of_src, w4, out=couts[i])), sets, 40)
+        bytes_comb = T4 * d4 * 2 * 2 + T4 * 12
+        hbm["combine"] = {"ms": ms, "GBps": bytes_comb / (ms * 1e-3) / 1e9, "frac": bytes_comb / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                          "bytes": bytes_comb}
+        gw4 = torch.randn((c4.E, d4), device=dev).to(torch.bfloat16)
+        gi = torch.empty((T4, 1), dtype=torch.int32, device=dev)
+        gwt = torch.empty((T4, 1), dtype=torch.float32, device=dev)
+        ms = _time_rotating(lambda i: (lambda: lib.moe_gate_topk(xs4[i].data_ptr(), gw4.data_ptr(), T4, d4, c4.E, 1, 0, B.EXF_BF16,
+                                                                 None, gi.data_ptr(), gwt.data_ptr(), B._stream())), sets, 40)
+        bytes_gate = T4 * d4 * 2 + c4.E * d4 * 2 + T4 * 8
+        hbm["gate"] = {"ms": ms, "GBps": bytes_gate / (ms * 1e-3) / 1e9, "frac": bytes_gate / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                       "bytes": bytes_gate}
+        del xs4, outs, couts
+        tr4_h, _ = syn.config_trace(c4)
+        pl4 = torch.from_numpy(syn.balanced_random_placement(c4.trace_L, c4.trace_E, c4.G, syn.seed_for(4, 5))).to(dev)
+        tr_sets = 3  # 3 x 100.7 MB > 256 MB
+        base = torch.from_numpy(tr4_h).to(dev)
+        traces = [base] + [base.roll(shifts=7 * (i + 1), dims=1).contiguous() for i in range(tr_sets - 1)]
+        aff4 = AffinityRun(base, pl4, c4.trace_E, c4.G)
+        bytes_tr = 4 * c4.trace_L * c4.trace_N
+        ms = _time_rotating(lambda i: (lambda: aff4.histogram(traces[i])), tr_sets, 30)
+        hbm["affinity_histogram"] = {"ms": ms, "GBps": bytes_tr / (ms * 1e-3) / 1e9, "frac": bytes_tr / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                     "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
+        ms = _time_rotating(lambda i: (lambda: aff4.locality(traces[i])), tr_sets, 30)
+        hbm["placement_locality"] = {"ms": ms, "GBps": bytes_tr / (ms * 1e-3) / 1e9, "frac": bytes_tr / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                     "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
+        result["hbm_bound_calls_config4_shapes"] = hbm
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, x_h, wg_h, w1_h, w2_h, trace_h, pl_h)
+    else:
+        result["cpu_baseline"] = None
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

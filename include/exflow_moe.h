@@ -194,6 +194,18 @@ int placement_locality(const int32_t* trace, const int32_t* placement, int L, in
  * exclusivity constraints of the integer program); EXF_ERR_BAD_SHAPE otherwise. */
 int exf_check_placement(const int32_t* placement_host, int L, int E, int G);
 
+/* ---------------------------------------------------------------------------------------
+ * Measurement probes (no counterpart in the paper; used by the benchmark to report achieved
+ * rates next to the data-sheet peaks and to calibrate the profiler's HBM byte counters).
+ *   exf_probe_copy: dst[0..bytes) = src[0..bytes), a plain streaming copy; bytes % 16 == 0,
+ *                   both device pointers 16-byte aligned.
+ *   exf_probe_mfma: `workgroups` x 256 threads, every wavefront issues 4*iters independent
+ *                   32x32x16 bf16 MFMAs (4*iters*32768 flop per wavefront); out receives
+ *                   workgroups*256 floats (device) so that the loop cannot be removed.
+ * ------------------------------------------------------------------------------------- */
+int exf_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+int exf_probe_mfma(int workgroups, int iters, float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

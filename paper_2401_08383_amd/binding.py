@@ -45,6 +45,8 @@ SIGNATURES = {
     "affinity_histogram": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "placement_locality_workspace_bytes": (_sz, [_i, _i64]),
     "placement_locality": (_i, [_vp, _vp, _i, _i64, _i, _i, _vp, _vp, _sz, _vp]),
+    "exf_probe_copy": (_i, [_vp, _vp, _sz, _vp]),
+    "exf_probe_mfma": (_i, [_i, _i, _vp, _vp]),
 }
 
 _lib = None
