@@ -44,9 +44,16 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
     return static_cast<bf16_t>(u >> 16);
 }
 
+// Two floats -> two bf16 in one register (gfx950 has a packed round-to-nearest-even convert).
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_v;
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_v;
+    const f32x2_v f = {lo, hi};
+    const bf16x2_v b = __builtin_convertvector(f, bf16x2_v);
+    uint32_t u;
+    __builtin_memcpy(&u, &b, sizeof(u));
+    return u;
 }
 
 __device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & (kWave - 1); }

@@ -23,6 +23,7 @@
 //     panels in that XCD's L2.
 // fp32 kernel: LDS-tiled 64x64x16, 4x4 outputs per thread (tiny configuration; latency bound).
 #include <math.h>
+#include <stdlib.h>
 
 #include "common.hpp"
 
@@ -40,136 +41,203 @@ __device__ __forceinline__ float gelu_tanh_exact(float z)
     return 0.5f * z * (1.0f + tanhf(0.79788456080286535588f * (z + 0.044715f * z * z * z)));
 }
 
-// erf by the rational-exponential formula 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7),
-// enough for a result that is rounded to bf16 next.
+// bf16 path: z * Phi(z) with the normal CDF evaluated as a logistic function of an odd
+// polynomial,  Phi(z) ~ 1 / (1 + exp(-z (c0 + c1 z^2 + c2 z^4))),  coefficients fitted (minimax
+// on [-10,10]) to the exact erf form: max |error| of the GELU value is 2.6e-5, two orders of
+// magnitude below the bf16 rounding the result receives next.  z^2 is clamped where the logistic
+// has long saturated, so that the quartic term cannot turn the polynomial around.
 __device__ __forceinline__ float gelu_erf_fast(float z)
 {
-    const float x = fabsf(z) * 0.70710678118654752440f;
-    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    const float erfc_abs = p * t * __expf(-x * x);      // 1 - erf(|z|/sqrt2)
-    const float erf_signed = copysignf(1.0f - erfc_abs, z);
-    return 0.5f * z * (1.0f + erf_signed);
+    const float t = fminf(z * z, 60.0f);
+    float p = fmaf(-7.02902502e-4f, t, 7.40107343e-2f);
+    p = fmaf(p, t, 1.59501506f);
+    const float e = __expf(-z * p);
+    return z * __builtin_amdgcn_rcpf(1.0f + e);  // v_rcp_f32: 1 ulp
 }
 // z/2 (1 + tanh u) = z / (1 + exp(-2u))
 __device__ __forceinline__ float gelu_tanh_fast(float z)
 {
     const float u = 0.79788456080286535588f * (z + 0.044715f * z * z * z);
-    return z * __frcp_rn(1.0f + __expf(-2.0f * u));
+    return z * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
 }
 
 enum Epilogue { kEpiNone = 0, kEpiGeluErf = 1, kEpiGeluTanh = 2 };
 
+#ifdef EXF_TUNE_TIMING
+__device__ unsigned long long exf_tune_times[8 * 64];
+#define EXF_STAMP(slot)                                                                   \
+    do {                                                                                  \
+        if (blockIdx.x < 64 * 8 && (blockIdx.x % 8) == 0 && threadIdx.x == 0)             \
+            exf_tune_times[(blockIdx.x / 8) * 8 + (slot)] = clock64();                    \
+    } while (0)
+#else
+#define EXF_STAMP(slot) do { } while (0)
+#endif
+
 // ---------------------------------------------------------------------------- tile lookup
+// Rows of expert e are cut into "full" row tiles of MT rows and, for the remainder, "tail" row
+// tiles of kTailRows rows, so that a ragged remainder costs in proportion to its size instead of
+// a whole tile.  Tile order: all full tiles as (expert, column tile, row tile), then all tail
+// tiles in the same way; the cheap tail tiles therefore fill the last round of the launch.
+constexpr int kTailRows = 64;
+constexpr int kXcdChunk = 16;  // consecutive tiles handed to one XCD at a time
+
 struct Tile2D {
     int expert;
     int row_begin, row_end;
     int n_tile;
+    bool tail;
 };
 
-// Tiles ordered (expert, column tile, row tile); `idx` is the position in that order.
+// Workgroup id -> tile index.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
+// id % 8 is the XCD and id / 8 the position in that XCD's queue; chunks of kXcdChunk consecutive
+// tiles (which share an expert's activation rows and a few weight panels) go to the same XCD and
+// therefore meet in the same L2.
+__device__ __forceinline__ int tile_index_of_workgroup(int wg)
+{
+    const int xcd = wg % kXcdCount, slot = wg / kXcdCount;
+    return ((slot / kXcdChunk) * kXcdCount + xcd) * kXcdChunk + slot % kXcdChunk;
+}
+
 __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles, int max_rows,
-                                            int xcd, int slot, Tile2D& out)
+                                            int idx, Tile2D& out)
 {
     const int lane = lane_id();
     int lo = 0, hi = 0;
-    if (lane < E_local) {
+    if (lane < E_local) {  // clamped so that a corrupt offsets array can never index past the buffers
         lo = min(max(offsets[lane], 0), max_rows);
         hi = min(max(offsets[lane + 1], lo), max_rows);
     }
-    const int row_tiles = (hi - lo + mt - 1) / mt;
-    const int tiles = row_tiles * n_tiles;
-    const int incl = wave_inclusive_scan(tiles);
-    const int excl = incl - tiles;
-    const int total = __shfl(incl, kWave - 1, kWave);
-    const int per_xcd = (total + kXcdCount - 1) / kXcdCount;
-    const int idx = xcd * per_xcd + slot;
-    if (slot >= per_xcd || idx >= total) return false;
-    const unsigned long long m = __ballot(lane < E_local && idx >= excl && idx < incl);
+    const int cnt = hi - lo;
+    const int full_rt = cnt / mt;
+    const int tail_rt = (cnt - full_rt * mt + kTailRows - 1) / kTailRows;
+    const int full_incl = wave_inclusive_scan(full_rt * n_tiles);
+    const int tail_incl = wave_inclusive_scan(tail_rt * n_tiles);
+    const int total_full = __shfl(full_incl, kWave - 1, kWave);
+    const int total = total_full + __shfl(tail_incl, kWave - 1, kWave);
+    if (idx >= total) return false;
+    const bool tail = idx >= total_full;
+    const int j = tail ? idx - total_full : idx;
+    const int incl = tail ? tail_incl : full_incl;
+    const int rt = tail ? tail_rt : full_rt;
+    const int excl = incl - rt * n_tiles;
+    const unsigned long long m = __ballot(lane < E_local && j >= excl && j < incl);
     if (m == 0ull) return false;
     const int src = __ffsll(static_cast<long long>(m)) - 1;
     const int e_lo = __shfl(lo, src, kWave);
     const int e_hi = __shfl(hi, src, kWave);
-    const int e_rt = __shfl(row_tiles, src, kWave);
-    const int r = idx - __shfl(excl, src, kWave);
-    out.expert = src;
-    out.n_tile = r / e_rt;
-    out.row_begin = e_lo + (r % e_rt) * mt;
-    out.row_end = min(out.row_begin + mt, e_hi);
+    const int e_rt = __shfl(rt, src, kWave);
+    const int e_full = __shfl(full_rt, src, kWave);
+    const int r = j - __shfl(excl, src, kWave);
+    const int row_tile = r % e_rt;
+    const int begin = tail ? e_lo + e_full * mt + row_tile * kTailRows : e_lo + row_tile * mt;
+    // every lane holds the same values; readfirstlane tells the compiler so (scalar registers)
+    out.expert = __builtin_amdgcn_readfirstlane(src);
+    out.n_tile = __builtin_amdgcn_readfirstlane(r / e_rt);
+    out.row_begin = __builtin_amdgcn_readfirstlane(begin);
+    out.row_end = __builtin_amdgcn_readfirstlane(min(begin + (tail ? kTailRows : mt), e_hi));
+    out.tail = tail;
     return true;
 }
 
 // ---------------------------------------------------------------------------- bf16 MFMA kernel
+// XOR swizzle of the 16-byte chunk index inside a tile row, chosen so that the lanes of one
+// ds_read_b128 (consecutive rows, same logical chunk) fall on distinct banks.
+//   SWZ 0: 128-byte rows -> row & 7;        64-byte rows -> (row >> 1) & 3
+//   SWZ 1: 128-byte rows -> (row >> 1) & 7  (16 consecutive rows distinct over 64 banks)
+template <int KT, int SWZ>
+__device__ __forceinline__ int chunk_swizzle(int row)
+{
+    if constexpr (KT == 64) return SWZ == 1 ? ((row >> 1) & 7) : (row & 7);
+    return (row >> 1) & 3;
+}
+
+// A pointer that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    return reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// One wavefront-wide direct-to-LDS load: lane i fetches 16 bytes at base + voff and they land at
+// LDS byte address lds_addr + 16*i (M0 carries the wavefront-uniform LDS address).  Issued as
+// inline assembly on purpose: the compiler then keeps exact lgkmcnt waits for the ds_read
+// operand fetches, and the landing of these loads is awaited explicitly with wait_vmcnt.
+__device__ __forceinline__ void lds_dma_16B(const unsigned char* base, uint32_t voff, uint32_t lds_addr)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" : : "v"(voff), "s"(base), "s"(lds_addr) : "memory");
+#else
+    (void)base; (void)voff; (void)lds_addr;
+#endif
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+#if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+#endif
 }
 
-template <int MT, int NT, int KT, int STAGES, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_bf16_kernel(const bf16_t* __restrict__ act,     // [A,K]
-                                                                         const int32_t* __restrict__ offsets,
-                                                                         const bf16_t* __restrict__ weight,  // [E_local,N,K]
-                                                                         const bf16_t* __restrict__ bias,    // [E_local,N] or null
-                                                                         int max_rows, int K, int N, int E_local,
-                                                                         bf16_t* __restrict__ out)           // [A,N]
+// One output tile: rows [row_begin,row_end) (at most MT) x columns [n0, n0+NT) of expert weights wexp.
+template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int EPI, bool BIAS>
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const bf16_t* __restrict__ wexp,
+                                          const bf16_t* __restrict__ bias_e, int row_begin, int row_end, int n0, int K, int N,
+                                          bf16_t* __restrict__ out, unsigned char* smem)
 {
     constexpr int NWAVES = WM * WN;
     constexpr int RB = KT * 2;              // bytes per tile row
     constexpr int CPR = RB / 16;            // 16-byte chunks per tile row
     constexpr int RPI = 1024 / RB;          // tile rows covered by one wavefront-wide direct-to-LDS load
-    constexpr int GROUPS = (MT + NT) / RPI; // load instructions per K tile (whole workgroup)
-    constexpr int LPW = GROUPS / NWAVES;    // ... per wavefront
+    constexpr int LPW = (MT + NT) / RPI / NWAVES;  // direct-to-LDS load instructions per K tile and wavefront
     constexpr int STAGE_BYTES = (MT + NT) * RB;
     constexpr int WTM = MT / WM, WTN = NT / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int KSTEPS = KT / 16;
     static_assert(KT == 32 || KT == 64, "row swizzle is written for 64- and 128-byte tile rows");
-    static_assert(GROUPS % NWAVES == 0 && MT % RPI == 0 && NT % RPI == 0, "tile must split evenly over the wavefronts");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wavefront tile is made of 32x32 MFMA tiles");
     static_assert((STAGES - 1) * LPW < 64, "outstanding loads must fit the vmcnt counter");
 
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-
     const int lane = lane_id();
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int wm = wave / WN, wn = wave % WN;
 
-    Tile2D tile;
-    const int n_tiles = (N + NT - 1) / NT;
-    if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, blockIdx.x % kXcdCount, blockIdx.x / kXcdCount, tile)) return;
-    const int n0 = tile.n_tile * NT;
-    const bf16_t* wexp = weight + static_cast<size_t>(tile.expert) * N * K;
-
-    // ---- per-lane source pointers of this wavefront's direct-to-LDS loads -------------------
-    // Group gi covers tile rows [gi*RPI, gi*RPI+RPI); lane -> row gi*RPI + lane/CPR and the
-    // 16-byte chunk (lane%CPR) ^ swizzle(row) of that row; it lands at LDS byte gi*1024 + lane*16.
-    const bf16_t* src[LPW];
+    // ---- per-lane sources of this wavefront's direct-to-LDS loads ---------------------------
+    // A stage holds MT activation rows followed by NT weight rows.  One wavefront-wide load
+    // covers RPI consecutive rows (1 KiB of LDS): lane -> row lane/CPR of the group and the
+    // 16-byte chunk (lane%CPR) ^ swizzle(row); it lands at LDS byte group*1024 + lane*16.
+    // Every wavefront owns LA activation groups and LW weight groups; sources are kept as 32-bit
+    // byte offsets from the two (uniform) base pointers.
+    constexpr int LA = MT / RPI / NWAVES, LW = NT / RPI / NWAVES;
+    static_assert(LA * RPI * NWAVES == MT && LW * RPI * NWAVES == NT, "tile rows must split evenly over the wavefronts");
+    uint32_t off_a[LA], off_w[LW];
 #pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-        const int gi = wave + i * NWAVES;
-        const int row = gi * RPI + lane / CPR;  // row inside the stage: activation rows first, then weight rows
-        const int swz = (KT == 64) ? (row & 7) : ((row >> 1) & 3);
-        const int chunk = (lane % CPR) ^ swz;
-        if (row < MT) {
-            const int r = min(tile.row_begin + row, tile.row_end - 1);  // rows past the tile end re-read the last valid row
-            src[i] = act + static_cast<size_t>(r) * K + chunk * 8;
-        } else {
-            const int r = min(n0 + row - MT, N - 1);
-            src[i] = wexp + static_cast<size_t>(r) * K + chunk * 8;
-        }
+    for (int i = 0; i < LA; ++i) {
+        const int row = (wave * LA + i) * RPI + lane / CPR;
+        const int chunk = (lane % CPR) ^ chunk_swizzle<KT, SWZ>(row);
+        const int r = min(row_begin + row, row_end - 1);  // rows past the tile end re-read the last valid row
+        off_a[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
     }
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        const int row = (wave * LW + i) * RPI + lane / CPR;
+        const int chunk = (lane % CPR) ^ chunk_swizzle<KT, SWZ>(MT + row);
+        const int r = min(n0 + row, N - 1);
+        off_w[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
+    }
+    const unsigned char* act_b = uniform_ptr(reinterpret_cast<const unsigned char*>(act));
+    const unsigned char* wgt_b = uniform_ptr(reinterpret_cast<const unsigned char*>(wexp));
 
     // ---- per-lane LDS byte offsets of the MFMA operand reads -------------------------------
     // operand row = base + lane%32; K step ks uses logical chunk 2*ks + lane/32
     int frag_off[KSTEPS];
     {
         const int row = lane & 31;
-        const int swz = (KT == 64) ? (row & 7) : ((row >> 1) & 3);
+        const int swz = chunk_swizzle<KT, SWZ>(row);
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) frag_off[ks] = row * RB + (((2 * ks + (lane >> 5)) ^ swz) * 16);
     }
@@ -185,22 +253,29 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_bf16_kernel(const bf
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
     const int nk = K / KT;
+    const uint32_t smem_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) unsigned char*)smem));  // LDS byte address of the ring
     auto issue = [&](int kt) {
-        unsigned char* stage = smem + (kt % STAGES) * STAGE_BYTES;
+        const uint32_t stage = smem_addr + (kt % STAGES) * STAGE_BYTES;
+        const size_t kbyte = static_cast<size_t>(kt) * (KT * 2);
 #pragma unroll
-        for (int i = 0; i < LPW; ++i) {
-            const int gi = wave + i * NWAVES;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(src[i] + static_cast<size_t>(kt) * KT),
-                (__attribute__((address_space(3))) void*)(stage + gi * 1024), 16, 0, 0);
-        }
+        for (int i = 0; i < LA; ++i) lds_dma_16B(act_b + kbyte, off_a[i], stage + (wave * LA + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < LW; ++i) lds_dma_16B(wgt_b + kbyte, off_w[i], stage + MT * RB + (wave * LW + i) * 1024);
     };
 
+    EXF_STAMP(1);
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
         if (s < nk) issue(s);
 
+#ifdef EXF_TUNE_TIMING
+    long long t_sync = 0, t_comp = 0;
+#endif
     for (int kt = 0; kt < nk; ++kt) {
+#ifdef EXF_TUNE_TIMING
+        const long long c0 = clock64();
+#endif
         // K tile kt must have landed; up to STAGES-2 younger tiles may still be in flight
         const int younger = min(nk - 1, kt + STAGES - 2) - kt;
         if constexpr (STAGES >= 4) {
@@ -214,53 +289,174 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_bf16_kernel(const bf
             wait_vmcnt<0>();
         }
         __syncthreads();  // everyone's share of tile kt is in LDS, and everyone is done reading tile kt-1
+#ifdef EXF_TUNE_TIMING
+        const long long c1 = clock64();
+#endif
+#ifndef EXF_TUNE_NO_LOAD
         if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
+#endif
 
+        // MFMA operands are double-buffered in registers: the LDS reads of K step ks+1 are in
+        // flight while the matrix cores work on K step ks.
         const unsigned char* stage = smem + (kt % STAGES) * STAGE_BYTES;
+        const unsigned char* pw = stage + wgt_base;
+        const unsigned char* pa = stage + act_base;
+        bf16x8_t fa[2][TN], fb[2][TM];
+#pragma unroll
+        for (int a = 0; a < TN; ++a) fa[0][a] = *reinterpret_cast<const bf16x8_t*>(pw + a * 32 * RB + frag_off[0]);
+#pragma unroll
+        for (int b = 0; b < TM; ++b) fb[0][b] = *reinterpret_cast<const bf16x8_t*>(pa + b * 32 * RB + frag_off[0]);
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            bf16x8_t fa[TN], fb[TM];
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < KSTEPS) {
+#pragma unroll
+                for (int a = 0; a < TN; ++a)
+                    fa[nxt][a] = *reinterpret_cast<const bf16x8_t*>(pw + a * 32 * RB + frag_off[ks + 1]);
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+                    fb[nxt][b] = *reinterpret_cast<const bf16x8_t*>(pa + b * 32 * RB + frag_off[ks + 1]);
+            }
+#ifndef EXF_TUNE_NO_MFMA
 #pragma unroll
             for (int a = 0; a < TN; ++a)
-                fa[a] = *reinterpret_cast<const bf16x8_t*>(stage + wgt_base + a * 32 * RB + frag_off[ks]);
 #pragma unroll
-            for (int b = 0; b < TM; ++b)
-                fb[b] = *reinterpret_cast<const bf16x8_t*>(stage + act_base + b * 32 * RB + frag_off[ks]);
+                for (int b = 0; b < TM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][a], fb[cur][b], acc[a][b], 0, 0, 0);
+#else
+            acc[0][0][0] += static_cast<float>(fa[cur][0][0]) + static_cast<float>(fb[cur][0][0]);
+#endif
+            // Issue order inside the K step: one operand fetch for the next step, then a couple of
+            // MFMAs of this step, and so on - the LDS traffic of the four wavefronts is spread under
+            // the matrix-core work instead of arriving as one burst while the MFMA pipes idle.
+            if (ks + 1 < KSTEPS) {
 #pragma unroll
-            for (int a = 0; a < TN; ++a)
-#pragma unroll
-                for (int b = 0; b < TM; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-        }
-    }
-
-    // ---- epilogue: lane holds, for output row m = .. + lane%32, columns n = .. + 8*g + 4*(lane/32) + r ----
-    const bf16_t* bexp = bias != nullptr ? bias + static_cast<size_t>(tile.expert) * N : nullptr;
-#pragma unroll
-    for (int b = 0; b < TM; ++b) {
-        const int m = tile.row_begin + wm * WTM + b * 32 + (lane & 31);
-        if (m >= tile.row_end) continue;
-        bf16_t* orow = out + static_cast<size_t>(m) * N;
-#pragma unroll
-        for (int a = 0; a < TN; ++a) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * WTN + a * 32 + g * 8 + (lane >> 5) * 4;
-                if (n >= N) continue;  // N % 4 == 0: a group of four is entirely inside or outside
-                float v[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float z = acc[a][b][g * 4 + r];
-                    if (bexp != nullptr) z += bf16_to_f32(bexp[n + r]);
-                    if constexpr (EPI == kEpiGeluErf) z = gelu_erf_fast(z);
-                    if constexpr (EPI == kEpiGeluTanh) z = gelu_tanh_fast(z);
-                    v[r] = z;
+                for (int i = 0; i < TN + TM; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                         // 1 LDS read
+                    __builtin_amdgcn_sched_group_barrier(0x008, (TN * TM) / (TN + TM), 0);     // MFMAs
                 }
-                uint2 packed;
-                packed.x = pack_bf16x2(v[0], v[1]);
-                packed.y = pack_bf16x2(v[2], v[3]);
-                *reinterpret_cast<uint2*>(orow + n) = packed;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#ifdef EXF_TUNE_TIMING
+        const long long c2 = clock64();
+        t_sync += c1 - c0;
+        t_comp += c2 - c1;
+#endif
+    }
+#ifdef EXF_TUNE_TIMING
+    if (blockIdx.x < 64 * 8 && (blockIdx.x % 8) == 0 && threadIdx.x == 0) {
+        exf_tune_times[(blockIdx.x / 8) * 8 + 6] = t_sync;
+        exf_tune_times[(blockIdx.x / 8) * 8 + 7] = t_comp;
+    }
+#endif
+
+    // ---- epilogue -----------------------------------------------------------------------------
+    // A lane holds, for output row m = .. + lane%32, the columns n = .. + 8*g + 4*(lane/32) + r.
+    // Writing that straight to memory would touch 32 rows per store instruction, so every
+    // wavefront transposes its tile through its own slice of the (now idle) LDS ring, 64 rows at a
+    // time, and stores whole 16-byte chunks of contiguous row segments.
+    constexpr int BP = TM >= 2 ? 2 : 1;            // 32-row MFMA tiles per pass
+    constexpr int ROW_BYTES = WTN * 2;
+    constexpr int S = ROW_BYTES + 8;               // padded LDS row stride: conflict-free 8-byte writes
+    constexpr int REGION = BP * 32 * S;
+    constexpr int CW = ROW_BYTES / 16;             // 16-byte chunks per row segment
+    constexpr int RPI_OUT = 64 / CW;               // rows covered by one wavefront-wide 16-byte access
+    static_assert(NWAVES * REGION <= STAGES * STAGE_BYTES, "epilogue staging must fit in the LDS ring");
+    static_assert(64 % CW == 0 && (BP * 32) % RPI_OUT == 0, "row segments must tile the wavefront");
+    EXF_STAMP(2);
+#ifdef EXF_TUNE_NO_EPI
+    if (acc[0][0][0] != 123.456f) return;
+#endif
+    __syncthreads();  // every wavefront is done reading the last K tile
+    EXF_STAMP(3);
+    unsigned char* region = smem + wave * REGION;
+    const int n_wave = n0 + wn * WTN;
+    // bias of the 4 columns a lane owns in every (a, g) group; the same for all of its rows
+    float bias_v[TN][4][4];
+    if constexpr (BIAS) {
+        const bf16_t* bexp = bias_e;
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    bias_v[a][g][r] = bf16_to_f32(bexp[min(n_wave + a * 32 + g * 8 + (lane >> 5) * 4 + r, N - 1)]);
+    }
+#pragma unroll
+    for (int pass = 0; pass < TM / BP; ++pass) {
+#pragma unroll
+        for (int bl = 0; bl < BP; ++bl) {
+            const int b = pass * BP + bl;
+#pragma unroll
+            for (int a = 0; a < TN; ++a) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = a * 32 + g * 8 + (lane >> 5) * 4;
+                    float v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float z = acc[a][b][g * 4 + r];
+                        if constexpr (BIAS) z += bias_v[a][g][r];
+                        if constexpr (EPI == kEpiGeluErf) z = gelu_erf_fast(z);
+                        if constexpr (EPI == kEpiGeluTanh) z = gelu_tanh_fast(z);
+                        v[r] = z;
+                    }
+                    uint2 packed;
+                    packed.x = pack_bf16x2(v[0], v[1]);
+                    packed.y = pack_bf16x2(v[2], v[3]);
+                    *reinterpret_cast<uint2*>(region + (bl * 32 + (lane & 31)) * S + col * 2) = packed;
+                }
             }
         }
+        // same wavefront reads back what it just wrote (LDS operations of a wavefront execute in order)
+        const int m_pass = row_begin + wm * WTM + pass * BP * 32;
+#pragma unroll
+        for (int it = 0; it < BP * 32 / RPI_OUT; ++it) {
+            const int r = it * RPI_OUT + lane / CW;
+            const int c = lane % CW;
+            const uint4 val = *reinterpret_cast<const uint4*>(region + r * S + c * 16);
+            const int m = m_pass + r;
+            const int n = n_wave + c * 8;
+            if (m < row_end && n < N)  // N % 8 == 0: a chunk is entirely inside or outside
+                *reinterpret_cast<uint4*>(out + static_cast<size_t>(m) * N + n) = val;
+        }
+    }
+    EXF_STAMP(4);
+#ifdef EXF_TUNE_TIMING
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    EXF_STAMP(5);
+#endif
+}
+
+template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int OCC, int EPI, bool BIAS>
+__global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(const bf16_t* __restrict__ act,     // [A,K]
+                                                                         const int32_t* __restrict__ offsets,
+                                                                         const bf16_t* __restrict__ weight,  // [E_local,N,K]
+                                                                         const bf16_t* __restrict__ bias,    // [E_local,N] or null
+                                                                         int max_rows, int K, int N, int E_local,
+                                                                         bf16_t* __restrict__ out)           // [A,N]
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    EXF_STAMP(0);
+    Tile2D tile;
+    const int n_tiles = (N + NT - 1) / NT;
+    if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, tile_index_of_workgroup(blockIdx.x), tile)) return;
+    const bf16_t* wexp = weight + static_cast<size_t>(tile.expert) * N * K;
+    const bf16_t* bias_e = BIAS ? bias + static_cast<size_t>(tile.expert) * N : nullptr;
+    if (!tile.tail || MT <= kTailRows) {
+        gemm_tile<MT, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end, tile.n_tile * NT, K,
+                                                              N, out, smem);
+    } else if constexpr (MT > kTailRows) {
+        // remainder rows: all wavefronts side by side over the columns, kTailRows rows each.  A
+        // tail stage is smaller than a full one, so the same LDS ring holds a deeper pipeline -
+        // which the tail needs, because it has little MFMA work per K tile to hide the loads.
+        constexpr int kRing = STAGES * (MT + NT) * KT * 2;
+        constexpr int kFit = kRing / ((kTailRows + NT) * KT * 2);
+        constexpr int STAGES_T = kFit >= 4 ? 4 : (kFit >= 3 ? 3 : 2);
+        gemm_tile<kTailRows, NT, KT, STAGES_T, 1, WM * WN, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end,
+                                                                           tile.n_tile * NT, K, N, out, smem);
     }
 }
 
@@ -330,19 +526,21 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
 }
 
 // ---------------------------------------------------------------------------- host launchers
-template <int MT, int NT, int KT, int STAGES, int WM, int WN>
+template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int OCC>
 static int launch_bf16(const void* act, const int32_t* offsets, const void* weight, const void* bias, int64_t A, int K, int N,
                        int E_local, int epi, void* out, hipStream_t stream)
 {
     constexpr size_t lds = static_cast<size_t>(STAGES) * (MT + NT) * KT * 2;
-    const int64_t row_tiles = (A + MT - 1) / MT + E_local;
+    // worst case: A/MT full row tiles plus MT/kTailRows tail row tiles for every expert
+    const int64_t row_tiles = A / MT + static_cast<int64_t>(E_local) * ((MT + kTailRows - 1) / kTailRows);
     const int64_t n_tiles = (N + NT - 1) / NT;
     const int64_t ub = row_tiles * n_tiles;
-    const int64_t grid = (ub + kXcdCount - 1) / kXcdCount * kXcdCount;
+    const int64_t round = static_cast<int64_t>(kXcdCount) * kXcdChunk;
+    const int64_t grid = (ub + round - 1) / round * round;
     if (grid >= (1ll << 31)) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn: too many tiles");
-#define EXF_LAUNCH_BF16(EPI)                                                                                                    \
+#define EXF_LAUNCH_BF16(EPI, BIAS)                                                                                              \
     do {                                                                                                                        \
-        auto kern = grouped_gemm_bf16_kernel<MT, NT, KT, STAGES, WM, WN, EPI>;                                                  \
+        auto kern = grouped_gemm_bf16_kernel<MT, NT, KT, STAGES, WM, WN, SWZ, OCC, EPI, BIAS>;                                  \
         if (lds > 64 * 1024) {                                                                                                  \
             hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                  static_cast<int>(lds));                                                       \
@@ -352,9 +550,15 @@ static int launch_bf16(const void* act, const int32_t* offsets, const void* weig
                            static_cast<const bf16_t*>(act), offsets, static_cast<const bf16_t*>(weight),                        \
                            static_cast<const bf16_t*>(bias), static_cast<int>(A), K, N, E_local, static_cast<bf16_t*>(out));    \
     } while (0)
-    if (epi == kEpiNone) EXF_LAUNCH_BF16(kEpiNone);
-    else if (epi == kEpiGeluErf) EXF_LAUNCH_BF16(kEpiGeluErf);
-    else EXF_LAUNCH_BF16(kEpiGeluTanh);
+    if (bias == nullptr) {
+        if (epi == kEpiNone) EXF_LAUNCH_BF16(kEpiNone, false);
+        else if (epi == kEpiGeluErf) EXF_LAUNCH_BF16(kEpiGeluErf, false);
+        else EXF_LAUNCH_BF16(kEpiGeluTanh, false);
+    } else {
+        if (epi == kEpiNone) EXF_LAUNCH_BF16(kEpiNone, true);
+        else if (epi == kEpiGeluErf) EXF_LAUNCH_BF16(kEpiGeluErf, true);
+        else EXF_LAUNCH_BF16(kEpiGeluTanh, true);
+    }
 #undef EXF_LAUNCH_BF16
     return EXF_OK;
 }
@@ -379,7 +583,35 @@ static int launch_f32(const void* act, const int32_t* offsets, const void* weigh
     return EXF_OK;
 }
 
+// Tile configuration <MT, NT, KT, STAGES, WM, WN, SWZ, OCC> of the two contractions
+// (OCC = wavefronts per SIMD the register allocation must leave room for).
+#ifndef EXF_GEMM1_CFG
+#define EXF_GEMM1_CFG 256, 128, 32, 3, 2, 2, 0, 2
+#endif
+#ifndef EXF_GEMM2_CFG
+#define EXF_GEMM2_CFG 256, 128, 32, 3, 2, 2, 0, 2
+#endif
+
+// Tuning builds (-DEXF_FFN_TUNE) can skip one of the two contractions to time the other alone.
+static bool tune_skip(int which)
+{
+#ifdef EXF_FFN_TUNE
+    const char* only = getenv("EXF_TUNE_ONLY");
+    return only != nullptr && atoi(only) != 0 && atoi(only) != which;
+#else
+    (void)which;
+    return false;
+#endif
+}
+
 }  // namespace exf
+
+#ifdef EXF_TUNE_TIMING
+extern "C" int exf_tune_read_times(unsigned long long* host)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(exf::exf_tune_times), sizeof(unsigned long long) * 8 * 64) == hipSuccess ? 0 : -5;
+}
+#endif
 
 extern "C" size_t moe_expert_ffn_workspace_bytes(int64_t A, int d, int f, int E_local, int dt)
 {
@@ -403,6 +635,12 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
     const int gran = dt == EXF_BF16 ? 64 : 4;
     if (d < gran || d % gran != 0 || f < gran || f % gran != 0)
         return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn: d = %d and f = %d must be positive multiples of %d", d, f, gran);
+    if (dt == EXF_BF16) {  // the bf16 kernel addresses rows with 32-bit byte offsets
+        const unsigned long long widest = static_cast<unsigned long long>(d > f ? d : f);
+        if (static_cast<unsigned long long>(A) * widest * 2ull >= (1ull << 32) ||
+            static_cast<unsigned long long>(d) * static_cast<unsigned long long>(f) * 2ull >= (1ull << 32))
+            return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn: A*max(d,f) and d*f must stay below 2^31 elements (bf16)");
+    }
     if (A == 0) return EXF_OK;
     EXF_REQUIRE_PTR(x_sorted);
     EXF_REQUIRE_PTR(expert_offsets);
@@ -425,9 +663,10 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
         rc = launch_f32(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s);
         if (rc == EXF_OK) rc = launch_f32(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
     } else {
-        rc = launch_bf16<128, 128, 64, 2, 2, 2>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s);
-        if (rc == EXF_OK)
-            rc = launch_bf16<128, 128, 64, 2, 2, 2>(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
+        rc = EXF_OK;
+        if (!tune_skip(1)) rc = launch_bf16<EXF_GEMM1_CFG>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s);
+        if (rc == EXF_OK && !tune_skip(2))
+            rc = launch_bf16<EXF_GEMM2_CFG>(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
     }
     if (rc != EXF_OK) return rc;
     return check_launch("moe_expert_ffn");
