@@ -72,7 +72,7 @@ def _time_rotating(make_fn, n_sets, iters):
     return a.elapsed_time(b) / iters
 
 
-def cpu_baseline(cfg, x, wg, w1, w2, trace, placement, sample_rows_per_expert=96):
+def cpu_baseline(cfg, x, wg, w1, w2, trace, placement, sample_rows_per_expert=None):
     """The CPU oracle as it stands, timed on this host: every step in full except the expert
     FFN, which runs on a sample of rows of every expert and is extrapolated linearly."""
     import oracle
@@ -89,7 +89,7 @@ def cpu_baseline(cfg, x, wg, w1, w2, trace, placement, sample_rows_per_expert=96
     rows = []
     for e in range(cfg.E_local):
         lo, hi = int(disp["offsets"][e]), int(disp["offsets"][e + 1])
-        rows.extend(range(lo, min(hi, lo + sample_rows_per_expert)))
+        rows.extend(range(lo, hi if sample_rows_per_expert is None else min(hi, lo + sample_rows_per_expert)))
     rows = np.array(rows, dtype=np.int64)
     t0 = time.perf_counter()
     y = oracle.expert_ffn_rows(xs, disp["offsets"], w1, None, w2, None, 0, rows)
@@ -113,8 +113,10 @@ def cpu_baseline(cfg, x, wg, w1, w2, trace, placement, sample_rows_per_expert=96
         "unit": "tokens/s",
         "cores": oracle.threads(),
         "kind": "oracle",
-        "sample": f"expert FFN on {len(rows)} of {disp['kept']} rows ({sample_rows_per_expert} per expert, measured "
-                  f"{t_ffn_sample:.2f} s, extrapolated linearly); gate, dispatch, combine, affinity, locality in full",
+        "sample": (f"one full step of the benchmark workload (all {disp['kept']} rows through the expert FFN, "
+                   f"{t_ffn_sample:.2f} s of the total)") if len(rows) == disp["kept"] else
+                  (f"expert FFN on {len(rows)} of {disp['kept']} rows (measured {t_ffn_sample:.2f} s, extrapolated linearly); "
+                   f"gate, dispatch, combine, affinity, locality in full"),
         "seconds_per_step_extrapolated": total,
         "seconds": {k: round(v, 4) for k, v in t.items()},
     }

@@ -1,14 +1,17 @@
 // affinity_histogram and placement_locality: reductions over a routing trace [L,N] (int32,
-// layer-major).  Both are bound by the HBM read of the trace (4 bytes per token and layer).
+// layer-major).  Both are bound by the HBM read of the trace (4 bytes per token and layer), so
+// both are shaped like a streaming read: about one 1024-thread workgroup per CU, every thread
+// keeping several 16-byte loads in flight.
 //
 // affinity_histogram
-//   partial : a workgroup owns a chunk of tokens and a group of `g` consecutive layer pairs.
-//             It keeps the g E x E histograms in LDS (replicated when E*E is small so that hot
-//             bins do not serialise), walks the g+1 trace columns with the previous layer's ids
-//             held in registers, bins every transition with an LDS atomic, and stores its
-//             histograms as 32-bit partials.  Workgroups of one token chunk are mapped to one
-//             XCD so that the column shared by neighbouring pair groups is served by that
-//             XCD's L2.
+//   partial : a workgroup owns a chunk of tokens (< 65536) and a group of g <= 6 consecutive
+//             layer pairs.  A thread loads the g+1 trace columns of its tokens at once, then walks
+//             the pairs and bins every transition with one LDS atomic.  The g E x E histograms
+//             live in LDS as 16-bit counters packed two to a word (a workgroup can never count
+//             more than its chunk, so they cannot overflow), replicated when E*E is small so that
+//             hot bins do not serialise.  The packed words are stored as per-chunk partials.
+//             Workgroups of one token chunk are mapped to one XCD, so the column shared by two
+//             neighbouring pair groups is served by that XCD's L2.
 //   finalize: one wavefront per (pair, source expert) row sums the partials over the chunks
 //             into int64 counts, forms the row sum, the layer loads and the conditional
 //             probabilities; a last small kernel derives the loads of the final layer.
@@ -17,25 +20,37 @@
 //
 // placement_locality
 //   a workgroup owns a chunk of tokens for ALL layers (each trace entry is read exactly once),
-//   maps expert -> device through an LDS copy of the placement, and counts per pair the tokens
-//   whose device does not change; per-chunk partial counts are summed by a second kernel.
+//   maps expert -> device through an LDS copy of the placement, keeps the loads of four layers in
+//   flight, and counts per pair the tokens whose device does not change; per-chunk partial counts
+//   are summed by a second kernel.
 #include "common.hpp"
 
 namespace exf {
 
 constexpr int kXcds = 8;
-constexpr int kAffThreads = 256;
-constexpr int kAffSlots = 4;                                  // register-held token groups per thread
-constexpr size_t kAffHistBudget = 48 * 1024;                  // LDS bytes for the pair histograms
+#ifndef EXF_TRACE_THREADS
+#define EXF_TRACE_THREADS 1024
+#endif
+#ifndef EXF_TARGET_WGS
+#define EXF_TARGET_WGS 256
+#endif
+#ifndef EXF_LOC_AHEAD
+#define EXF_LOC_AHEAD 4
+#endif
+constexpr int kTraceThreads = EXF_TRACE_THREADS;
+constexpr int kAffMaxGroup = 6;                        // layer pairs per workgroup (7 columns in registers)
+constexpr size_t kAffHistBudget = 48 * 1024;           // LDS bytes for the packed pair histograms
+constexpr int64_t kAffMaxChunk = 61440;                // tokens per workgroup: 16-bit counters cannot overflow
+constexpr int kTargetWorkgroups = EXF_TARGET_WGS;       // about one per CU
 
 struct AffinityPlan {
     int g;           // layer pairs per workgroup
     int Q;           // pair groups
     int copies;      // histogram replicas (power of two)
+    int words;       // 32-bit words of one packed E x E histogram
     int64_t chunk;   // tokens per workgroup
     int C;           // token chunks
     int vec;         // 4 if 16-byte trace loads are possible, else 1
-    // workspace layout (32-bit words unless noted)
     size_t off_counts, off_orphan_next, off_orphan_last, off_invalid, total_bytes;
 };
 
@@ -43,27 +58,29 @@ static AffinityPlan make_affinity_plan(int L, int64_t N, int E, bool aligned)
 {
     AffinityPlan p;
     const int pairs = L > 1 ? L - 1 : 0;
-    const size_t bins = static_cast<size_t>(E) * E;
-    p.copies = 1;
-    while (p.copies < 16 && bins * (p.copies * 2) <= 1024) p.copies *= 2;
-    int g = static_cast<int>(kAffHistBudget / (bins * p.copies * sizeof(uint32_t)));
+    p.words = (E * E + 1) / 2;
+    const size_t hist_bytes = static_cast<size_t>(p.words) * sizeof(uint32_t);
+    int g = static_cast<int>(kAffHistBudget / hist_bytes);
+    if (g > kAffMaxGroup) g = kAffMaxGroup;
     if (g < 1) g = 1;
-    if (g > 4) g = 4;
     if (pairs > 0 && g > pairs) g = pairs;
     p.g = g;
+    p.copies = 1;
+    while (p.copies < 16 && hist_bytes * g * (p.copies * 2) <= kAffHistBudget) p.copies *= 2;
     p.Q = pairs > 0 ? (pairs + g - 1) / g : 1;
     p.vec = (aligned && N % 4 == 0) ? 4 : 1;
-    // tokens per workgroup: at least one full sweep of the registers, at most what keeps the
-    // partial-histogram traffic an order of magnitude below the trace itself.
-    const int64_t sweep = static_cast<int64_t>(kAffThreads) * kAffSlots * p.vec;
-    int64_t chunk = static_cast<int64_t>(bins) * 8;  // one partial bin is stored per 8 tokens binned
-    if (chunk < sweep) chunk = sweep;
+    const int64_t sweep = static_cast<int64_t>(kTraceThreads) * p.vec;  // tokens one pass of the workgroup covers
+    int c_target = kTargetWorkgroups / p.Q;
+    if (c_target < 1) c_target = 1;
+    int64_t chunk = (N + c_target - 1) / c_target;
     chunk = (chunk + sweep - 1) / sweep * sweep;
+    if (chunk < sweep) chunk = sweep;
+    if (chunk > kAffMaxChunk) chunk = kAffMaxChunk / sweep * sweep;
     p.chunk = chunk;
     p.C = static_cast<int>(N > 0 ? (N + chunk - 1) / chunk : 0);
     size_t off = 0;
     p.off_counts = off;
-    off += align_up(static_cast<size_t>(p.C) * pairs * bins * sizeof(uint32_t), 256);
+    off += align_up(static_cast<size_t>(p.C) * pairs * p.words * sizeof(uint32_t), 256);
     p.off_orphan_next = off;
     off += align_up(static_cast<size_t>(p.C) * (pairs > 0 ? pairs : 1) * E * sizeof(uint32_t), 256);
     p.off_orphan_last = off;
@@ -85,11 +102,12 @@ __device__ __forceinline__ TokVec<VEC> load_tokens(const int32_t* __restrict__ c
     TokVec<VEC> r;
     if constexpr (VEC == 4) {
         if (n + 3 < end) {
-            const int4 q = *reinterpret_cast<const int4*>(col + n);
-            r.v[0] = q.x;
-            r.v[1] = q.y;
-            r.v[2] = q.z;
-            r.v[3] = q.w;
+            typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_v;
+            const i32x4_v q = __builtin_nontemporal_load(reinterpret_cast<const i32x4_v*>(col + n));  // streamed once
+            r.v[0] = q[0];
+            r.v[1] = q[1];
+            r.v[2] = q[2];
+            r.v[3] = q[3];
         } else {
 #pragma unroll
             for (int u = 0; u < 4; ++u) r.v[u] = (n + u < end) ? col[n + u] : 0;
@@ -101,17 +119,16 @@ __device__ __forceinline__ TokVec<VEC> load_tokens(const int32_t* __restrict__ c
 }
 
 template <int VEC>
-__global__ __launch_bounds__(kAffThreads) void affinity_partial_kernel(const int32_t* __restrict__ trace, int L, int64_t N, int E,
-                                                                        int g, int Q, int copies, int64_t chunk, int C,
-                                                                        uint32_t* __restrict__ part_counts,
-                                                                        uint32_t* __restrict__ part_orphan_next,
-                                                                        uint32_t* __restrict__ part_orphan_last,
-                                                                        uint32_t* __restrict__ part_invalid)
+__global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const int32_t* __restrict__ trace, int L, int64_t N, int E,
+                                                                          int g, int Q, int copies, int words, int64_t chunk, int C,
+                                                                          uint32_t* __restrict__ part_counts,
+                                                                          uint32_t* __restrict__ part_orphan_next,
+                                                                          uint32_t* __restrict__ part_orphan_last,
+                                                                          uint32_t* __restrict__ part_invalid)
 {
     extern __shared__ uint32_t lds[];
-    const int bins = E * E;
-    uint32_t* hist = lds;                                 // [copies][g][bins]
-    uint32_t* orphan_next = hist + copies * g * bins;     // [g][E]   valid id whose successor is invalid
+    uint32_t* hist = lds;                                 // [copies][g][words], two 16-bit counters per word
+    uint32_t* orphan_next = hist + copies * g * words;    // [g][E]   valid id whose successor is invalid
     uint32_t* orphan_last = orphan_next + g * E;          // [E]      valid id of the final layer whose predecessor is invalid
     uint32_t* invalid_cnt = orphan_last + E;              // [1]
 
@@ -123,8 +140,8 @@ __global__ __launch_bounds__(kAffThreads) void affinity_partial_kernel(const int
     const int q = j % Q;
     if (c >= C) return;
 
-    const int lds_words = copies * g * bins + g * E + E + 1;
-    for (int i = threadIdx.x; i < lds_words; i += kAffThreads) lds[i] = 0u;
+    const int lds_words = copies * g * words + g * E + E + 1;
+    for (int i = threadIdx.x; i < lds_words; i += kTraceThreads) lds[i] = 0u;
     __syncthreads();
 
     const int pairs = L - 1;
@@ -133,180 +150,213 @@ __global__ __launch_bounds__(kAffThreads) void affinity_partial_kernel(const int
     const bool owns_last = (l1 == L - 1);
     const int64_t n_begin = static_cast<int64_t>(c) * chunk;
     const int64_t n_end = min(N, n_begin + chunk);
-    uint32_t* my_hist = hist + (threadIdx.x & (copies - 1)) * g * bins;
+    uint32_t* my_hist = hist + (threadIdx.x & (copies - 1)) * g * words;
     uint32_t invalid_local = 0;
 
-    for (int64_t base = n_begin; base < n_end; base += static_cast<int64_t>(kAffThreads) * kAffSlots * VEC) {
-        TokVec<VEC> prev[kAffSlots];
-        int64_t n0[kAffSlots];
+    for (int64_t base = n_begin; base < n_end; base += static_cast<int64_t>(kTraceThreads) * VEC) {
+        const int64_t n0 = base + static_cast<int64_t>(threadIdx.x) * VEC;
+        // all columns of the group at once: up to seven 16-byte loads in flight per thread
+        TokVec<VEC> col[kAffMaxGroup + 1];
 #pragma unroll
-        for (int s = 0; s < kAffSlots; ++s) {
-            n0[s] = base + (static_cast<int64_t>(s) * kAffThreads + threadIdx.x) * VEC;
-            prev[s] = load_tokens<VEC>(trace + static_cast<int64_t>(l0) * N, n0[s], n_end);
-        }
-        for (int l = l0 + 1; l <= l1; ++l) {
-            TokVec<VEC> cur[kAffSlots];
+        for (int s = 0; s <= kAffMaxGroup; ++s)
+            if (l0 + s <= l1 || s == 0) col[s] = load_tokens<VEC>(trace + static_cast<int64_t>(l0 + s) * N, n0, n_end);
 #pragma unroll
-            for (int s = 0; s < kAffSlots; ++s) cur[s] = load_tokens<VEC>(trace + static_cast<int64_t>(l) * N, n0[s], n_end);
-            uint32_t* h = my_hist + (l - 1 - l0) * bins;
+        for (int s = 1; s <= kAffMaxGroup; ++s) {
+            const int l = l0 + s;
+            if (l > l1) break;
+            uint32_t* h = my_hist + (s - 1) * words;
             const bool last = (l == L - 1);
 #pragma unroll
-            for (int s = 0; s < kAffSlots; ++s) {
-#pragma unroll
-                for (int u = 0; u < VEC; ++u) {
-                    if (n0[s] + u < n_end) {
-                        const int a = prev[s].v[u];
-                        const int b = cur[s].v[u];
-                        const bool va = static_cast<unsigned>(a) < static_cast<unsigned>(E);
-                        const bool vb = static_cast<unsigned>(b) < static_cast<unsigned>(E);
-                        if (va && vb) {
-                            atomicAdd(&h[a * E + b], 1u);
-                        } else if (va) {
-                            atomicAdd(&orphan_next[(l - 1 - l0) * E + a], 1u);
-                        }
-                        if (!va) invalid_local += 1;             // layer l-1 belongs to this group
-                        if (last) {
-                            if (!vb) invalid_local += 1;
-                            else if (!va) atomicAdd(&orphan_last[b], 1u);
-                        }
+            for (int u = 0; u < VEC; ++u) {
+                if (n0 + u < n_end) {
+                    const int a = col[s - 1].v[u];
+                    const int b = col[s].v[u];
+                    const bool va = static_cast<unsigned>(a) < static_cast<unsigned>(E);
+                    const bool vb = static_cast<unsigned>(b) < static_cast<unsigned>(E);
+                    if (va && vb) {
+                        const int bin = a * E + b;
+#ifndef EXF_TUNE_NO_ATOMIC
+                        atomicAdd(&h[bin >> 1], (bin & 1) ? 0x10000u : 1u);
+#else
+                        invalid_local += bin == 77777;
+#endif
+                    } else if (va) {
+                        atomicAdd(&orphan_next[(s - 1) * E + a], 1u);
                     }
-                    prev[s].v[u] = cur[s].v[u];
+                    if (!va) invalid_local += 1;  // layer l-1 belongs to this group
+                    if (last) {
+                        if (!vb) invalid_local += 1;
+                        else if (!va) atomicAdd(&orphan_last[b], 1u);
+                    }
                 }
             }
         }
         if (L == 1) {  // no pair at all: the single column only feeds loads and the invalid tally
 #pragma unroll
-            for (int s = 0; s < kAffSlots; ++s)
-#pragma unroll
-                for (int u = 0; u < VEC; ++u)
-                    if (n0[s] + u < n_end) {
-                        const int a = prev[s].v[u];
-                        if (static_cast<unsigned>(a) < static_cast<unsigned>(E)) atomicAdd(&orphan_last[a], 1u);
-                        else invalid_local += 1;
-                    }
+            for (int u = 0; u < VEC; ++u)
+                if (n0 + u < n_end) {
+                    const int a = col[0].v[u];
+                    if (static_cast<unsigned>(a) < static_cast<unsigned>(E)) atomicAdd(&orphan_last[a], 1u);
+                    else invalid_local += 1;
+                }
         }
     }
     if (invalid_local) atomicAdd(invalid_cnt, invalid_local);
     __syncthreads();
 
-    // flush: sum the replicas, store 32-bit partials
+    // flush: sum the replicas (packed halves cannot carry: a bin holds at most `chunk` < 65536)
     const int my_pairs = l1 - l0;
-    for (int i = threadIdx.x; i < my_pairs * bins; i += kAffThreads) {
+    for (int i = threadIdx.x; i < my_pairs * words; i += kTraceThreads) {
         uint32_t s = 0;
-        for (int r = 0; r < copies; ++r) s += hist[r * g * bins + i];
-        part_counts[(static_cast<size_t>(c) * pairs + l0) * bins + i] = s;
+        for (int r = 0; r < copies; ++r) s += hist[r * g * words + i];
+        part_counts[(static_cast<size_t>(c) * pairs + l0) * words + i] = s;
     }
-    for (int i = threadIdx.x; i < my_pairs * E; i += kAffThreads)
+    for (int i = threadIdx.x; i < my_pairs * E; i += kTraceThreads)
         part_orphan_next[(static_cast<size_t>(c) * pairs + l0) * E + i] = orphan_next[i];
     if (owns_last || L == 1)
-        for (int i = threadIdx.x; i < E; i += kAffThreads) part_orphan_last[static_cast<size_t>(c) * E + i] = orphan_last[i];
+        for (int i = threadIdx.x; i < E; i += kTraceThreads) part_orphan_last[static_cast<size_t>(c) * E + i] = orphan_last[i];
     if (threadIdx.x == 0) part_invalid[static_cast<size_t>(c) * Q + q] = *invalid_cnt;
 }
 
-// One wavefront per (pair l, source expert i): lane p sums bin (i,p) over the chunks.
-__global__ __launch_bounds__(kWave) void affinity_finalize_kernel(const uint32_t* __restrict__ part_counts,
-                                                                   const uint32_t* __restrict__ part_orphan_next, int C, int L,
-                                                                   int E, int64_t* __restrict__ counts, int64_t* __restrict__ loads,
-                                                                   float* __restrict__ cond_prob)
+// One workgroup of 256 threads per (pair l, source expert i): wavefront w sums the chunks
+// c = w, w+4, ... of bin (i, p = lane); the four partial sums meet in LDS.
+__global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* __restrict__ part_counts,
+                                                                const uint32_t* __restrict__ part_orphan_next, int C, int L, int E,
+                                                                int words, int64_t* __restrict__ counts, int64_t* __restrict__ loads,
+                                                                float* __restrict__ cond_prob)
 {
+    __shared__ long long red[4][kWave];
+    __shared__ long long orphan_red[4];
     const int pairs = L - 1;
     const int l = blockIdx.x / E;
     const int i = blockIdx.x % E;
-    const int p = threadIdx.x;
-    const size_t bins = static_cast<size_t>(E) * E;
+    const int p = lane_id();
+    const int w = threadIdx.x / kWave;
     long long cnt = 0;
-    if (p < E)
-        for (int c = 0; c < C; ++c) cnt += part_counts[(static_cast<size_t>(c) * pairs + l) * bins + static_cast<size_t>(i) * E + p];
-    const long long row = wave_sum(cnt);
     if (p < E) {
-        const size_t o = (static_cast<size_t>(l) * E + i) * E + p;
-        counts[o] = cnt;
-        if (cond_prob != nullptr) cond_prob[o] = row > 0 ? static_cast<float>(static_cast<double>(cnt) / static_cast<double>(row)) : 0.0f;
+        const int bin = i * E + p;
+        const int shift = (bin & 1) * 16;
+        const uint32_t* src = part_counts + static_cast<size_t>(l) * words + (bin >> 1);
+        const size_t step = static_cast<size_t>(pairs) * words;
+#pragma unroll 4
+        for (int c = w; c < C; c += 4) cnt += (src[c * step] >> shift) & 0xffffu;
     }
-    if (loads != nullptr && p == 0) {
-        long long orphan = 0;
-        for (int c = 0; c < C; ++c) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
-        loads[static_cast<size_t>(l) * E + i] = row + orphan;
+    long long orphan = 0;
+    for (int c = threadIdx.x; c < C; c += 256) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
+    orphan = wave_sum(orphan);
+    red[w][p] = cnt;
+    if (p == 0) orphan_red[w] = orphan;
+    __syncthreads();
+    if (w == 0) {
+        cnt = red[0][p] + red[1][p] + red[2][p] + red[3][p];
+        const long long row = wave_sum(cnt);
+        if (p < E) {
+            const size_t o = (static_cast<size_t>(l) * E + i) * E + p;
+            counts[o] = cnt;
+            if (cond_prob != nullptr)
+                cond_prob[o] = row > 0 ? static_cast<float>(static_cast<double>(cnt) / static_cast<double>(row)) : 0.0f;
+        }
+        if (loads != nullptr && p == 0)
+            loads[static_cast<size_t>(l) * E + i] = row + orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
     }
 }
 
-// loads of the final layer (column sums of the last pair + orphans) and the invalid tally.
-__global__ __launch_bounds__(kWave) void affinity_tail_kernel(const uint32_t* __restrict__ part_orphan_last,
-                                                               const uint32_t* __restrict__ part_invalid, int C, int Q, int L, int E,
-                                                               const int64_t* __restrict__ counts, int64_t* __restrict__ loads,
-                                                               int64_t* __restrict__ n_invalid)
+// loads of the final layer (column sums of the last pair + orphans) and the invalid tally:
+// one workgroup of 1024 threads, wavefront w takes the rows / chunks congruent to w mod 16.
+__global__ __launch_bounds__(1024) void affinity_tail_kernel(const uint32_t* __restrict__ part_orphan_last,
+                                                             const uint32_t* __restrict__ part_invalid, int C, int Q, int L, int E,
+                                                             const int64_t* __restrict__ counts, int64_t* __restrict__ loads,
+                                                             int64_t* __restrict__ n_invalid)
 {
-    const int p = threadIdx.x;
+    __shared__ long long red[16][kWave];
+    __shared__ long long inv_red[16];
+    const int p = lane_id();
+    const int w = threadIdx.x / kWave;
+    long long s = 0;
     if (loads != nullptr && p < E) {
-        long long s = 0;
         if (L > 1)
-            for (int i = 0; i < E; ++i) s += counts[(static_cast<size_t>(L - 2) * E + i) * E + p];
-        for (int c = 0; c < C; ++c) s += part_orphan_last[static_cast<size_t>(c) * E + p];
-        loads[static_cast<size_t>(L - 1) * E + p] = s;
+            for (int i = w; i < E; i += 16) s += counts[(static_cast<size_t>(L - 2) * E + i) * E + p];
+        for (int c = w; c < C; c += 16) s += part_orphan_last[static_cast<size_t>(c) * E + p];
     }
-    if (n_invalid != nullptr) {
-        long long s = 0;
-        for (int i = p; i < C * Q; i += kWave) s += part_invalid[i];
-        s = wave_sum(s);
-        if (p == 0) *n_invalid = s;
+    long long inv = 0;
+    for (int i = threadIdx.x; i < C * Q; i += 1024) inv += part_invalid[i];
+    inv = wave_sum(inv);
+    red[w][p] = s;
+    if (p == 0) inv_red[w] = inv;
+    __syncthreads();
+    if (w == 0) {
+        long long t = 0, ti = 0;
+        for (int q = 0; q < 16; ++q) {
+            t += red[q][p];
+            ti += inv_red[q];
+        }
+        if (loads != nullptr && p < E) loads[static_cast<size_t>(L - 1) * E + p] = t;
+        if (n_invalid != nullptr && p == 0) *n_invalid = ti;
     }
 }
 
 // ------------------------------------------------------------------------------------------
-constexpr int kLocThreads = 256;
-constexpr int kLocSlots = 4;
+constexpr int kLocAhead = EXF_LOC_AHEAD;  // trace layers whose loads are in flight together
 
 template <int VEC>
-__global__ __launch_bounds__(kLocThreads) void locality_partial_kernel(const int32_t* __restrict__ trace,
-                                                                        const int32_t* __restrict__ placement, int L, int64_t N,
-                                                                        int E, int64_t chunk, uint32_t* __restrict__ part)
+__global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const int32_t* __restrict__ trace,
+                                                                          const int32_t* __restrict__ placement, int L, int64_t N,
+                                                                          int E, int64_t chunk, uint32_t* __restrict__ part)
 {
     extern __shared__ int32_t lds_i[];
-    int32_t* pl = lds_i;                                          // [L][E]
+    int32_t* pl = lds_i;                                              // [L][E]
     uint32_t* pair_cnt = reinterpret_cast<uint32_t*>(lds_i + L * E);  // [L-1]
-    for (int i = threadIdx.x; i < L * E; i += kLocThreads) pl[i] = placement[i];
-    for (int i = threadIdx.x; i < L - 1; i += kLocThreads) pair_cnt[i] = 0u;
+    for (int i = threadIdx.x; i < L * E; i += kTraceThreads) pl[i] = placement[i];
+    for (int i = threadIdx.x; i < L - 1; i += kTraceThreads) pair_cnt[i] = 0u;
     __syncthreads();
 
     const int lane = lane_id();
     const int64_t n_begin = static_cast<int64_t>(blockIdx.x) * chunk;
     const int64_t n_end = min(N, n_begin + chunk);
-    for (int64_t base = n_begin; base < n_end; base += static_cast<int64_t>(kLocThreads) * kLocSlots * VEC) {
-        int dev_prev[kLocSlots][VEC];
-        bool ok_prev[kLocSlots][VEC];
-        int64_t n0[kLocSlots];
-#pragma unroll
-        for (int s = 0; s < kLocSlots; ++s) {
-            n0[s] = base + (static_cast<int64_t>(s) * kLocThreads + threadIdx.x) * VEC;
-            const TokVec<VEC> t = load_tokens<VEC>(trace, n0[s], n_end);
+    for (int64_t base = n_begin; base < n_end; base += static_cast<int64_t>(kTraceThreads) * VEC) {
+        const int64_t n0 = base + static_cast<int64_t>(threadIdx.x) * VEC;
+        int dev_prev[VEC];
+        bool ok_prev[VEC];
+        {
+            const TokVec<VEC> t = load_tokens<VEC>(trace, n0, n_end);
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
-                ok_prev[s][u] = (n0[s] + u < n_end) && static_cast<unsigned>(t.v[u]) < static_cast<unsigned>(E);
-                dev_prev[s][u] = ok_prev[s][u] ? pl[t.v[u]] : 0;
+                ok_prev[u] = (n0 + u < n_end) && static_cast<unsigned>(t.v[u]) < static_cast<unsigned>(E);
+                dev_prev[u] = ok_prev[u] ? pl[t.v[u]] : 0;
             }
         }
-        for (int l = 1; l < L; ++l) {
-            TokVec<VEC> cur[kLocSlots];
+        for (int lb = 1; lb < L; lb += kLocAhead) {
+            TokVec<VEC> cur[kLocAhead];
 #pragma unroll
-            for (int s = 0; s < kLocSlots; ++s) cur[s] = load_tokens<VEC>(trace + static_cast<int64_t>(l) * N, n0[s], n_end);
-            int same = 0;
+            for (int a = 0; a < kLocAhead; ++a)
+                if (lb + a < L) cur[a] = load_tokens<VEC>(trace + static_cast<int64_t>(lb + a) * N, n0, n_end);
 #pragma unroll
-            for (int s = 0; s < kLocSlots; ++s) {
+            for (int a = 0; a < kLocAhead; ++a) {
+                const int l = lb + a;
+                if (l >= L) break;
+                // wavefront total of "device unchanged" flags by ballot + popcount (scalar unit)
+                int same = 0;
+#ifdef EXF_TUNE_LOC_NOCOMPUTE
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) dev_prev[u] ^= cur[a].v[u];
+                if (dev_prev[0] == 0x7fffffff) same = 1;
+                if (lane == 0 && same != 0) atomicAdd(&pair_cnt[l - 1], 1u);
+                continue;
+#endif
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) {
-                    const bool ok = (n0[s] + u < n_end) && static_cast<unsigned>(cur[s].v[u]) < static_cast<unsigned>(E);
-                    const int dev = ok ? pl[l * E + cur[s].v[u]] : 0;
-                    same += (ok && ok_prev[s][u] && dev == dev_prev[s][u]) ? 1 : 0;
-                    ok_prev[s][u] = ok;
-                    dev_prev[s][u] = dev;
+                    const bool ok = (n0 + u < n_end) && static_cast<unsigned>(cur[a].v[u]) < static_cast<unsigned>(E);
+                    const int dev = ok ? pl[l * E + cur[a].v[u]] : 0;
+                    same += __popcll(__ballot(ok && ok_prev[u] && dev == dev_prev[u]));
+                    ok_prev[u] = ok;
+                    dev_prev[u] = dev;
                 }
+                if (lane == 0 && same != 0) atomicAdd(&pair_cnt[l - 1], static_cast<uint32_t>(same));
             }
-            same = wave_sum(same);
-            if (lane == 0 && same != 0) atomicAdd(&pair_cnt[l - 1], static_cast<uint32_t>(same));
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < L - 1; i += kLocThreads) part[static_cast<size_t>(blockIdx.x) * (L - 1) + i] = pair_cnt[i];
+    for (int i = threadIdx.x; i < L - 1; i += kTraceThreads) part[static_cast<size_t>(blockIdx.x) * (L - 1) + i] = pair_cnt[i];
 }
 
 __global__ __launch_bounds__(kWave) void locality_finalize_kernel(const uint32_t* __restrict__ part, int C, int pairs,
@@ -321,11 +371,12 @@ __global__ __launch_bounds__(kWave) void locality_finalize_kernel(const uint32_t
 
 static int64_t locality_chunk(int64_t N, int vec)
 {
-    const int64_t sweep = static_cast<int64_t>(kLocThreads) * kLocSlots * vec;
-    // aim at ~4 workgroups per CU, at least one register sweep each
-    int64_t chunk = (N + 1023) / 1024;
+    const int64_t sweep = static_cast<int64_t>(kTraceThreads) * vec;
+    int64_t chunk = (N + kTargetWorkgroups - 1) / kTargetWorkgroups;  // about one workgroup per CU
     chunk = (chunk + sweep - 1) / sweep * sweep;
-    return chunk < sweep ? sweep : chunk;
+    if (chunk < sweep) chunk = sweep;
+    const int64_t cap = (1ll << 31) / sweep * sweep;  // 32-bit partial counters
+    return chunk > cap ? cap : chunk;
 }
 
 static int validate_trace_args(const char* fn, int L, int64_t N, int E)
@@ -334,6 +385,16 @@ static int validate_trace_args(const char* fn, int L, int64_t N, int E)
     if (N < 0) return fail(EXF_ERR_BAD_SHAPE, "%s: N = %lld < 0", fn, static_cast<long long>(N));
     if (E < 1 || E > EXF_MAX_EXPERTS) return fail(EXF_ERR_BAD_SHAPE, "%s: E = %d outside [1,%d]", fn, E, EXF_MAX_EXPERTS);
     if (N >= (1ll << 40)) return fail(EXF_ERR_BAD_SHAPE, "%s: N must be below 2^40", fn);
+    return EXF_OK;
+}
+
+template <typename Kern>
+static int allow_large_lds(Kern kern, size_t bytes, const char* what)
+{
+    if (bytes <= 64 * 1024) return EXF_OK;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         static_cast<int>(bytes));
+    if (err != hipSuccess) return fail(EXF_ERR_HIP, "%s: LDS attribute: %s", what, hipGetErrorString(err));
     return EXF_OK;
 }
 
@@ -368,19 +429,22 @@ extern "C" int affinity_histogram(const int32_t* trace, int L, int64_t N, int E,
     if (p.C > 0) {
         const int c_pad = (p.C + kXcds - 1) / kXcds * kXcds;
         const unsigned grid = static_cast<unsigned>(c_pad) * p.Q;
-        const size_t lds = (static_cast<size_t>(p.copies) * p.g * E * E + static_cast<size_t>(p.g) * E + E + 1) * sizeof(uint32_t);
-        if (p.vec == 4)
-            hipLaunchKernelGGL(affinity_partial_kernel<4>, dim3(grid), dim3(kAffThreads), lds, s, trace, L, N, E, p.g, p.Q, p.copies,
-                               p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid);
-        else
-            hipLaunchKernelGGL(affinity_partial_kernel<1>, dim3(grid), dim3(kAffThreads), lds, s, trace, L, N, E, p.g, p.Q, p.copies,
-                               p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid);
+        const size_t lds = (static_cast<size_t>(p.copies) * p.g * p.words + static_cast<size_t>(p.g) * E + E + 1) * sizeof(uint32_t);
+        if (p.vec == 4) {
+            if (int rc = allow_large_lds(affinity_partial_kernel<4>, lds, "affinity_histogram")) return rc;
+            hipLaunchKernelGGL(affinity_partial_kernel<4>, dim3(grid), dim3(kTraceThreads), lds, s, trace, L, N, E, p.g, p.Q, p.copies,
+                               p.words, p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid);
+        } else {
+            if (int rc = allow_large_lds(affinity_partial_kernel<1>, lds, "affinity_histogram")) return rc;
+            hipLaunchKernelGGL(affinity_partial_kernel<1>, dim3(grid), dim3(kTraceThreads), lds, s, trace, L, N, E, p.g, p.Q, p.copies,
+                               p.words, p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid);
+        }
     }
     if (L > 1)
-        hipLaunchKernelGGL(affinity_finalize_kernel, dim3(static_cast<unsigned>((L - 1) * E)), dim3(kWave), 0, s, part_counts,
-                           part_orphan_next, p.C, L, E, counts, loads, cond_prob);
+        hipLaunchKernelGGL(affinity_finalize_kernel, dim3(static_cast<unsigned>((L - 1) * E)), dim3(256), 0, s, part_counts,
+                           part_orphan_next, p.C, L, E, p.words, counts, loads, cond_prob);
     if (loads != nullptr || n_invalid != nullptr)
-        hipLaunchKernelGGL(affinity_tail_kernel, dim3(1), dim3(kWave), 0, s, part_orphan_last, part_invalid, p.C, p.Q, L, E, counts,
+        hipLaunchKernelGGL(affinity_tail_kernel, dim3(1), dim3(1024), 0, s, part_orphan_last, part_invalid, p.C, p.Q, L, E, counts,
                            loads, n_invalid);
     return check_launch("affinity_histogram");
 }
@@ -414,10 +478,13 @@ extern "C" int placement_locality(const int32_t* trace, const int32_t* placement
     uint32_t* part = static_cast<uint32_t*>(workspace);
     if (C > 0) {
         const size_t lds = (static_cast<size_t>(L) * E + (L - 1)) * sizeof(int32_t);
-        if (vec == 4)
-            hipLaunchKernelGGL(locality_partial_kernel<4>, dim3(C), dim3(kLocThreads), lds, s, trace, placement, L, N, E, chunk, part);
-        else
-            hipLaunchKernelGGL(locality_partial_kernel<1>, dim3(C), dim3(kLocThreads), lds, s, trace, placement, L, N, E, chunk, part);
+        if (vec == 4) {
+            if (int rc = allow_large_lds(locality_partial_kernel<4>, lds, "placement_locality")) return rc;
+            hipLaunchKernelGGL(locality_partial_kernel<4>, dim3(C), dim3(kTraceThreads), lds, s, trace, placement, L, N, E, chunk, part);
+        } else {
+            if (int rc = allow_large_lds(locality_partial_kernel<1>, lds, "placement_locality")) return rc;
+            hipLaunchKernelGGL(locality_partial_kernel<1>, dim3(C), dim3(kTraceThreads), lds, s, trace, placement, L, N, E, chunk, part);
+        }
     }
     hipLaunchKernelGGL(locality_finalize_kernel, dim3(L - 1), dim3(kWave), 0, s, part, C, L - 1, local_per_pair);
     return check_launch("placement_locality");

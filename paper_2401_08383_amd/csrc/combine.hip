@@ -1,69 +1,87 @@
 // moe_combine: out[t] = sum_j topk_w[t][j] * y_sorted[sorted_of_src[t*k+j]], fp32 accumulation,
-// one rounding to the storage type.  A pure stream: every thread owns 16-byte chunks of output
-// rows; all the loads of an unrolled group are issued before the arithmetic.
+// one rounding to the storage type.  A pure stream over the rows.
 #include "common.hpp"
 
 namespace exf {
 
+// Rows are handled in batches of `row_batch` (at most 16) consecutive output rows per wavefront: the lanes first
+// fetch the batch's source positions and weights with one coalesced load each (so the
+// data-dependent addresses are known before any row data is requested), then the wavefront
+// streams the batch as a flat sequence of 16-byte chunks, four per lane in flight.
 template <int K, bool BF16>
 __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ y, const int32_t* __restrict__ sorted_of_src,
                                                        const float* __restrict__ topk_w, int64_t T, int vec_per_row, int64_t A,
-                                                       uint4* __restrict__ out)
+                                                       int row_batch, uint4* __restrict__ out)
 {
     constexpr int U = 4;
-    const int64_t total = T * vec_per_row;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-    for (int64_t i0 = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i0 < total; i0 += U * stride) {
-        uint4 v[U][K];
-        float w[U][K];
+    const int lane = lane_id();
+    const int64_t n_batches = (T + row_batch - 1) / row_batch;
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * (blockDim.x / kWave);
+    const float rcp = 1.0f / static_cast<float>(vec_per_row);
+    for (int64_t b = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave; b < n_batches; b += n_waves) {
+        const int64_t t0 = b * row_batch;
+        const int rows = static_cast<int>(min(static_cast<int64_t>(row_batch), T - t0));
+        int pos[K];
+        float wt[K];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = i0 + u * stride;
-            const bool live = i < total;
-            const int64_t t = live ? i / vec_per_row : 0;
-            const int c = live ? static_cast<int>(i - t * vec_per_row) : 0;
-#pragma unroll
-            for (int j = 0; j < K; ++j) {
-                const int s = live ? sorted_of_src[t * K + j] : -1;
-                const bool ok = s >= 0 && s < A;
-                w[u][j] = ok ? topk_w[t * K + j] : 0.0f;
-                v[u][j] = ok ? y[static_cast<int64_t>(s) * vec_per_row + c] : uint4{0u, 0u, 0u, 0u};
-            }
+        for (int j = 0; j < K; ++j) {  // lane r < rows holds the K assignments of token t0 + r
+            const int s = lane < rows ? sorted_of_src[(t0 + lane) * K + j] : -1;
+            const bool ok = s >= 0 && s < A;
+            pos[j] = ok ? s : -1;
+            wt[j] = ok ? topk_w[(t0 + lane) * K + j] : 0.0f;
         }
+        const int total = rows * vec_per_row;
+        for (int c0 = lane; c0 < total; c0 += kWave * U) {
+            uint4 v[U][K];
+            float w[U][K];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = i0 + u * stride;
-            if (i >= total) continue;
-            uint4 r;
-            if constexpr (BF16) {
-                float acc[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
-#pragma unroll
-                for (int j = 0; j < K; ++j) {
-                    const uint32_t p[4] = {v[u][j].x, v[u][j].y, v[u][j].z, v[u][j].w};
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        acc[2 * q] = fmaf(w[u][j], __uint_as_float(p[q] << 16), acc[2 * q]);
-                        acc[2 * q + 1] = fmaf(w[u][j], __uint_as_float(p[q] & 0xffff0000u), acc[2 * q + 1]);
-                    }
-                }
-                r.x = pack_bf16x2(acc[0], acc[1]);
-                r.y = pack_bf16x2(acc[2], acc[3]);
-                r.z = pack_bf16x2(acc[4], acc[5]);
-                r.w = pack_bf16x2(acc[6], acc[7]);
-            } else {
-                float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * kWave;
+                const bool live = c < total;
+                const int r = live ? row_of_chunk(c, vec_per_row, rcp) : 0;
+                const int col = c - r * vec_per_row;
 #pragma unroll
                 for (int j = 0; j < K; ++j) {
-                    acc[0] = fmaf(w[u][j], __uint_as_float(v[u][j].x), acc[0]);
-                    acc[1] = fmaf(w[u][j], __uint_as_float(v[u][j].y), acc[1]);
-                    acc[2] = fmaf(w[u][j], __uint_as_float(v[u][j].z), acc[2]);
-                    acc[3] = fmaf(w[u][j], __uint_as_float(v[u][j].w), acc[3]);
+                    const int s = __shfl(pos[j], r, kWave);
+                    w[u][j] = __shfl(wt[j], r, kWave);
+                    v[u][j] = (live && s >= 0) ? load_stream16(y + static_cast<int64_t>(s) * vec_per_row + col) : uint4{0u, 0u, 0u, 0u};
                 }
-                r = uint4{__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]), __float_as_uint(acc[3])};
             }
-            out[i] = r;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * kWave;
+                if (c >= total) continue;
+                uint4 r;
+                if constexpr (BF16) {
+                    float acc[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < K; ++j) {
+                        const uint32_t p[4] = {v[u][j].x, v[u][j].y, v[u][j].z, v[u][j].w};
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            acc[2 * q] = fmaf(w[u][j], __uint_as_float(p[q] << 16), acc[2 * q]);
+                            acc[2 * q + 1] = fmaf(w[u][j], __uint_as_float(p[q] & 0xffff0000u), acc[2 * q + 1]);
+                        }
+                    }
+                    r.x = pack_bf16x2(acc[0], acc[1]);
+                    r.y = pack_bf16x2(acc[2], acc[3]);
+                    r.z = pack_bf16x2(acc[4], acc[5]);
+                    r.w = pack_bf16x2(acc[6], acc[7]);
+                } else {
+                    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                    for (int j = 0; j < K; ++j) {
+                        acc[0] = fmaf(w[u][j], __uint_as_float(v[u][j].x), acc[0]);
+                        acc[1] = fmaf(w[u][j], __uint_as_float(v[u][j].y), acc[1]);
+                        acc[2] = fmaf(w[u][j], __uint_as_float(v[u][j].z), acc[2]);
+                        acc[3] = fmaf(w[u][j], __uint_as_float(v[u][j].w), acc[3]);
+                    }
+                    r = uint4{__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+                }
+                store_stream16(out + t0 * vec_per_row + c, r);
+            }
         }
     }
 }
@@ -90,23 +108,23 @@ extern "C" int moe_combine(const void* y_sorted, const int32_t* sorted_of_src, c
     EXF_REQUIRE_ALIGNED(out);
     const int vec_per_row = d / gran;
     const int64_t A = T * k;
-    const int64_t total = T * vec_per_row;
-    int64_t blocks = (total + 256 * 4 - 1) / (256 * 4);
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    const int row_batch = row_batch_for(T);
+    int64_t blocks = ((T + row_batch - 1) / row_batch + 3) / 4;  // four wavefronts (row batches) per workgroup
+    if (blocks > kStreamWorkgroups) blocks = kStreamWorkgroups;
     const dim3 grid(static_cast<unsigned>(blocks)), block(256);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint4* y = static_cast<const uint4*>(y_sorted);
     uint4* o = static_cast<uint4*>(out);
     if (dt == EXF_BF16) {
         if (k == 1)
-            hipLaunchKernelGGL((combine_kernel<1, true>), grid, block, 0, s, y, sorted_of_src, topk_w, T, vec_per_row, A, o);
+            hipLaunchKernelGGL((combine_kernel<1, true>), grid, block, 0, s, y, sorted_of_src, topk_w, T, vec_per_row, A, row_batch, o);
         else
-            hipLaunchKernelGGL((combine_kernel<2, true>), grid, block, 0, s, y, sorted_of_src, topk_w, T, vec_per_row, A, o);
+            hipLaunchKernelGGL((combine_kernel<2, true>), grid, block, 0, s, y, sorted_of_src, topk_w, T, vec_per_row, A, row_batch, o);
     } else {
         if (k == 1)
-            hipLaunchKernelGGL((combine_kernel<1, false>), grid, block, 0, s, y, sorted_of_src, topk_w, T, vec_per_row, A, o);
+            hipLaunchKernelGGL((combine_kernel<1, false>), grid, block, 0, s, y, sorted_of_src, topk_w, T, vec_per_row, A, row_batch, o);
         else
-            hipLaunchKernelGGL((combine_kernel<2, false>), grid, block, 0, s, y, sorted_of_src, topk_w, T, vec_per_row, A, o);
+            hipLaunchKernelGGL((combine_kernel<2, false>), grid, block, 0, s, y, sorted_of_src, topk_w, T, vec_per_row, A, row_batch, o);
     }
     return check_launch("moe_combine");
 }

@@ -56,6 +56,42 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return u;
 }
 
+// 16-byte streaming accesses: data that is touched once should not displace reusable lines.
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_v;
+__device__ __forceinline__ uint4 load_stream16(const uint4* p)
+{
+    const u32x4_v v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_v*>(p));
+    return uint4{v[0], v[1], v[2], v[3]};
+}
+__device__ __forceinline__ void store_stream16(uint4* p, uint4 x)
+{
+    const u32x4_v v = {x.x, x.y, x.z, x.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_v*>(p));
+}
+
+// Launch width of the pure streaming kernels: a grid-stride loop over about two workgroups per
+// CU sustained the highest HBM rate when measured (many more workgroups were slower).
+constexpr int kStreamWorkgroups = 512;
+
+// Row batches of the gather / combine streams (see combine.hip): rows per wavefront batch, chosen
+// so that about 2048 wavefronts have work (a short batch keeps a small problem parallel, a long
+// one amortises the index fetch), and the row a flat chunk index falls in: c / vec_per_row
+// through a float reciprocal with one correction step (c < 2^24).
+inline int row_batch_for(int64_t rows)
+{
+    int b = 16;
+    while (b > 1 && rows / b < 2048) b >>= 1;
+    return b;
+}
+__device__ __forceinline__ int row_of_chunk(int c, int vec_per_row, float rcp)
+{
+    int q = static_cast<int>(static_cast<float>(c) * rcp);
+    const int r = c - q * vec_per_row;
+    if (r < 0) q -= 1;
+    else if (r >= vec_per_row) q += 1;
+    return q;
+}
+
 __device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & (kWave - 1); }
 
 template <typename T>

@@ -112,31 +112,41 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     }
 }
 
-// 16-byte chunks of the kept rows; `vec_per_row` = row bytes / 16.
+// x_sorted[s] = x[src_of_sorted[s] / k] for the kept rows, in batches of `row_batch` (at most 16) sorted rows per
+// wavefront: the lanes fetch the batch's source rows first, then the wavefront streams the batch
+// as a flat sequence of 16-byte chunks (`vec_per_row` = row bytes / 16), four per lane in flight.
 __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ src_of_sorted,
                                                                const int32_t* __restrict__ expert_offsets, int E_local, int k,
-                                                               int vec_per_row, int64_t A, uint4* __restrict__ x_sorted)
+                                                               int vec_per_row, int64_t A, int row_batch, uint4* __restrict__ x_sorted)
 {
+    constexpr int U = 4;
+    const int lane = lane_id();
     const int64_t kept = min(static_cast<int64_t>(max(expert_offsets[E_local], 0)), A);
-    const int64_t total = kept * vec_per_row;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-    int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < total; i += 4 * stride) {
-        uint4 v[4];
+    const int64_t n_batches = (kept + row_batch - 1) / row_batch;
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * (blockDim.x / kWave);
+    const float rcp = 1.0f / static_cast<float>(vec_per_row);
+    for (int64_t b = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave; b < n_batches; b += n_waves) {
+        const int64_t s0 = b * row_batch;
+        const int rows = static_cast<int>(min(static_cast<int64_t>(row_batch), kept - s0));
+        const int src_row = lane < rows ? src_of_sorted[s0 + lane] / k : 0;
+        const int total = rows * vec_per_row;
+        for (int c0 = lane; c0 < total; c0 += kWave * U) {
+            uint4 v[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t j = i + u * stride;
-            const int64_t s = j / vec_per_row;
-            const int c = static_cast<int>(j - s * vec_per_row);
-            v[u] = x[static_cast<int64_t>(src_of_sorted[s] / k) * vec_per_row + c];
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * kWave;
+                const bool live = c < total;
+                const int r = live ? row_of_chunk(c, vec_per_row, rcp) : 0;
+                const int col = c - r * vec_per_row;
+                const int t = __shfl(src_row, r, kWave);
+                v[u] = live ? load_stream16(x + static_cast<int64_t>(t) * vec_per_row + col) : uint4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * kWave;
+                if (c < total) store_stream16(x_sorted + s0 * vec_per_row + c, v[u]);
+            }
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) x_sorted[i + u * stride] = v[u];
-    }
-    for (; i < total; i += stride) {
-        const int64_t s = i / vec_per_row;
-        const int c = static_cast<int>(i - s * vec_per_row);
-        x_sorted[i] = x[static_cast<int64_t>(src_of_sorted[s] / k) * vec_per_row + c];
     }
 }
 
@@ -197,12 +207,12 @@ extern "C" int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_
                            E_local, block_counts, expert_offsets, src_of_sorted, sorted_of_src);
         if (x_sorted != nullptr) {
             const int vec_per_row = d * (dt == EXF_BF16 ? 2 : 4) / 16;
-            const int64_t vecs = A * vec_per_row;
-            int64_t blocks = (vecs + 256 * 4 - 1) / (256 * 4);
-            if (blocks > 256 * 16) blocks = 256 * 16;
+            const int row_batch = row_batch_for(A);
+            int64_t blocks = ((A + row_batch - 1) / row_batch + 3) / 4;  // four wavefronts (row batches) per workgroup
+            if (blocks > kStreamWorkgroups) blocks = kStreamWorkgroups;
             if (blocks < 1) blocks = 1;
             hipLaunchKernelGGL(dispatch_gather_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
-                               static_cast<const uint4*>(x), src_of_sorted, expert_offsets, E_local, k, vec_per_row, A,
+                               static_cast<const uint4*>(x), src_of_sorted, expert_offsets, E_local, k, vec_per_row, A, row_batch,
                                static_cast<uint4*>(x_sorted));
         }
     }

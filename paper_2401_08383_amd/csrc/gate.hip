@@ -282,6 +282,160 @@ __global__ __launch_bounds__(NW * 64) void gate_bf16_kernel(const bf16_t* __rest
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// bf16 gate with W_gate resident in LDS (used whenever the padded weight fits): a persistent
+// workgroup copies W_gate into LDS once, laid out so that the 16 lanes of an MFMA row group
+// read 256 contiguous bytes; after that every wavefront streams its own 16-token tiles over the
+// full reduction dimension - x is read from HBM exactly once, there is no cross-wavefront
+// reduction and no barrier in the loop.  A token's logits end up in 4 lanes (l, l^16, l^32,
+// l^48), so softmax and top-k need two shuffle steps.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void pick_better(float& v, int& i, float ov, int oi)
+{
+    if (ov > v || (ov == v && oi < i)) {
+        v = ov;
+        i = oi;
+    }
+}
+
+template <int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wg,
+                                                                    int64_t T, int d, int E, int k, int renormalize,
+                                                                    float* __restrict__ logits_out, int32_t* __restrict__ topk_idx,
+                                                                    float* __restrict__ topk_w)
+{
+    constexpr int EP = NT * 16;
+    extern __shared__ uint4 wlds[];  // [d/8][EP]: 16-byte piece c of expert e at wlds[c*EP + e]
+    const int chunks = d / 8;
+    const uint4* wg16 = reinterpret_cast<const uint4*>(wg);
+    for (int i = threadIdx.x; i < EP * chunks; i += WAVES * 64) {
+        const int e = i / chunks, c = i - e * chunks;
+        wlds[c * EP + e] = e < E ? wg16[static_cast<int64_t>(e) * chunks + c] : uint4{0u, 0u, 0u, 0u};
+    }
+    __syncthreads();
+
+    const int lane = lane_id();
+    const int wave = threadIdx.x / kWave;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int64_t n_tiles = (T + 15) / 16;
+    const int steps = (chunks + 3) / 4;
+    const bf16x8_t zero8 = {};
+    for (int64_t tile = static_cast<int64_t>(blockIdx.x) * WAVES + wave; tile < n_tiles; tile += static_cast<int64_t>(gridDim.x) * WAVES) {
+        const int64_t t = min(tile * 16 + r16, T - 1);
+        const bf16_t* xrow = x + t * d;
+        f32x4_t acc[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        constexpr int PF = 8;
+        for (int s0 = 0; s0 < steps; s0 += PF) {
+            bf16x8_t b[PF];
+            int cc[PF];
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {  // eight 16-byte loads of x in flight per lane
+                const int c = (s0 + u) * 4 + g;
+                const bool ok = c < chunks;
+                cc[u] = ok ? c : 0;
+                b[u] = *reinterpret_cast<const bf16x8_t*>(xrow + cc[u] * 8);
+                if (!ok) b[u] = zero8;
+            }
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const uint4 wv = wlds[cc[u] * EP + nt * 16 + r16];
+                    bf16x8_t a;
+                    __builtin_memcpy(&a, &wv, sizeof(a));
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[u], acc[nt], 0, 0, 0);
+                }
+            }
+        }
+        // this lane: token tile*16 + r16, experts nt*16 + 4g + v (ascending in (nt, v))
+        float l0 = -INFINITY;
+        int i0 = 2 * kWave;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int e = nt * 16 + 4 * g + v;
+                if (e < E) pick_better(l0, i0, acc[nt][v], e);
+            }
+        pick_better(l0, i0, __shfl_xor(l0, 16, kWave), __shfl_xor(i0, 16, kWave));
+        pick_better(l0, i0, __shfl_xor(l0, 32, kWave), __shfl_xor(i0, 32, kWave));
+        float l1 = -INFINITY;
+        int i1 = 2 * kWave;
+        if (k > 1) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int e = nt * 16 + 4 * g + v;
+                    if (e < E && e != i0) pick_better(l1, i1, acc[nt][v], e);
+                }
+            pick_better(l1, i1, __shfl_xor(l1, 16, kWave), __shfl_xor(i1, 16, kWave));
+            pick_better(l1, i1, __shfl_xor(l1, 32, kWave), __shfl_xor(i1, 32, kWave));
+        }
+        float se = 0.0f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (nt * 16 + 4 * g + v < E) se += expf(acc[nt][v] - l0);
+        se += __shfl_xor(se, 16, kWave);
+        se += __shfl_xor(se, 32, kWave);
+        const int64_t tok = tile * 16 + r16;
+        if (tok < T) {
+            if (logits_out != nullptr) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int e = nt * 16 + 4 * g + v;
+                        if (e < E) logits_out[tok * E + e] = acc[nt][v];
+                    }
+            }
+            if (g == 0) {
+                Route r;
+                r.i0 = i0;
+                r.i1 = i1;
+                route_weights(r, l0, l1, se, k, renormalize);
+                store_route(r, tok, k, topk_idx, topk_w);
+            }
+        }
+    }
+}
+
+constexpr size_t kGateLdsLimit = 128 * 1024;
+
+template <int NT>
+static int launch_gate_bf16_lds(const void* x, const void* wg, int64_t T, int d, int E, int k, int renormalize, float* logits_out,
+                                int32_t* topk_idx, float* topk_w, hipStream_t stream)
+{
+    const size_t lds = static_cast<size_t>(NT) * 16 * d * 2;
+    const int64_t n_tiles = (T + 15) / 16;
+    // persistent workgroups, one per CU (more when the weight copy is small); 4 to 16 wavefronts
+    // each, chosen so that about 256 workgroups take part
+    const int per_cu = static_cast<int>(lds <= 32 * 1024 ? 4 : (lds <= 64 * 1024 ? 2 : 1));
+    const int waves = n_tiles >= 256 * 16 ? 16 : (n_tiles >= 256 * 8 ? 8 : 4);
+    int64_t blocks = (n_tiles + waves - 1) / waves;
+    if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+#define EXF_LAUNCH_GATE_LDS(W)                                                                                                   \
+    do {                                                                                                                        \
+        auto kern = gate_bf16_lds_kernel<NT, W>;                                                                                \
+        if (lds > 64 * 1024) {                                                                                                  \
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                 static_cast<int>(lds));                                                       \
+            if (err != hipSuccess) return fail(EXF_ERR_HIP, "moe_gate_topk: LDS attribute: %s", hipGetErrorString(err));         \
+        }                                                                                                                       \
+        hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(W * 64), lds, stream, static_cast<const bf16_t*>(x),  \
+                           static_cast<const bf16_t*>(wg), T, d, E, k, renormalize, logits_out, topk_idx, topk_w);              \
+    } while (0)
+    if (waves == 16) EXF_LAUNCH_GATE_LDS(16);
+    else if (waves == 8) EXF_LAUNCH_GATE_LDS(8);
+    else EXF_LAUNCH_GATE_LDS(4);
+#undef EXF_LAUNCH_GATE_LDS
+    return EXF_OK;
+}
+
 template <int MT, int NT, int NW>
 static void launch_gate_bf16(const void* x, const void* wg, int64_t T, int d, int E, int k, int renormalize,
                              float* logits_out, int32_t* topk_idx, float* topk_w, hipStream_t stream)
@@ -343,7 +497,20 @@ extern "C" int moe_gate_topk(const void* x, const void* w_gate, int64_t T, int d
                            static_cast<const float*>(x), static_cast<const float*>(w_gate), T, d, E, k, renormalize,
                            logits_out, topk_idx, topk_w);
     } else {
-        switch ((E + 15) / 16) {
+        const int nt = (E + 15) / 16;
+        // long batches: W_gate resident in LDS; short ones: the split-K kernel (more workgroups)
+        if (static_cast<size_t>(nt) * 16 * d * 2 <= kGateLdsLimit && T >= 16384) {
+            int rc = EXF_OK;
+            switch (nt) {
+                case 1: rc = launch_gate_bf16_lds<1>(x, w_gate, T, d, E, k, renormalize, logits_out, topk_idx, topk_w, s); break;
+                case 2: rc = launch_gate_bf16_lds<2>(x, w_gate, T, d, E, k, renormalize, logits_out, topk_idx, topk_w, s); break;
+                case 3: rc = launch_gate_bf16_lds<3>(x, w_gate, T, d, E, k, renormalize, logits_out, topk_idx, topk_w, s); break;
+                default: rc = launch_gate_bf16_lds<4>(x, w_gate, T, d, E, k, renormalize, logits_out, topk_idx, topk_w, s); break;
+            }
+            if (rc != EXF_OK) return rc;
+            return check_launch("moe_gate_topk");
+        }
+        switch (nt) {
             case 1: dispatch_gate_bf16<1>(x, w_gate, T, d, E, k, renormalize, logits_out, topk_idx, topk_w, s); break;
             case 2: dispatch_gate_bf16<2>(x, w_gate, T, d, E, k, renormalize, logits_out, topk_idx, topk_w, s); break;
             case 3: dispatch_gate_bf16<3>(x, w_gate, T, d, E, k, renormalize, logits_out, topk_idx, topk_w, s); break;

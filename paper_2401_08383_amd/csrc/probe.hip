@@ -14,9 +14,9 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict
     for (; i + 3 * stride < n; i += 4 * stride) {
         uint4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = src[i + u * stride];
+        for (int u = 0; u < 4; ++u) v[u] = load_stream16(src + i + u * stride);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) dst[i + u * stride] = v[u];
+        for (int u = 0; u < 4; ++u) store_stream16(dst + i + u * stride, v[u]);
     }
     for (; i < n; i += stride) dst[i] = src[i];
 }
@@ -56,7 +56,7 @@ extern "C" int exf_probe_copy(void* dst, const void* src, size_t bytes, void* st
     if (bytes % 16 != 0) return fail(EXF_ERR_BAD_SHAPE, "exf_probe_copy: bytes must be a multiple of 16");
     const int64_t n = static_cast<int64_t>(bytes / 16);
     int64_t blocks = (n + 256 * 4 - 1) / (256 * 4);
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks > kStreamWorkgroups) blocks = kStreamWorkgroups;
     hipLaunchKernelGGL(probe_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint4*>(src), static_cast<uint4*>(dst), n);
     return check_launch("exf_probe_copy");

@@ -35,6 +35,7 @@ GATE_CASES = [
     ("bf16", 512, 64, 8, 1, 0), ("bf16", 1000, 1024, 8, 1, 0), ("bf16", 300, 200, 17, 2, 1),
     ("bf16", 2500, 512, 32, 1, 0), ("bf16", 999, 1024, 64, 2, 1), ("bf16", 16, 4096, 64, 2, 1),
     ("bf16", 33000, 256, 48, 2, 0), ("bf16", 16500, 128, 64, 1, 0),
+    ("bf16", 17000, 64, 8, 1, 0), ("bf16", 20001, 200, 20, 2, 1), ("bf16", 70000, 32, 33, 1, 0),
 ]
 
 
