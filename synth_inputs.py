@@ -102,6 +102,23 @@ def expert_weights(cfg: MoEConfig, layer: int = 0, E_local: int | None = None):
     return w1, w2
 
 
+def device_expert_weights(cfg: MoEConfig, layer: int, device: str):
+    """W1 [E_local,f,d], W2 [E_local,d,f] ~ N(0,0.02) drawn ON THE DEVICE in the storage dtype (torch's
+    seeded device generator).  For configurations whose weights are too large to draw on the host
+    in reasonable time (the decode-shaped one: 17 GB per layer); checks copy back the experts they need."""
+    import torch
+
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    out = []
+    for tensor, shape in ((2, (cfg.E_local, cfg.f, cfg.d)), (3, (cfg.E_local, cfg.d, cfg.f))):
+        g = torch.Generator(device=device)
+        g.manual_seed(seed_for(cfg.index, tensor, layer))
+        w = torch.empty(shape, dtype=dt, device=device)
+        w.normal_(0.0, 0.02, generator=g)
+        out.append(w)
+    return out[0], out[1]
+
+
 # --------------------------------------------------------------------------- routing traces
 def zipf_loads(E: int, s: float) -> np.ndarray:
     p = 1.0 / np.arange(1, E + 1, dtype=np.float64) ** s

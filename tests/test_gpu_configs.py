@@ -1,0 +1,243 @@
+"""The five workload configurations at their full sizes, run through the same pre-allocated
+pipeline the benchmark times, and checked against the CPU oracle: integer outputs in full,
+floating-point outputs on sampled rows the oracle can evaluate one by one."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2401_08383_amd as exf
+import synth_inputs as syn
+from helpers import (DEV, GATE_TOL, OUT_RTOL, assert_close_max, assert_gate_close, check_routing_against_fp64, to_dev, to_host)
+from paper_2401_08383_amd.pipeline import AffinityRun, MoELayerRun
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _sample_rows(offsets, per_expert, seed):
+    """First, last and a few random rows of every non-empty expert."""
+    g = syn.rng(seed)
+    rows = []
+    for e in range(len(offsets) - 1):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi > lo:
+            pick = {lo, hi - 1}
+            pick.update(int(v) for v in g.integers(lo, hi, size=per_expert))
+            rows.extend(sorted(pick))
+    return np.array(rows, dtype=np.int64)
+
+
+def _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=None, expert_map=None, rows_per_expert=2, seed=0,
+                 weights_on_host=True):
+    """Compares one executed MoELayerRun with the oracle.  w1/w2: host fp32 arrays, or device
+    tensors from which only the sampled experts are copied back."""
+    dtype = cfg.dtype
+    k, E, E_local = cfg.k, cfg.E, cfg.E_local
+    idx = layer.topk_idx.cpu().numpy() if forced_idx is None else forced_idx
+    w = layer.topk_w.cpu().numpy()
+    if forced_idx is None:
+        logits64 = oracle.gate_logits(x, wg)
+        n_amb = check_routing_against_fp64(idx, logits64, k, GATE_TOL[dtype])
+        assert n_amb <= max(3, cfg.T // 500)
+        p = oracle.softmax(logits64)
+        w_ref = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+        if cfg.renormalize and k > 1:
+            w_ref = w_ref / w_ref.sum(axis=1, keepdims=True)
+        assert_gate_close(w, w_ref, GATE_TOL[dtype], "gate weights")
+    ref = oracle.dispatch(idx, expert_map, E, E_local)
+    kept = ref["kept"]
+    np.testing.assert_array_equal(layer.expert_counts.cpu().numpy(), ref["counts"])
+    np.testing.assert_array_equal(layer.expert_offsets.cpu().numpy(), ref["offsets"])
+    np.testing.assert_array_equal(layer.src_of_sorted.cpu().numpy()[:kept], ref["src_of_sorted"])
+    np.testing.assert_array_equal(layer.sorted_of_src.cpu().numpy(), ref["sorted_of_src"])
+    xs = to_host(layer.x_sorted)[:kept]
+    np.testing.assert_array_equal(xs, x[ref["src_of_sorted"] // k])
+    # expert FFN on sampled sorted rows
+    rows = _sample_rows(ref["offsets"], rows_per_expert, seed)
+    y = to_host(layer.y_sorted)
+    if weights_on_host:
+        y_ref = oracle.expert_ffn_rows(xs, ref["offsets"], w1, None, w2, None, 0, rows)
+    else:  # copy back only the experts that own sampled rows (one at a time)
+        y_ref = np.zeros((len(rows), cfg.d))
+        owner = np.searchsorted(ref["offsets"], rows, side="right") - 1
+        for e in np.unique(owner):
+            sel = np.nonzero(owner == e)[0]
+            w1e = w1[e].float().cpu().numpy()[None]
+            w2e = w2[e].float().cpu().numpy()[None]
+            lo = int(ref["offsets"][e])
+            off1 = np.array([0, int(ref["offsets"][e + 1]) - lo], dtype=np.int32)
+            y_ref[sel] = oracle.expert_ffn_rows(xs[lo:int(ref["offsets"][e + 1])], off1, w1e, None, w2e, None, 0, rows[sel] - lo)
+    scale = np.abs(y_ref).max()
+    assert np.abs(y[rows] - y_ref).max() <= OUT_RTOL[dtype] * scale, "expert FFN rows"
+    # combine on the tokens that own the sampled rows (from the GPU's own y_sorted, widened)
+    toks = np.unique(ref["src_of_sorted"][rows] // k)
+    out = to_host(layer.out)
+    inv = ref["sorted_of_src"].reshape(cfg.T, k)
+    out_ref = np.zeros((len(toks), cfg.d))
+    mag = np.zeros((len(toks), cfg.d))
+    for j in range(k):
+        pos = inv[toks, j]
+        ok = pos >= 0
+        term = w[toks[ok], j][:, None].astype(np.float64) * y[pos[ok]].astype(np.float64)
+        out_ref[ok] += term
+        mag[ok] += np.abs(term)
+    eps = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -22  # one rounding to storage after an fp32 sum of k terms
+    assert (np.abs(out[toks] - out_ref) <= eps * mag + 1e-30).all(), "combine"
+    return ref
+
+
+def _check_affinity(oracle, cfg, trace, placement):
+    aff = AffinityRun(torch.from_numpy(trace).to(DEV), torch.from_numpy(placement).to(DEV), cfg.trace_E, cfg.G)
+    aff.step()
+    counts, loads, n_inv = oracle.affinity_counts(trace, cfg.trace_E)
+    np.testing.assert_array_equal(aff.counts.cpu().numpy(), counts)
+    np.testing.assert_array_equal(aff.loads.cpu().numpy(), loads)
+    assert int(aff.n_invalid.cpu()) == n_inv == 0
+    prob = oracle.cond_prob(counts).astype(np.float32)
+    assert (np.abs(aff.cond_prob.cpu().numpy() - prob) <= np.spacing(prob)).all()
+    loc = aff.local_per_pair.cpu().numpy()
+    np.testing.assert_array_equal(loc, oracle.placement_locality(trace, placement))
+    np.testing.assert_array_equal(loc, oracle.placement_locality_from_counts(counts, placement))
+    return loc.sum() / (trace.shape[1] * (trace.shape[0] - 1))
+
+
+def test_config2_gpt_moe_350m(oracle):
+    cfg = syn.CONFIGS[2]
+    _say("config 2: T=8192 d=1024 f=4096 E=8 top-1 bf16")
+    x, wg = syn.tokens(cfg), syn.gate_weight(cfg)
+    w1, w2 = syn.expert_weights(cfg)
+    layer = MoELayerRun(to_dev(x, "bf16"), to_dev(wg, "bf16"), to_dev(w1, "bf16"), to_dev(w2, "bf16"), cfg.k, cfg.renormalize)
+    layer.step()
+    ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, rows_per_expert=6, seed=21)
+    assert ref["counts"].min() > 800  # the synthetic gate is roughly balanced, as trained models are
+    trace, perms = syn.config_trace(cfg)
+    frac = _check_affinity(oracle, cfg, trace, syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(2, 5)))
+    assert abs(frac - 1 / cfg.G) < 0.15  # few (88) hot transitions: a wide band around 1/G
+    aligned = _check_affinity(oracle, cfg, trace, syn.aligned_placement(perms, cfg.trace_E, cfg.G))
+    assert aligned > 0.7  # a placement that follows the planted affinity keeps most tokens local
+
+
+def test_config3_xl_skewed(oracle):
+    cfg = syn.CONFIGS[3]
+    _say("config 3: T=16384 d=2048 f=8192 E=32 top-1 bf16, Zipf loads from the trace")
+    x, wg = syn.tokens(cfg), syn.gate_weight(cfg)
+    _say("  drawing expert weights (2 x 2.1 GB on the host)")
+    w1, w2 = syn.expert_weights(cfg)
+    trace, _ = syn.config_trace(cfg)
+    forced = trace[0].reshape(-1, 1).copy()
+    xd = to_dev(x, "bf16")
+    # the gate is checked on x as it stands; its probabilities at the forced experts weight the combine
+    idx_g, w_g, logits = exf.moe_gate_topk(xd, to_dev(wg, "bf16"), 1, False, want_logits=True)
+    logits64 = oracle.gate_logits(x, wg)
+    check_routing_against_fp64(idx_g.cpu().numpy(), logits64, 1, GATE_TOL["bf16"])
+    lg = logits.cpu().numpy().astype(np.float64)
+    pg = np.exp(lg - lg.max(axis=1, keepdims=True))
+    pg /= pg.sum(axis=1, keepdims=True)
+    forced_w = np.take_along_axis(pg, forced.astype(np.int64), axis=1).astype(np.float32)
+    layer = MoELayerRun(xd, to_dev(wg, "bf16"), to_dev(w1, "bf16"), to_dev(w2, "bf16"), 1, False,
+                        topk_idx=torch.from_numpy(forced).to(DEV))
+    layer.topk_w.copy_(torch.from_numpy(forced_w))
+    layer.dispatch()
+    layer.ffn()
+    layer.combine()
+    _say("  oracle on sampled rows")
+    ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=forced, rows_per_expert=1, seed=31)
+    assert ref["counts"].max() > 10 * max(1, ref["counts"].min())  # skewed loads
+    _check_affinity(oracle, cfg, trace, syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(3, 5)))
+
+
+def test_config4_one_gpu_share(oracle):
+    cfg = syn.CONFIGS[4]
+    _say("config 4: T=32768 d=1024 f=4096, 8 local of 64 experts, bf16; 24 x 1M trace")
+    x, wg = syn.tokens(cfg), syn.gate_weight(cfg)
+    w1, w2 = syn.expert_weights(cfg)
+    idx, expert_map = syn.local_routing(cfg, syn.seed_for(4, 4, 1))
+    xd, wgd = to_dev(x, "bf16"), to_dev(wg, "bf16")
+    layer = MoELayerRun(xd, wgd, to_dev(w1, "bf16"), to_dev(w2, "bf16"), 1, False, expert_map=torch.from_numpy(expert_map).to(DEV),
+                        topk_idx=torch.from_numpy(idx).to(DEV))
+    layer.gate()  # the shared gate over all 64 experts on the tokens this GPU holds
+    logits64 = oracle.gate_logits(x, wg)
+    idx_gate = layer.topk_idx.cpu().numpy()
+    check_routing_against_fp64(idx_gate, logits64, 1, GATE_TOL["bf16"])
+    w_ref = np.take_along_axis(oracle.softmax(logits64), idx_gate.astype(np.int64), axis=1)
+    assert_gate_close(layer.topk_w.cpu().numpy(), w_ref, GATE_TOL["bf16"], "gate weights")
+    layer.dispatch()  # post-exchange share: every token is routed to one of the 8 resident experts
+    layer.ffn()
+    layer.combine()
+    ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=idx, expert_map=expert_map, rows_per_expert=3, seed=41)
+    assert ref["kept"] == cfg.T
+    # the same layer fed with the gate's own routing: 7 of 8 tokens belong to other GPUs and are dropped here
+    layer2 = MoELayerRun(xd, wgd, layer.w1, layer.w2, 1, False, expert_map=layer.expert_map)
+    layer2.step()
+    ref2 = _check_layer(oracle, cfg, layer2, x, wg, w1, w2, expert_map=expert_map, rows_per_expert=2, seed=42)
+    assert 0 < ref2["kept"] < cfg.T // 4
+    dropped = ref2["sorted_of_src"] < 0
+    assert (to_host(layer2.out)[dropped] == 0).all()
+    _say("  affinity on the 24 x 1M trace")
+    trace, _ = syn.config_trace(cfg)
+    frac = _check_affinity(oracle, cfg, trace, syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(4, 5)))
+    assert abs(frac - 1 / cfg.G) < 0.03  # without placement optimisation any GPU is equally likely
+
+
+def test_config5_decode_top2(oracle):
+    cfg = syn.CONFIGS[5]
+    _say("config 5: T=256 d=4096 f=16384 E=64 top-2 renormalised, 8 layers with distinct weights (137 GB)")
+    free, _ = torch.cuda.mem_get_info()
+    layers = cfg.layers if free > 150e9 else 2  # the weights of all 8 layers need 137 GB of HBM
+    runs = []
+    for l in range(layers):
+        x, wg = syn.tokens(cfg, l), syn.gate_weight(cfg, l)
+        w1, w2 = syn.device_expert_weights(cfg, l, DEV)
+        runs.append((x, wg, w1, w2, MoELayerRun(to_dev(x, "bf16"), to_dev(wg, "bf16"), w1, w2, cfg.k, cfg.renormalize)))
+    for r in runs:  # consecutive layers back to back on one stream, no host synchronisation
+        r[4].step()
+    torch.cuda.synchronize()
+    for l, (x, wg, w1, w2, layer) in enumerate(runs):
+        _say(f"  layer {l}: oracle on sampled rows")
+        w = layer.topk_w.cpu().numpy()
+        np.testing.assert_allclose(w.sum(axis=1), 1.0, rtol=1e-6)  # renormalised top-2 gates
+        g = syn.rng(50 + l)
+        ref = oracle.dispatch(layer.topk_idx.cpu().numpy(), None, cfg.E, cfg.E_local)
+        # sampled rows from two random non-empty experts only (each needs 2 x 256 MB of weights on the host)
+        nonempty = np.nonzero(ref["counts"] > 0)[0]
+        keep = set(g.choice(nonempty, size=2, replace=False).tolist())
+        offs = ref["offsets"]
+        rows = np.array([int(offs[e]) for e in sorted(keep)] + [int(offs[e + 1]) - 1 for e in sorted(keep)], dtype=np.int64)
+        _check_layer_rows(oracle, cfg, layer, x, wg, w1, w2, rows)
+
+
+def _check_layer_rows(oracle, cfg, layer, x, wg, w1_dev, w2_dev, rows):
+    """Like _check_layer, for device-resident weights and an explicit list of sorted rows."""
+    k, E = cfg.k, cfg.E
+    idx = layer.topk_idx.cpu().numpy()
+    w = layer.topk_w.cpu().numpy()
+    logits64 = oracle.gate_logits(x, wg)
+    check_routing_against_fp64(idx, logits64, k, GATE_TOL["bf16"])
+    p = oracle.softmax(logits64)
+    w_ref = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+    w_ref = w_ref / w_ref.sum(axis=1, keepdims=True)
+    assert_gate_close(w, w_ref, GATE_TOL["bf16"], "gate weights")
+    ref = oracle.dispatch(idx, None, E, cfg.E_local)
+    kept = ref["kept"]
+    assert kept == cfg.T * k
+    np.testing.assert_array_equal(layer.expert_offsets.cpu().numpy(), ref["offsets"])
+    np.testing.assert_array_equal(layer.src_of_sorted.cpu().numpy(), ref["src_of_sorted"])
+    np.testing.assert_array_equal(layer.sorted_of_src.cpu().numpy(), ref["sorted_of_src"])
+    xs = to_host(layer.x_sorted)
+    np.testing.assert_array_equal(xs, x[ref["src_of_sorted"] // k])
+    y = to_host(layer.y_sorted)
+    owner = np.searchsorted(ref["offsets"], rows, side="right") - 1
+    for e in np.unique(owner):
+        sel = rows[owner == e]
+        lo, hi = int(ref["offsets"][e]), int(ref["offsets"][e + 1])
+        w1e = w1_dev[e].float().cpu().numpy()[None]
+        w2e = w2_dev[e].float().cpu().numpy()[None]
+        y_ref = oracle.expert_ffn_rows(xs[lo:hi], np.array([0, hi - lo], dtype=np.int32), w1e, None, w2e, None, 0, sel - lo)
+        assert np.abs(y[sel] - y_ref).max() <= OUT_RTOL["bf16"] * np.abs(y_ref).max(), f"expert {e} FFN rows"
+    # combine: every token, from the GPU's own y_sorted
+    out_ref = oracle.combine(y, ref["sorted_of_src"], w)
+    mag = oracle.combine(np.abs(y), ref["sorted_of_src"], np.abs(w))
+    assert (np.abs(to_host(layer.out) - out_ref) <= 2.0 ** -8 * mag + 1e-30).all(), "combine"
