@@ -7,6 +7,9 @@ gate+top-k -> dispatch -> grouped expert FFN -> combine, then affinity_histogram
 placement_locality over the configuration's 12-layer x 8192-token routing trace.
 Inputs are resident in HBM before the timed region; no allocation happens inside it.
 
+`--config N` times another of the five workload configurations the same way (the decode-shaped
+one runs its 8 consecutive layers per step and reports the weight-streaming HBM roofline).
+
 Prints ONE JSON line: tokens/s of the whole step, the roofline of the dominant kernel (the
 grouped expert GEMM, measured with HIP events on the launch stream), per-entry-point timings,
 HBM-bound entry points at the larger shapes of the one-GPU-share configuration, achieved copy
@@ -127,6 +130,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="workload configuration (default 2: the one the headline metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel and large-shape measurements")
     args = ap.parse_args()
@@ -146,46 +151,97 @@ def main():
     dev = "cuda:0"
     lib = B.lib()
 
-    cfg = syn.CONFIGS[2]
-    x_h, wg_h = syn.tokens(cfg), syn.gate_weight(cfg)
-    w1_h, w2_h = syn.expert_weights(cfg)
-    trace_h, _ = syn.config_trace(cfg)
-    pl_h = syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(cfg.index, 5))
+    cfg = syn.CONFIGS[args.config]
+    bf16 = cfg.dtype == "bf16"
 
-    def dev_bf16(a):
-        return torch.from_numpy(a).to(torch.bfloat16).to(dev)
+    def to_device(a):
+        t = torch.from_numpy(a)
+        return (t.to(torch.bfloat16) if bf16 else t).to(dev)
 
-    layer = MoELayerRun(dev_bf16(x_h), dev_bf16(wg_h), dev_bf16(w1_h), dev_bf16(w2_h), cfg.k, cfg.renormalize)
-    aff = AffinityRun(torch.from_numpy(trace_h).to(dev), torch.from_numpy(pl_h).to(dev), cfg.trace_E, cfg.G)
+    # ---- the workload: one MoELayerRun per consecutive layer, plus the affinity part ------------
+    layers = []
+    host = None  # host copies of layer 0 for the CPU baseline (benchmark configuration only)
+    for l in range(cfg.layers):
+        x_h, wg_h = syn.tokens(cfg, l), syn.gate_weight(cfg, l)
+        if cfg.index == 5:
+            w1_d, w2_d = syn.device_expert_weights(cfg, l, dev)  # 17 GB per layer: drawn on the device
+        else:
+            w1_h, w2_h = syn.expert_weights(cfg, l)
+            w1_d, w2_d = to_device(w1_h), to_device(w2_h)
+            if l == 0 and cfg.index == 2:
+                host = (x_h, wg_h, w1_h, w2_h)
+        kwargs = {}
+        if cfg.index == 3:  # trace-driven (Zipf) routing: layer-0 column of the trace
+            tr3, _ = syn.config_trace(cfg)
+            kwargs["topk_idx"] = torch.from_numpy(tr3[0].reshape(-1, 1).copy()).to(dev)
+        if cfg.index == 4:  # this GPU's post-exchange share: 8 resident experts of 64
+            idx4_h, map4_h = syn.local_routing(cfg, syn.seed_for(4, 4, 1))
+            kwargs["topk_idx"] = torch.from_numpy(idx4_h).to(dev)
+            kwargs["expert_map"] = torch.from_numpy(map4_h).to(dev)
+        layers.append(MoELayerRun(to_device(x_h), to_device(wg_h), w1_d, w2_d, cfg.k, cfg.renormalize, **kwargs))
+    layer = layers[0]
+    aff = None
+    if cfg.trace_L > 0:
+        trace_h, _ = syn.config_trace(cfg)
+        pl_h = syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(cfg.index, 5))
+        aff = AffinityRun(torch.from_numpy(trace_h).to(dev), torch.from_numpy(pl_h).to(dev), cfg.trace_E, cfg.G)
 
     def step():
-        layer.step()
-        aff.step()
+        for lay in layers:
+            lay.step()
+        if aff is not None:
+            aff.step()
 
     for _ in range(args.warmup):
         step()
-    ffn_ev = [_events(2) for _ in range(args.steps)]
+    ffn_ev = [[_events(2) for _ in layers] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        layer.gate()
-        layer.dispatch()
-        ffn_ev[i][0].record()
-        layer.ffn()
-        ffn_ev[i][1].record()
-        layer.combine()
-        aff.step()
+        for j, lay in enumerate(layers):
+            lay.gate()
+            lay.dispatch()
+            ffn_ev[i][j][0].record()
+            lay.ffn()
+            ffn_ev[i][j][1].record()
+            lay.combine()
+        if aff is not None:
+            aff.step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
-    ffn_ms = float(np.mean([a.elapsed_time(b) for a, b in ffn_ev]))
+    ffn_ms = float(np.mean([a.elapsed_time(b) for step_ev in ffn_ev for a, b in step_ev]))
 
     A = cfg.T * cfg.k
     ffn_flops = 4.0 * A * cfg.d * cfg.f
-    achieved = ffn_flops / (ffn_ms * 1e-3) / 1e12
+    elem = 2 if bf16 else 4
+    achieved_tf = ffn_flops / (ffn_ms * 1e-3) / 1e12
+    if cfg.index == 5:
+        # weight-bandwidth bound: every expert that owns a row streams W1 and W2 once
+        ffn_bytes = 2.0 * cfg.E_local * cfg.d * cfg.f * elem + 2.0 * A * cfg.d * elem
+        achieved = ffn_bytes / (ffn_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "grouped_gemm_bf16_kernel (moe_expert_ffn: both contractions)", "achieved": achieved,
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                    "ms_per_launch": ffn_ms, "bytes_per_launch": ffn_bytes}
+    else:
+        roofline = {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel (moe_expert_ffn: both contractions)"
+                    if bf16 else "grouped_gemm_f32_kernel (moe_expert_ffn, fp32 vector ALU: latency-bound tiny case)",
+                    "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS if bf16 else 157.3, "unit": "TFLOP/s",
+                    "frac": achieved_tf / (PEAK_BF16_TFLOPS if bf16 else 157.3),
+                    "traffic": FFN_TRAFFIC_BYTES if cfg.index == 2 else None, "ms_per_launch": ffn_ms, "flops_per_launch": ffn_flops}
+    workloads = {
+        1: "configs[0] tiny fp32: d_model=64 d_ff=256 E=8 top-1 T=512; 2-layer x 512-token trace",
+        2: "configs[1] GPT-MoE-350M-shaped: d_model=1024 d_ff=4096 E=8 top-1 T=8192 bf16; affinity on a 12-layer x 8192-token "
+           "trace, placement G=4",
+        3: "configs[2] GPT-MoE-XL-shaped: d_model=2048 d_ff=8192 E=32 top-1 T=16384 bf16, Zipf(1.1) expert loads from the trace; "
+           "12-layer x 16384-token trace, G=8",
+        4: "configs[3] one GPU's share of E=64 (8 local experts): d_model=1024 d_ff=4096 T=32768 bf16; 24-layer x 1M-token trace, G=8",
+        5: "configs[4] decode-shaped: d_model=4096 d_ff=16384 E=64 top-2 renormalised T=256 bf16, 8 consecutive layers with "
+           "distinct weights (a step = all 8 layers)",
+    }
     result = {
         "metric": "MoE-layer tokens/s (gate+dispatch+expert FFN+combine+affinity statistic per step)",
-        "value": cfg.T / (ms_per_step * 1e-3),
+        "value": cfg.T * cfg.layers / (ms_per_step * 1e-3),  # token-layer passes per second (layers = 1 except for the decode shape)
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -194,16 +250,14 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": cfg.dtype,
         "data": "synthetic",
-        "config": {"workload": "configs[1] GPT-MoE-350M-shaped: d_model=1024 d_ff=4096 E=8 top-1 T=8192 bf16; "
-                               "affinity on a 12-layer x 8192-token trace, placement G=4",
-                   "tokens": cfg.T, "d_model": cfg.d, "d_ff": cfg.f, "experts": cfg.E, "top_k": cfg.k,
-                   "trace_layers": cfg.trace_L, "trace_tokens": cfg.trace_N},
-        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel (moe_expert_ffn: both contractions)",
-                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": FFN_TRAFFIC_BYTES, "ms_per_launch": ffn_ms, "flops_per_launch": ffn_flops},
+        "config": {"workload": workloads[cfg.index], "tokens": cfg.T, "d_model": cfg.d, "d_ff": cfg.f, "experts": cfg.E,
+                   "local_experts": cfg.E_local, "top_k": cfg.k, "layers_per_step": cfg.layers, "trace_layers": cfg.trace_L,
+                   "trace_tokens": cfg.trace_N},
+        "roofline": roofline,
     }
+    achieved = achieved_tf
 
     if not args.no_extra:
         # per-entry-point averages at the benchmark configuration
@@ -212,8 +266,9 @@ def main():
         per["dispatch_ms"] = _time_call(layer.dispatch, 50)
         per["ffn_ms"] = _time_call(layer.ffn, 30)
         per["combine_ms"] = _time_call(layer.combine, 50)
-        per["affinity_histogram_ms"] = _time_call(aff.histogram, 50)
-        per["placement_locality_ms"] = _time_call(aff.locality, 50)
+        if aff is not None:
+            per["affinity_histogram_ms"] = _time_call(aff.histogram, 50)
+            per["placement_locality_ms"] = _time_call(aff.locality, 50)
         layer_ms = per["gate_ms"] + per["dispatch_ms"] + per["ffn_ms"] + per["combine_ms"]
         per["layer_tokens_per_s"] = cfg.T / (layer_ms * 1e-3)
         result["per_call"] = per
@@ -230,8 +285,10 @@ def main():
         ms = _time_call(lambda: lib.exf_probe_mfma(wgs, iters, sink.data_ptr(), B._stream()), 5)
         mfma_tflops = wgs * 4 * 4 * iters * 32768.0 / (ms * 1e-3) / 1e12
         result["box"] = {"copy_GBps": copy_gbs, "mfma_loop_TFLOPs": mfma_tflops}
-        result["roofline"]["frac_of_measured_mfma_loop"] = achieved / mfma_tflops
+        if roofline["bound"] == "mfma" and bf16:
+            result["roofline"]["frac_of_measured_mfma_loop"] = achieved / mfma_tflops
 
+    if not args.no_extra and cfg.index == 2:
         # HBM-bound entry points at the shapes of the one-GPU-share configuration (rotating buffers)
         c4 = syn.CONFIGS[4]
         hbm = {}
@@ -278,8 +335,8 @@ def main():
                                      "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
         result["hbm_bound_calls_config4_shapes"] = hbm
 
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, x_h, wg_h, w1_h, w2_h, trace_h, pl_h)
+    if not args.no_cpu_baseline and host is not None:
+        result["cpu_baseline"] = cpu_baseline(cfg, host[0], host[1], host[2], host[3], trace_h, pl_h)
     else:
         result["cpu_baseline"] = None
 
