@@ -32,10 +32,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per moe_expert_ffn call at the benchmark configuration, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs scaled by the copy-kernel calibration (see profiles/); None
-# until measured.
-FFN_TRAFFIC_BYTES = None
+# HBM-side bytes per moe_expert_ffn call at the benchmark configuration, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch summed over the call's two launches), each
+# scaled by what the same counter reads for the 1 GiB copy probe (FETCH x2.000, WRITE x1.000):
+# (126681.4 + 138053.2) KiB x 2 + (65536 + 16384) KiB.  See profiles/bench_config2_hbm_traffic.txt.
+FFN_TRAFFIC_BYTES = int((126681.4 + 138053.2) * 2 * 1024 + (65536 + 16384) * 1024)
 
 
 def _events(n):
