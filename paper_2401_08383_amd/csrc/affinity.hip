@@ -14,7 +14,8 @@
 //             neighbouring pair groups is served by that XCD's L2.
 //   finalize: one wavefront per (pair, source expert) row sums the partials over the chunks
 //             into int64 counts, forms the row sum, the layer loads and the conditional
-//             probabilities; a last small kernel derives the loads of the final layer.
+//             probabilities; extra workgroups of the same launch derive the loads of the final layer
+//             and the invalid tally.
 //   Entries outside [0,E) are tallied; a transition touching one is not binned, but the valid
 //   end still counts towards its layer's load through small "orphan" histograms.
 //
@@ -218,80 +219,80 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
     if (threadIdx.x == 0) part_invalid[static_cast<size_t>(c) * Q + q] = *invalid_cnt;
 }
 
-// One workgroup of 256 threads per (pair l, source expert i): wavefront w sums the chunks
-// c = w, w+4, ... of bin (i, p = lane); the four partial sums meet in LDS.
+// Workgroups of 256 threads.  The first (L-1)*E take one (pair l, source expert i) row each:
+// wavefront w sums the chunks c = w, w+4, ... of bin (i, p = lane), the four partial sums meet in
+// LDS -> counts, row sum, load of (l, i), conditional probabilities.  The next E workgroups take one
+// expert p of the FINAL layer each: its load is the column sum of the last pair (taken from the
+// partials, so that no result of another workgroup is needed) plus the orphans.  The last workgroup
+// adds up the invalid tally.
 __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* __restrict__ part_counts,
-                                                                const uint32_t* __restrict__ part_orphan_next, int C, int L, int E,
+                                                                const uint32_t* __restrict__ part_orphan_next,
+                                                                const uint32_t* __restrict__ part_orphan_last,
+                                                                const uint32_t* __restrict__ part_invalid, int C, int Q, int L, int E,
                                                                 int words, int64_t* __restrict__ counts, int64_t* __restrict__ loads,
-                                                                float* __restrict__ cond_prob)
+                                                                float* __restrict__ cond_prob, int64_t* __restrict__ n_invalid)
 {
     __shared__ long long red[4][kWave];
     __shared__ long long orphan_red[4];
     const int pairs = L - 1;
-    const int l = blockIdx.x / E;
-    const int i = blockIdx.x % E;
     const int p = lane_id();
     const int w = threadIdx.x / kWave;
-    long long cnt = 0;
-    if (p < E) {
-        const int bin = i * E + p;
-        const int shift = (bin & 1) * 16;
-        const uint32_t* src = part_counts + static_cast<size_t>(l) * words + (bin >> 1);
-        const size_t step = static_cast<size_t>(pairs) * words;
-#pragma unroll 4
-        for (int c = w; c < C; c += 4) cnt += (src[c * step] >> shift) & 0xffffu;
-    }
-    long long orphan = 0;
-    for (int c = threadIdx.x; c < C; c += 256) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
-    orphan = wave_sum(orphan);
-    red[w][p] = cnt;
-    if (p == 0) orphan_red[w] = orphan;
-    __syncthreads();
-    if (w == 0) {
-        cnt = red[0][p] + red[1][p] + red[2][p] + red[3][p];
-        const long long row = wave_sum(cnt);
+    const int row_blocks = pairs * E;
+    if (static_cast<int>(blockIdx.x) < row_blocks) {
+        const int l = blockIdx.x / E;
+        const int i = blockIdx.x % E;
+        long long cnt = 0;
         if (p < E) {
-            const size_t o = (static_cast<size_t>(l) * E + i) * E + p;
-            counts[o] = cnt;
-            if (cond_prob != nullptr)
-                cond_prob[o] = row > 0 ? static_cast<float>(static_cast<double>(cnt) / static_cast<double>(row)) : 0.0f;
+            const int bin = i * E + p;
+            const int shift = (bin & 1) * 16;
+            const uint32_t* src = part_counts + static_cast<size_t>(l) * words + (bin >> 1);
+            const size_t step = static_cast<size_t>(pairs) * words;
+#pragma unroll 4
+            for (int c = w; c < C; c += 4) cnt += (src[c * step] >> shift) & 0xffffu;
         }
-        if (loads != nullptr && p == 0)
-            loads[static_cast<size_t>(l) * E + i] = row + orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
-    }
-}
-
-// loads of the final layer (column sums of the last pair + orphans) and the invalid tally:
-// one workgroup of 1024 threads, wavefront w takes the rows / chunks congruent to w mod 16.
-__global__ __launch_bounds__(1024) void affinity_tail_kernel(const uint32_t* __restrict__ part_orphan_last,
-                                                             const uint32_t* __restrict__ part_invalid, int C, int Q, int L, int E,
-                                                             const int64_t* __restrict__ counts, int64_t* __restrict__ loads,
-                                                             int64_t* __restrict__ n_invalid)
-{
-    __shared__ long long red[16][kWave];
-    __shared__ long long inv_red[16];
-    const int p = lane_id();
-    const int w = threadIdx.x / kWave;
-    long long s = 0;
-    if (loads != nullptr && p < E) {
-        if (L > 1)
-            for (int i = w; i < E; i += 16) s += counts[(static_cast<size_t>(L - 2) * E + i) * E + p];
-        for (int c = w; c < C; c += 16) s += part_orphan_last[static_cast<size_t>(c) * E + p];
-    }
-    long long inv = 0;
-    for (int i = threadIdx.x; i < C * Q; i += 1024) inv += part_invalid[i];
-    inv = wave_sum(inv);
-    red[w][p] = s;
-    if (p == 0) inv_red[w] = inv;
-    __syncthreads();
-    if (w == 0) {
-        long long t = 0, ti = 0;
-        for (int q = 0; q < 16; ++q) {
-            t += red[q][p];
-            ti += inv_red[q];
+        long long orphan = 0;
+        for (int c = threadIdx.x; c < C; c += 256) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
+        orphan = wave_sum(orphan);
+        red[w][p] = cnt;
+        if (p == 0) orphan_red[w] = orphan;
+        __syncthreads();
+        if (w == 0) {
+            cnt = red[0][p] + red[1][p] + red[2][p] + red[3][p];
+            const long long row = wave_sum(cnt);
+            if (p < E) {
+                const size_t o = (static_cast<size_t>(l) * E + i) * E + p;
+                counts[o] = cnt;
+                if (cond_prob != nullptr)
+                    cond_prob[o] = row > 0 ? static_cast<float>(static_cast<double>(cnt) / static_cast<double>(row)) : 0.0f;
+            }
+            if (loads != nullptr && p == 0)
+                loads[static_cast<size_t>(l) * E + i] = row + orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
         }
-        if (loads != nullptr && p < E) loads[static_cast<size_t>(L - 1) * E + p] = t;
-        if (n_invalid != nullptr && p == 0) *n_invalid = ti;
+    } else if (static_cast<int>(blockIdx.x) < row_blocks + E) {
+        if (loads == nullptr) return;
+        const int pe = blockIdx.x - row_blocks;  // expert of the final layer
+        long long s = 0;
+        if (pairs > 0) {  // column pe of the last pair: sum over chunks c and source experts i
+            const int total = C * E;
+            for (int j = threadIdx.x; j < total; j += 256) {
+                const int c = j / E, i = j - c * E;
+                const int bin = i * E + pe;
+                s += (part_counts[(static_cast<size_t>(c) * pairs + (pairs - 1)) * words + (bin >> 1)] >> ((bin & 1) * 16)) & 0xffffu;
+            }
+        }
+        for (int c = threadIdx.x; c < C; c += 256) s += part_orphan_last[static_cast<size_t>(c) * E + pe];
+        s = wave_sum(s);
+        if (p == 0) orphan_red[w] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) loads[static_cast<size_t>(L - 1) * E + pe] = orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
+    } else {
+        if (n_invalid == nullptr) return;
+        long long inv = 0;
+        for (int i = threadIdx.x; i < C * Q; i += 256) inv += part_invalid[i];
+        inv = wave_sum(inv);
+        if (p == 0) orphan_red[w] = inv;
+        __syncthreads();
+        if (threadIdx.x == 0) *n_invalid = orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
     }
 }
 
@@ -440,12 +441,10 @@ extern "C" int affinity_histogram(const int32_t* trace, int L, int64_t N, int E,
                                p.words, p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid);
         }
     }
-    if (L > 1)
-        hipLaunchKernelGGL(affinity_finalize_kernel, dim3(static_cast<unsigned>((L - 1) * E)), dim3(256), 0, s, part_counts,
-                           part_orphan_next, p.C, L, E, p.words, counts, loads, cond_prob);
-    if (loads != nullptr || n_invalid != nullptr)
-        hipLaunchKernelGGL(affinity_tail_kernel, dim3(1), dim3(1024), 0, s, part_orphan_last, part_invalid, p.C, p.Q, L, E, counts,
-                           loads, n_invalid);
+    // rows of all pairs, then the loads of the final layer, then the invalid tally
+    const unsigned fin_grid = static_cast<unsigned>((L - 1) * E + E + 1);
+    hipLaunchKernelGGL(affinity_finalize_kernel, dim3(fin_grid), dim3(256), 0, s, part_counts, part_orphan_next, part_orphan_last,
+                       part_invalid, p.C, p.Q, L, E, p.words, counts, loads, cond_prob, n_invalid);
     return check_launch("affinity_histogram");
 }
 

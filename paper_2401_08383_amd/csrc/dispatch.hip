@@ -2,9 +2,10 @@
 //
 //   1. count   : every workgroup histograms its chunk of CH consecutive assignments into LDS
 //                and stores one row of per-expert counts.
-//   2. scan    : one workgroup turns the [blocks x E_local] count matrix into per-chunk start
-//                positions (exclusive scan down each expert column) and writes expert_counts /
-//                expert_offsets.
+//   2. scan    : the [blocks x E_local] count matrix becomes per-chunk start positions (exclusive
+//                scan down each expert column) plus expert_counts / expert_offsets.  Up to 256
+//                chunks every scatter workgroup does this for itself from the small matrix; a
+//                separate one-workgroup scan kernel serves longer inputs.
 //   3. scatter : every workgroup ranks its chunk again — rank inside a wavefront from a ballot
 //                per expert (lanes with a lower id and the same expert), wavefronts ordered
 //                through LDS — which keeps equal experts in ascending assignment order
@@ -18,6 +19,7 @@ namespace exf {
 constexpr int kDispThreads = 256;
 constexpr int kDispWaves = kDispThreads / kWave;
 constexpr int kDispChunk = 1024;  // assignments per workgroup in count / scatter
+constexpr int kDispFusedScanBlocks = 256;  // up to this many chunks every scatter workgroup scans the count matrix itself
 
 __device__ __forceinline__ int local_expert(const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ expert_map,
                                             int64_t a, int E, int E_local)
@@ -69,17 +71,45 @@ __global__ __launch_bounds__(kWave) void dispatch_scan_kernel(int32_t* __restric
     if (e == E_local - 1) expert_offsets[E_local] = incl;
 }
 
+// FUSED_SCAN: block_base holds the RAW per-chunk counts of dispatch_count_kernel and every
+// workgroup derives its own start positions (column sums over the chunks before it) and the
+// expert offsets (column totals) from that small matrix - no separate scan launch.  Otherwise
+// block_base already holds the scanned start positions.
+template <bool FUSED_SCAN>
 __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ expert_map, int64_t A, int E, int E_local,
-    const int32_t* __restrict__ block_base, const int32_t* __restrict__ expert_offsets, int32_t* __restrict__ src_of_sorted,
-    int32_t* __restrict__ sorted_of_src)
+    const int32_t* __restrict__ block_base, int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
+    int32_t* __restrict__ src_of_sorted, int32_t* __restrict__ sorted_of_src)
 {
     __shared__ int cursor[EXF_MAX_EXPERTS];               // next free sorted position per expert
     __shared__ int wave_cnt[kDispWaves][EXF_MAX_EXPERTS];  // per-round, per-wavefront counts
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
-    if (threadIdx.x < E_local)
-        cursor[threadIdx.x] = expert_offsets[threadIdx.x] + block_base[static_cast<int64_t>(blockIdx.x) * E_local + threadIdx.x];
+    if constexpr (FUSED_SCAN) {
+        if (wave == 0) {  // lane e walks down column e of the count matrix
+            int before = 0, total = 0;
+            if (lane < E_local) {
+                const int n_blocks = gridDim.x;
+                for (int b = 0; b < n_blocks; ++b) {
+                    const int c = block_base[static_cast<int64_t>(b) * E_local + lane];
+                    if (b < static_cast<int>(blockIdx.x)) before += c;
+                    total += c;
+                }
+            }
+            const int incl = wave_inclusive_scan(lane < E_local ? total : 0);
+            if (lane < E_local) cursor[lane] = incl - total + before;
+            if (blockIdx.x == 0) {
+                if (lane < E_local) {
+                    expert_counts[lane] = total;
+                    expert_offsets[lane] = incl - total;
+                }
+                if (lane == E_local - 1) expert_offsets[E_local] = incl;
+            }
+        }
+    } else {
+        if (threadIdx.x < E_local)
+            cursor[threadIdx.x] = expert_offsets[threadIdx.x] + block_base[static_cast<int64_t>(blockIdx.x) * E_local + threadIdx.x];
+    }
     __syncthreads();
 
     const int64_t base = static_cast<int64_t>(blockIdx.x) * kDispChunk;
@@ -200,11 +230,17 @@ extern "C" int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_
     if (n_blocks > 0)
         hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E, E_local,
                            block_counts);
-    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(kWave), 0, s, block_counts, n_blocks, E_local, expert_counts,
-                       expert_offsets);
+    const bool fused = n_blocks > 0 && n_blocks <= kDispFusedScanBlocks;
+    if (!fused)
+        hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(kWave), 0, s, block_counts, n_blocks, E_local, expert_counts,
+                           expert_offsets);
     if (n_blocks > 0) {
-        hipLaunchKernelGGL(dispatch_scatter_kernel, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E,
-                           E_local, block_counts, expert_offsets, src_of_sorted, sorted_of_src);
+        if (fused)
+            hipLaunchKernelGGL(dispatch_scatter_kernel<true>, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E,
+                               E_local, block_counts, expert_counts, expert_offsets, src_of_sorted, sorted_of_src);
+        else
+            hipLaunchKernelGGL(dispatch_scatter_kernel<false>, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E,
+                               E_local, block_counts, expert_counts, expert_offsets, src_of_sorted, sorted_of_src);
         if (x_sorted != nullptr) {
             const int vec_per_row = d * (dt == EXF_BF16 ? 2 : 4) / 16;
             const int row_batch = row_batch_for(A);

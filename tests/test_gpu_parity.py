@@ -89,7 +89,8 @@ def _run_dispatch(oracle, x, idx, E, E_local, expert_map, dtype):
 
 
 @pytest.mark.parametrize("dtype,T,d,k,E", [("f32", 512, 64, 1, 8), ("bf16", 1, 64, 1, 8), ("bf16", 1023, 128, 1, 8),
-                                           ("bf16", 5000, 256, 2, 64), ("bf16", 3333, 64, 1, 32), ("f32", 2049, 32, 2, 5)])
+                                           ("bf16", 5000, 256, 2, 64), ("bf16", 3333, 64, 1, 32), ("f32", 2049, 32, 2, 5),
+                                           ("bf16", 300001, 8, 1, 16)])
 def test_dispatch_parity(oracle, dtype, T, d, k, E):
     _say(f"dispatch {dtype} T={T} d={d} k={k} E={E}")
     g = syn.rng(300 + T)
