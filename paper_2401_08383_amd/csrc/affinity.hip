@@ -154,13 +154,45 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
     uint32_t* my_hist = hist + (threadIdx.x & (copies - 1)) * g * words;
     uint32_t invalid_local = 0;
 
-    for (int64_t base = n_begin; base < n_end; base += static_cast<int64_t>(kTraceThreads) * VEC) {
-        const int64_t n0 = base + static_cast<int64_t>(threadIdx.x) * VEC;
-        // all columns of the group at once: up to seven 16-byte loads in flight per thread
-        TokVec<VEC> col[kAffMaxGroup + 1];
+    // Software pipeline over the sweeps of the chunk: the (up to seven) 16-byte column loads of the
+    // NEXT sweep are issued before the current sweep is binned, so that the memory system is never
+    // idle while the LDS atomics run.
+    const int64_t sweep = static_cast<int64_t>(kTraceThreads) * VEC;
+    auto load_cols = [&](int64_t n0, TokVec<VEC>(&col)[kAffMaxGroup + 1]) {
 #pragma unroll
         for (int s = 0; s <= kAffMaxGroup; ++s)
             if (l0 + s <= l1 || s == 0) col[s] = load_tokens<VEC>(trace + static_cast<int64_t>(l0 + s) * N, n0, n_end);
+    };
+    TokVec<VEC> col[kAffMaxGroup + 1], nxt[kAffMaxGroup + 1];
+    load_cols(n_begin + static_cast<int64_t>(threadIdx.x) * VEC, col);
+    for (int64_t base = n_begin; base < n_end; base += sweep) {
+        const int64_t n0 = base + static_cast<int64_t>(threadIdx.x) * VEC;
+        const bool more = base + sweep < n_end;
+        if (more) load_cols(n0 + sweep, nxt);
+        // Fast path (the normal case): every id this wavefront holds in the sweep is inside [0,E) and
+        // no lane is past the end of the chunk - one multiply-add, a shift and one LDS atomic per
+        // transition.  Anything else goes through the fully checked path below.
+        bool clean = n0 + VEC <= n_end;
+#pragma unroll
+        for (int s = 0; s <= kAffMaxGroup; ++s) {
+            if (l0 + s > l1 && s != 0) break;
+            unsigned m = 0;
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) m = max(m, static_cast<unsigned>(col[s].v[u]));
+            clean = clean && m < static_cast<unsigned>(E);
+        }
+        if (__ballot(!clean) == 0ull && L > 1) {
+#pragma unroll
+            for (int s = 1; s <= kAffMaxGroup; ++s) {
+                if (l0 + s > l1) break;
+                uint32_t* h = my_hist + (s - 1) * words;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) {
+                    const int bin = col[s - 1].v[u] * E + col[s].v[u];
+                    atomicAdd(&h[bin >> 1], 1u << ((bin & 1) * 16));
+                }
+            }
+        } else {
 #pragma unroll
         for (int s = 1; s <= kAffMaxGroup; ++s) {
             const int l = l0 + s;
@@ -176,11 +208,7 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
                     const bool vb = static_cast<unsigned>(b) < static_cast<unsigned>(E);
                     if (va && vb) {
                         const int bin = a * E + b;
-#ifndef EXF_TUNE_NO_ATOMIC
                         atomicAdd(&h[bin >> 1], (bin & 1) ? 0x10000u : 1u);
-#else
-                        invalid_local += bin == 77777;
-#endif
                     } else if (va) {
                         atomicAdd(&orphan_next[(s - 1) * E + a], 1u);
                     }
@@ -192,6 +220,7 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
                 }
             }
         }
+        }
         if (L == 1) {  // no pair at all: the single column only feeds loads and the invalid tally
 #pragma unroll
             for (int u = 0; u < VEC; ++u)
@@ -200,6 +229,10 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
                     if (static_cast<unsigned>(a) < static_cast<unsigned>(E)) atomicAdd(&orphan_last[a], 1u);
                     else invalid_local += 1;
                 }
+        }
+        if (more) {
+#pragma unroll
+            for (int s = 0; s <= kAffMaxGroup; ++s) col[s] = nxt[s];
         }
     }
     if (invalid_local) atomicAdd(invalid_cnt, invalid_local);
@@ -318,42 +351,67 @@ __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const i
         const int64_t n0 = base + static_cast<int64_t>(threadIdx.x) * VEC;
         int dev_prev[VEC];
         bool ok_prev[VEC];
+        const bool in_range = n0 + VEC <= n_end;  // all tokens of this lane exist
+        bool prev_clean;                           // all ids of the previous layer valid (and in range)
         {
             const TokVec<VEC> t = load_tokens<VEC>(trace, n0, n_end);
+            prev_clean = in_range;
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
                 ok_prev[u] = (n0 + u < n_end) && static_cast<unsigned>(t.v[u]) < static_cast<unsigned>(E);
                 dev_prev[u] = ok_prev[u] ? pl[t.v[u]] : 0;
+                prev_clean = prev_clean && ok_prev[u];
             }
         }
-        for (int lb = 1; lb < L; lb += kLocAhead) {
-            TokVec<VEC> cur[kLocAhead];
+        auto load_layers = [&](int lb, TokVec<VEC>(&dst)[kLocAhead]) {
 #pragma unroll
             for (int a = 0; a < kLocAhead; ++a)
-                if (lb + a < L) cur[a] = load_tokens<VEC>(trace + static_cast<int64_t>(lb + a) * N, n0, n_end);
+                if (lb + a < L) dst[a] = load_tokens<VEC>(trace + static_cast<int64_t>(lb + a) * N, n0, n_end);
+        };
+        // software pipeline over batches of kLocAhead layers: the next batch is requested before the
+        // current one is counted
+        TokVec<VEC> cur[kLocAhead], nxt[kLocAhead];
+        load_layers(1, cur);
+        for (int lb = 1; lb < L; lb += kLocAhead) {
+            if (lb + kLocAhead < L) load_layers(lb + kLocAhead, nxt);
 #pragma unroll
             for (int a = 0; a < kLocAhead; ++a) {
                 const int l = lb + a;
                 if (l >= L) break;
+                unsigned m = 0;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) m = max(m, static_cast<unsigned>(cur[a].v[u]));
+                const bool clean = in_range && m < static_cast<unsigned>(E);
                 // wavefront total of "device unchanged" flags by ballot + popcount (scalar unit)
                 int same = 0;
-#ifdef EXF_TUNE_LOC_NOCOMPUTE
+                if (__ballot(!(clean && prev_clean)) == 0ull) {
+                    // fast path: every id of this wavefront is valid in both layers - one table
+                    // look-up and one compare per transition
 #pragma unroll
-                for (int u = 0; u < VEC; ++u) dev_prev[u] ^= cur[a].v[u];
-                if (dev_prev[0] == 0x7fffffff) same = 1;
-                if (lane == 0 && same != 0) atomicAdd(&pair_cnt[l - 1], 1u);
-                continue;
-#endif
+                    for (int u = 0; u < VEC; ++u) {
+                        const int dev = pl[l * E + cur[a].v[u]];
+                        same += __popcll(__ballot(dev == dev_prev[u]));
+                        dev_prev[u] = dev;
+                    }
+                } else {
 #pragma unroll
-                for (int u = 0; u < VEC; ++u) {
-                    const bool ok = (n0 + u < n_end) && static_cast<unsigned>(cur[a].v[u]) < static_cast<unsigned>(E);
-                    const int dev = ok ? pl[l * E + cur[a].v[u]] : 0;
-                    same += __popcll(__ballot(ok && ok_prev[u] && dev == dev_prev[u]));
-                    ok_prev[u] = ok;
-                    dev_prev[u] = dev;
+                    for (int u = 0; u < VEC; ++u) {
+                        const bool ok = (n0 + u < n_end) && static_cast<unsigned>(cur[a].v[u]) < static_cast<unsigned>(E);
+                        const int dev = ok ? pl[l * E + cur[a].v[u]] : 0;
+                        same += __popcll(__ballot(ok && ok_prev[u] && dev == dev_prev[u]));
+                        ok_prev[u] = ok;
+                        dev_prev[u] = dev;
+                    }
                 }
+                if (clean) {  // the flags the checked path would have produced
+#pragma unroll
+                    for (int u = 0; u < VEC; ++u) ok_prev[u] = true;
+                }
+                prev_clean = clean;
                 if (lane == 0 && same != 0) atomicAdd(&pair_cnt[l - 1], static_cast<uint32_t>(same));
             }
+#pragma unroll
+            for (int a = 0; a < kLocAhead; ++a) cur[a] = nxt[a];
         }
     }
     __syncthreads();
