@@ -49,9 +49,10 @@ __device__ __forceinline__ float gelu_tanh_exact(float z)
 __device__ __forceinline__ float gelu_erf_fast(float z)
 {
     const float t = fminf(z * z, 60.0f);
-    float p = fmaf(-7.02902502e-4f, t, 7.40107343e-2f);
-    p = fmaf(p, t, 1.59501506f);
-    const float e = __expf(-z * p);
+    // coefficients carry the factor -log2(e): exp(-z p(t)) = 2^(z q(t)), one v_exp_f32
+    float q = fmaf(1.01407394e-3f, t, -1.06774916e-1f);
+    q = fmaf(q, t, -2.30112032f);
+    const float e = __builtin_amdgcn_exp2f(z * q);
     return z * __builtin_amdgcn_rcpf(1.0f + e);  // v_rcp_f32: 1 ulp
 }
 // z/2 (1 + tanh u) = z / (1 + exp(-2u))
@@ -75,11 +76,15 @@ __device__ unsigned long long exf_tune_times[8 * 64];
 #endif
 
 // ---------------------------------------------------------------------------- tile lookup
-// Rows of expert e are cut into "full" row tiles of MT rows and, for the remainder, "tail" row
-// tiles of kTailRows rows, so that a ragged remainder costs in proportion to its size instead of
-// a whole tile.  Tile order: all full tiles as (expert, column tile, row tile), then all tail
-// tiles in the same way; the cheap tail tiles therefore fill the last round of the launch.
+// Rows of expert e are cut into "full" row tiles of MT rows.  A remainder of at most MT/2 rows is
+// cut into "tail" row tiles of kTailRows rows, so that a small remainder costs in proportion to
+// its size instead of a whole tile; a larger remainder becomes one more full tile whose missing
+// rows are masked (a tail tile does a quarter of the MFMA work of a 256-row tile but loads the
+// same weight panel, so three or four of them cost more than the one masked tile).  Tile order:
+// all full tiles as (expert, column tile, row tile), then all tail tiles in the same way; the
+// cheap tail tiles therefore fill the last round of the launch.
 constexpr int kTailRows = 64;
+__host__ __device__ constexpr int max_tail_tiles(int mt) { return mt / 2 >= kTailRows ? (mt / 2 + kTailRows - 1) / kTailRows : 1; }
 constexpr int kXcdChunk = 16;  // consecutive tiles handed to one XCD at a time
 
 struct Tile2D {
@@ -109,8 +114,12 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
         hi = min(max(offsets[lane + 1], lo), max_rows);
     }
     const int cnt = hi - lo;
-    const int full_rt = cnt / mt;
-    const int tail_rt = (cnt - full_rt * mt + kTailRows - 1) / kTailRows;
+    int full_rt = cnt / mt;
+    int tail_rt = (cnt - full_rt * mt + kTailRows - 1) / kTailRows;
+    if (tail_rt > max_tail_tiles(mt)) {
+        full_rt += 1;
+        tail_rt = 0;
+    }
     const int full_incl = wave_inclusive_scan(full_rt * n_tiles);
     const int tail_incl = wave_inclusive_scan(tail_rt * n_tiles);
     const int total_full = __shfl(full_incl, kWave - 1, kWave);
@@ -264,6 +273,14 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         for (int i = 0; i < LW; ++i) lds_dma_16B(wgt_b + kbyte, off_w[i], stage + MT * RB + (wave * LW + i) * 1024);
     };
 
+    // one of the LPW loads of K tile kt (i < LA: activation group, else weight group)
+    auto issue_one = [&](int kt, int i) {
+        const uint32_t stage = smem_addr + (kt % STAGES) * STAGE_BYTES;
+        const size_t kbyte = static_cast<size_t>(kt) * (KT * 2);
+        if (i < LA) lds_dma_16B(act_b + kbyte, off_a[i < LA ? i : 0], stage + (wave * LA + i) * 1024);
+        else lds_dma_16B(wgt_b + kbyte, off_w[i >= LA ? i - LA : 0], stage + MT * RB + (wave * LW + (i - LA)) * 1024);
+    };
+
     EXF_STAMP(1);
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
@@ -292,12 +309,13 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
 #ifdef EXF_TUNE_TIMING
         const long long c1 = clock64();
 #endif
-#ifndef EXF_TUNE_NO_LOAD
-        if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
-#endif
-
-        // MFMA operands are double-buffered in registers: the LDS reads of K step ks+1 are in
-        // flight while the matrix cores work on K step ks.
+        // Hand-placed issue order of a K tile (the scheduling barriers pin it).  Slot m of K step ks
+        // issues MFMA m.  In front of every few slots sits one operand fetch (LDS -> registers) for
+        // the next K step: MFMA operands are double-buffered in registers.  Behind the slots of the
+        // first K steps sits one direct-to-LDS load of a later K tile at a time: a global load can
+        // take long to issue, and issued as one burst the loads would keep the wavefront - and with
+        // it its matrix cores - waiting at the head of every K tile.
+        const bool do_load = kt + STAGES - 1 < nk;
         const unsigned char* stage = smem + (kt % STAGES) * STAGE_BYTES;
         const unsigned char* pw = stage + wgt_base;
         const unsigned char* pa = stage + act_base;
@@ -306,37 +324,38 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         for (int a = 0; a < TN; ++a) fa[0][a] = *reinterpret_cast<const bf16x8_t*>(pw + a * 32 * RB + frag_off[0]);
 #pragma unroll
         for (int b = 0; b < TM; ++b) fb[0][b] = *reinterpret_cast<const bf16x8_t*>(pa + b * 32 * RB + frag_off[0]);
+        constexpr int SLOTS = TN * TM;
+        constexpr int SPREAD = KSTEPS >= 2 ? KSTEPS / 2 : 1;  // K steps that carry the global loads
+        constexpr int LOAD_SLOTS = SPREAD * SLOTS;
+        constexpr int READ_GAP = SLOTS / (TN + TM) > 0 ? SLOTS / (TN + TM) : 1;
+        constexpr int READS_PER_SLOT = (TN + TM + SLOTS - 1) / SLOTS;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < KSTEPS) {
+            const int ksn = ks + 1 < KSTEPS ? ks + 1 : KSTEPS - 1;
 #pragma unroll
-                for (int a = 0; a < TN; ++a)
-                    fa[nxt][a] = *reinterpret_cast<const bf16x8_t*>(pw + a * 32 * RB + frag_off[ks + 1]);
+            for (int m = 0; m < SLOTS; ++m) {
+                if (ks + 1 < KSTEPS && m % READ_GAP == 0) {
 #pragma unroll
-                for (int b = 0; b < TM; ++b)
-                    fb[nxt][b] = *reinterpret_cast<const bf16x8_t*>(pa + b * 32 * RB + frag_off[ks + 1]);
-            }
-#ifndef EXF_TUNE_NO_MFMA
-#pragma unroll
-            for (int a = 0; a < TN; ++a)
-#pragma unroll
-                for (int b = 0; b < TM; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][a], fb[cur][b], acc[a][b], 0, 0, 0);
-#else
-            acc[0][0][0] += static_cast<float>(fa[cur][0][0]) + static_cast<float>(fb[cur][0][0]);
-#endif
-            // Issue order inside the K step: one operand fetch for the next step, then a couple of
-            // MFMAs of this step, and so on - the LDS traffic of the four wavefronts is spread under
-            // the matrix-core work instead of arriving as one burst while the MFMA pipes idle.
-            if (ks + 1 < KSTEPS) {
-#pragma unroll
-                for (int i = 0; i < TN + TM; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                         // 1 LDS read
-                    __builtin_amdgcn_sched_group_barrier(0x008, (TN * TM) / (TN + TM), 0);     // MFMAs
+                    for (int q = 0; q < READS_PER_SLOT; ++q) {
+                        const int r = (m / READ_GAP) * READS_PER_SLOT + q;  // fetch number r of the next K step
+                        if (r < TN) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(pw + r * 32 * RB + frag_off[ksn]);
+                        else if (r < TN + TM) fb[nxt][r - TN] = *reinterpret_cast<const bf16x8_t*>(pa + (r - TN) * 32 * RB + frag_off[ksn]);
+                    }
                 }
+                acc[m / TM][m % TM] =
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m / TM], fb[cur][m % TM], acc[m / TM][m % TM], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#ifndef EXF_TUNE_NO_LOAD
+                if (ks < SPREAD) {
+                    const int g = ks * SLOTS + m;  // load i goes behind slot i*LOAD_SLOTS/LPW
+#pragma unroll
+                    for (int i = 0; i < LPW; ++i)
+                        if (i * LOAD_SLOTS / LPW == g && do_load) issue_one(kt + STAGES - 1, i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#endif
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
 #ifdef EXF_TUNE_TIMING
         const long long c2 = clock64();
@@ -364,10 +383,10 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     constexpr int RPI_OUT = 64 / CW;               // rows covered by one wavefront-wide 16-byte access
     static_assert(NWAVES * REGION <= STAGES * STAGE_BYTES, "epilogue staging must fit in the LDS ring");
     static_assert(64 % CW == 0 && (BP * 32) % RPI_OUT == 0, "row segments must tile the wavefront");
-    EXF_STAMP(2);
 #ifdef EXF_TUNE_NO_EPI
     if (acc[0][0][0] != 123.456f) return;
 #endif
+    EXF_STAMP(2);
     __syncthreads();  // every wavefront is done reading the last K tile
     EXF_STAMP(3);
     unsigned char* region = smem + wave * REGION;
@@ -531,8 +550,8 @@ static int launch_bf16(const void* act, const int32_t* offsets, const void* weig
                        int E_local, int epi, void* out, hipStream_t stream)
 {
     constexpr size_t lds = static_cast<size_t>(STAGES) * (MT + NT) * KT * 2;
-    // worst case: A/MT full row tiles plus MT/kTailRows tail row tiles for every expert
-    const int64_t row_tiles = A / MT + static_cast<int64_t>(E_local) * ((MT + kTailRows - 1) / kTailRows);
+    // worst case: A/MT unmasked row tiles plus, for every expert, its tail tiles or one masked tile
+    const int64_t row_tiles = A / MT + static_cast<int64_t>(E_local) * max_tail_tiles(MT);
     const int64_t n_tiles = (N + NT - 1) / NT;
     const int64_t ub = row_tiles * n_tiles;
     const int64_t round = static_cast<int64_t>(kXcdCount) * kXcdChunk;
@@ -586,10 +605,10 @@ static int launch_f32(const void* act, const int32_t* offsets, const void* weigh
 // Tile configuration <MT, NT, KT, STAGES, WM, WN, SWZ, OCC> of the two contractions
 // (OCC = wavefronts per SIMD the register allocation must leave room for).
 #ifndef EXF_GEMM1_CFG
-#define EXF_GEMM1_CFG 256, 128, 32, 3, 2, 2, 0, 2
+#define EXF_GEMM1_CFG 256, 256, 64, 2, 2, 2, 1, 1
 #endif
 #ifndef EXF_GEMM2_CFG
-#define EXF_GEMM2_CFG 256, 128, 32, 3, 2, 2, 0, 2
+#define EXF_GEMM2_CFG 256, 128, 64, 3, 2, 2, 1, 1
 #endif
 
 // Tuning builds (-DEXF_FFN_TUNE) can skip one of the two contractions to time the other alone.
