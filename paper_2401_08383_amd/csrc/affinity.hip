@@ -36,7 +36,7 @@ constexpr int kXcds = 8;
 #define EXF_TARGET_WGS 256
 #endif
 #ifndef EXF_LOC_AHEAD
-#define EXF_LOC_AHEAD 4
+#define EXF_LOC_AHEAD 2
 #endif
 constexpr int kTraceThreads = EXF_TRACE_THREADS;
 constexpr int kAffMaxGroup = 6;                        // layer pairs per workgroup (7 columns in registers)
@@ -97,24 +97,26 @@ struct TokVec {
     int v[VEC];
 };
 
+// Loads the ids of tokens n .. n+VEC-1 of one trace column.  The load is UNCONDITIONAL: a lane past
+// the end of its chunk re-reads the chunk's last vector (the caller masks such lanes through its own
+// range test).  Keeping branches away from the loads matters: with a branch around each of them the
+// compiler can no longer count the loads in flight and waits for all earlier ones before every new
+// one, which leaves a single load in flight per wavefront.  With VEC = 4 the column base, n and end
+// are multiples of four, so a vector is never cut by the end of the chunk.
 template <int VEC>
 __device__ __forceinline__ TokVec<VEC> load_tokens(const int32_t* __restrict__ col, int64_t n, int64_t end)
 {
     TokVec<VEC> r;
+    const int64_t n_safe = min(n, end - VEC);  // callers guarantee end - begin >= VEC
     if constexpr (VEC == 4) {
-        if (n + 3 < end) {
-            typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_v;
-            const i32x4_v q = __builtin_nontemporal_load(reinterpret_cast<const i32x4_v*>(col + n));  // streamed once
-            r.v[0] = q[0];
-            r.v[1] = q[1];
-            r.v[2] = q[2];
-            r.v[3] = q[3];
-        } else {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) r.v[u] = (n + u < end) ? col[n + u] : 0;
-        }
+        typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_v;
+        const i32x4_v q = __builtin_nontemporal_load(reinterpret_cast<const i32x4_v*>(col + n_safe));  // streamed once
+        r.v[0] = q[0];
+        r.v[1] = q[1];
+        r.v[2] = q[2];
+        r.v[3] = q[3];
     } else {
-        r.v[0] = n < end ? col[n] : 0;
+        r.v[0] = __builtin_nontemporal_load(col + n_safe);
     }
     return r;
 }
@@ -158,17 +160,18 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
     // NEXT sweep are issued before the current sweep is binned, so that the memory system is never
     // idle while the LDS atomics run.
     const int64_t sweep = static_cast<int64_t>(kTraceThreads) * VEC;
+    // (columns past the group's last one and sweeps past the chunk's end are clamped, not skipped:
+    // the loads stay free of branches, the duplicates are cache hits)
     auto load_cols = [&](int64_t n0, TokVec<VEC>(&col)[kAffMaxGroup + 1]) {
 #pragma unroll
         for (int s = 0; s <= kAffMaxGroup; ++s)
-            if (l0 + s <= l1 || s == 0) col[s] = load_tokens<VEC>(trace + static_cast<int64_t>(l0 + s) * N, n0, n_end);
+            col[s] = load_tokens<VEC>(trace + static_cast<int64_t>(min(l0 + s, l1)) * N, n0, n_end);
     };
     TokVec<VEC> col[kAffMaxGroup + 1], nxt[kAffMaxGroup + 1];
     load_cols(n_begin + static_cast<int64_t>(threadIdx.x) * VEC, col);
     for (int64_t base = n_begin; base < n_end; base += sweep) {
         const int64_t n0 = base + static_cast<int64_t>(threadIdx.x) * VEC;
-        const bool more = base + sweep < n_end;
-        if (more) load_cols(n0 + sweep, nxt);
+        load_cols(n0 + sweep, nxt);
         // Fast path (the normal case): every id this wavefront holds in the sweep is inside [0,E) and
         // no lane is past the end of the chunk - one multiply-add, a shift and one LDS atomic per
         // transition.  Anything else goes through the fully checked path below.
@@ -230,10 +233,8 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
                     else invalid_local += 1;
                 }
         }
-        if (more) {
 #pragma unroll
-            for (int s = 0; s <= kAffMaxGroup; ++s) col[s] = nxt[s];
-        }
+        for (int s = 0; s <= kAffMaxGroup; ++s) col[s] = nxt[s];
     }
     if (invalid_local) atomicAdd(invalid_cnt, invalid_local);
     __syncthreads();
@@ -365,15 +366,15 @@ __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const i
         }
         auto load_layers = [&](int lb, TokVec<VEC>(&dst)[kLocAhead]) {
 #pragma unroll
-            for (int a = 0; a < kLocAhead; ++a)
-                if (lb + a < L) dst[a] = load_tokens<VEC>(trace + static_cast<int64_t>(lb + a) * N, n0, n_end);
+            for (int a = 0; a < kLocAhead; ++a)  // layers past the last one are clamped, not skipped: no branch at the loads
+                dst[a] = load_tokens<VEC>(trace + static_cast<int64_t>(min(lb + a, L - 1)) * N, n0, n_end);
         };
         // software pipeline over batches of kLocAhead layers: the next batch is requested before the
         // current one is counted
         TokVec<VEC> cur[kLocAhead], nxt[kLocAhead];
         load_layers(1, cur);
         for (int lb = 1; lb < L; lb += kLocAhead) {
-            if (lb + kLocAhead < L) load_layers(lb + kLocAhead, nxt);
+            load_layers(lb + kLocAhead, nxt);
 #pragma unroll
             for (int a = 0; a < kLocAhead; ++a) {
                 const int l = lb + a;

@@ -30,8 +30,84 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
             pos[j] = ok ? s : -1;
             wt[j] = ok ? topk_w[(t0 + lane) * K + j] : 0.0f;
         }
+        // weighted sum of the K source chunks of one output chunk, rounded once to the storage type
+        auto reduce_chunk = [&](const uint4(&vj)[K], const float(&wj)[K]) -> uint4 {
+            uint4 r;
+            if constexpr (BF16) {
+                float acc[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    const uint32_t p[4] = {vj[j].x, vj[j].y, vj[j].z, vj[j].w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        acc[2 * q] = fmaf(wj[j], __uint_as_float(p[q] << 16), acc[2 * q]);
+                        acc[2 * q + 1] = fmaf(wj[j], __uint_as_float(p[q] & 0xffff0000u), acc[2 * q + 1]);
+                    }
+                }
+                r.x = pack_bf16x2(acc[0], acc[1]);
+                r.y = pack_bf16x2(acc[2], acc[3]);
+                r.z = pack_bf16x2(acc[4], acc[5]);
+                r.w = pack_bf16x2(acc[6], acc[7]);
+            } else {
+                float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    acc[0] = fmaf(wj[j], __uint_as_float(vj[j].x), acc[0]);
+                    acc[1] = fmaf(wj[j], __uint_as_float(vj[j].y), acc[1]);
+                    acc[2] = fmaf(wj[j], __uint_as_float(vj[j].z), acc[2]);
+                    acc[3] = fmaf(wj[j], __uint_as_float(vj[j].w), acc[3]);
+                }
+                r = uint4{__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+            }
+            return r;
+        };
         const int total = rows * vec_per_row;
-        for (int c0 = lane; c0 < total; c0 += kWave * U) {
+        constexpr int kPass = kWave * U;  // output chunks the wavefront produces per pass
+        if (total % kPass == 0) {
+            // Every lane has a chunk in every pass: no condition anywhere near the loads (a dropped
+            // assignment reads row 0 and is zeroed afterwards), and the loads of the next pass are issued
+            // before this pass is reduced and stored.
+            const int n_pass = total / kPass;
+            auto load_pass = [&](int pass, uint4(&v)[U][K], float(&w)[U][K]) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = pass * kPass + u * kWave + lane;
+                    const int r = row_of_chunk(c, vec_per_row, rcp);
+                    const int col = c - r * vec_per_row;
+#pragma unroll
+                    for (int j = 0; j < K; ++j) {
+                        const int s = __shfl(pos[j], r, kWave);
+                        w[u][j] = __shfl(wt[j], r, kWave);
+                        v[u][j] = load_stream16(y + static_cast<int64_t>(max(s, 0)) * vec_per_row + col);
+                        if (s < 0) v[u][j] = uint4{0u, 0u, 0u, 0u};
+                    }
+                }
+            };
+            auto store_pass = [&](int pass, const uint4(&v)[U][K], const float(&w)[U][K]) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    store_stream16(out + t0 * vec_per_row + pass * kPass + u * kWave + lane, reduce_chunk(v[u], w[u]));
+            };
+            uint4 cur[U][K], nxt[U][K];
+            float wcur[U][K], wnxt[U][K];
+            load_pass(0, cur, wcur);
+            for (int pass = 0; pass + 1 < n_pass; ++pass) {
+                load_pass(pass + 1, nxt, wnxt);
+                store_pass(pass, cur, wcur);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int j = 0; j < K; ++j) {
+                        cur[u][j] = nxt[u][j];
+                        wcur[u][j] = wnxt[u][j];
+                    }
+            }
+            store_pass(n_pass - 1, cur, wcur);
+            continue;
+        }
+        for (int c0 = lane; c0 < total; c0 += kWave * U) {  // ragged batch: every chunk checked
             uint4 v[U][K];
             float w[U][K];
 #pragma unroll
@@ -51,35 +127,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
             for (int u = 0; u < U; ++u) {
                 const int c = c0 + u * kWave;
                 if (c >= total) continue;
-                uint4 r;
-                if constexpr (BF16) {
-                    float acc[8];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
-#pragma unroll
-                    for (int j = 0; j < K; ++j) {
-                        const uint32_t p[4] = {v[u][j].x, v[u][j].y, v[u][j].z, v[u][j].w};
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            acc[2 * q] = fmaf(w[u][j], __uint_as_float(p[q] << 16), acc[2 * q]);
-                            acc[2 * q + 1] = fmaf(w[u][j], __uint_as_float(p[q] & 0xffff0000u), acc[2 * q + 1]);
-                        }
-                    }
-                    r.x = pack_bf16x2(acc[0], acc[1]);
-                    r.y = pack_bf16x2(acc[2], acc[3]);
-                    r.z = pack_bf16x2(acc[4], acc[5]);
-                    r.w = pack_bf16x2(acc[6], acc[7]);
-                } else {
-                    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                    for (int j = 0; j < K; ++j) {
-                        acc[0] = fmaf(w[u][j], __uint_as_float(v[u][j].x), acc[0]);
-                        acc[1] = fmaf(w[u][j], __uint_as_float(v[u][j].y), acc[1]);
-                        acc[2] = fmaf(w[u][j], __uint_as_float(v[u][j].z), acc[2]);
-                        acc[3] = fmaf(w[u][j], __uint_as_float(v[u][j].w), acc[3]);
-                    }
-                    r = uint4{__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]), __float_as_uint(acc[3])};
-                }
+                const uint4 r = reduce_chunk(v[u], w[u]);
                 store_stream16(out + t0 * vec_per_row + c, r);
             }
         }

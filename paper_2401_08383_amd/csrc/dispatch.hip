@@ -160,7 +160,38 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __res
         const int rows = static_cast<int>(min(static_cast<int64_t>(row_batch), kept - s0));
         const int src_row = lane < rows ? src_of_sorted[s0 + lane] / k : 0;
         const int total = rows * vec_per_row;
-        for (int c0 = lane; c0 < total; c0 += kWave * U) {
+        constexpr int kPass = kWave * U;  // chunks the wavefront moves per pass
+        if (total % kPass == 0) {
+            // Every lane has a chunk in every pass: no condition anywhere near the loads, and the loads
+            // of the next pass are issued before the stores of this one (with a branch around a load the
+            // compiler waits for all outstanding memory operations at every pass).
+            const int n_pass = total / kPass;
+            auto load_pass = [&](int pass, uint4(&v)[U]) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = pass * kPass + u * kWave + lane;
+                    const int r = row_of_chunk(c, vec_per_row, rcp);
+                    const int col = c - r * vec_per_row;
+                    const int t = __shfl(src_row, r, kWave);
+                    v[u] = load_stream16(x + static_cast<int64_t>(t) * vec_per_row + col);
+                }
+            };
+            auto store_pass = [&](int pass, const uint4(&v)[U]) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) store_stream16(x_sorted + s0 * vec_per_row + pass * kPass + u * kWave + lane, v[u]);
+            };
+            uint4 cur[U], nxt[U];
+            load_pass(0, cur);
+            for (int pass = 0; pass + 1 < n_pass; ++pass) {
+                load_pass(pass + 1, nxt);
+                store_pass(pass, cur);
+#pragma unroll
+                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+            }
+            store_pass(n_pass - 1, cur);
+            continue;
+        }
+        for (int c0 = lane; c0 < total; c0 += kWave * U) {  // ragged batch: every chunk checked
             uint4 v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {

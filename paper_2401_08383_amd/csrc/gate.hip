@@ -284,9 +284,9 @@ __global__ __launch_bounds__(NW * 64) void gate_bf16_kernel(const bf16_t* __rest
 
 // ------------------------------------------------------------------------------------------
 // bf16 gate with W_gate resident in LDS (used whenever the padded weight fits): a persistent
-// workgroup copies W_gate into LDS once, laid out so that the 16 lanes of an MFMA row group
-// read 256 contiguous bytes; after that every wavefront streams its own 16-token tiles over the
-// full reduction dimension - x is read from HBM exactly once, there is no cross-wavefront
+// workgroup copies W_gate into LDS once (row per expert, 16-byte pieces XOR-swizzled so that the
+// 16 lanes of an MFMA row group hit 16 different bank groups); after that every wavefront streams
+// its own 16-token tiles over the full reduction dimension - x is read from HBM exactly once, there is no cross-wavefront
 // reduction and no barrier in the loop.  A token's logits end up in 4 lanes (l, l^16, l^32,
 // l^48), so softmax and top-k need two shuffle steps.
 // ------------------------------------------------------------------------------------------
@@ -305,50 +305,92 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
                                                                     float* __restrict__ topk_w)
 {
     constexpr int EP = NT * 16;
-    extern __shared__ uint4 wlds[];  // [d/8][EP]: 16-byte piece c of expert e at wlds[c*EP + e]
+    // [EP][d/8] 16-byte pieces, row e = expert e (rows past E are zero); inside a row piece c sits at
+    // position c ^ (e & swz): the 16 lanes of an MFMA row group (16 consecutive experts, same c) then
+    // read 16 different 16-byte bank groups, while the copy from global memory stays row-contiguous.
+    extern __shared__ uint4 wlds[];
     const int chunks = d / 8;
-    const uint4* wg16 = reinterpret_cast<const uint4*>(wg);
-    for (int i = threadIdx.x; i < EP * chunks; i += WAVES * 64) {
-        const int e = i / chunks, c = i - e * chunks;
-        wlds[c * EP + e] = e < E ? wg16[static_cast<int64_t>(e) * chunks + c] : uint4{0u, 0u, 0u, 0u};
-    }
-    __syncthreads();
-
+    const int swz = min(15, (chunks & -chunks) - 1);  // the XOR must stay inside the row
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
     const int r16 = lane & 15, g = lane >> 4;
     const int64_t n_tiles = (T + 15) / 16;
     const int steps = (chunks + 3) / 4;
     const bf16x8_t zero8 = {};
-    for (int64_t tile = static_cast<int64_t>(blockIdx.x) * WAVES + wave; tile < n_tiles; tile += static_cast<int64_t>(gridDim.x) * WAVES) {
-        const int64_t t = min(tile * 16 + r16, T - 1);
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * WAVES;
+    int64_t tile = static_cast<int64_t>(blockIdx.x) * WAVES + wave;
+    const bool has_work = tile < n_tiles;  // (a wavefront without a tile still helps with the copy)
+
+    // The wavefront walks the batches (PF steps of 32 reduction elements) of its tiles as ONE
+    // stream: the PF 16-byte loads of the next batch - of the next tile, if this one is finished -
+    // are issued before the MFMAs of the current batch.  The loads are unconditional (indices past
+    // the end are clamped; the operand is zeroed when it is used) and a scheduling barrier keeps
+    // them in front of the MFMAs, so PF loads per lane are in flight while the matrix cores work;
+    // left to itself the compiler sinks every load down to its MFMA.
+#ifndef EXF_GATE_PF
+#define EXF_GATE_PF 4
+#endif
+    constexpr int PF = EXF_GATE_PF;
+    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_v;
+    auto issue = [&](int64_t tl, int s0, i32x4_v(&b)[PF]) {
+        const int64_t t = min(min(tl, n_tiles - 1) * 16 + r16, T - 1);
         const bf16_t* xrow = x + t * d;
-        f32x4_t acc[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        constexpr int PF = 8;
-        for (int s0 = 0; s0 < steps; s0 += PF) {
-            bf16x8_t b[PF];
-            int cc[PF];
+        for (int u = 0; u < PF; ++u) {
+            const int c = min((s0 + u) * 4 + g, chunks - 1);
+            b[u] = __builtin_nontemporal_load(reinterpret_cast<const i32x4_v*>(xrow + c * 8));  // x is streamed once
+        }
+    };
+    i32x4_v cur[PF], nxt[PF];
+    issue(tile, 0, cur);  // the first x loads travel while W_gate is copied
+
+    // W_gate -> LDS, eight 16-byte loads in flight per thread (a plain loop runs one at a time)
+#ifndef EXF_GATE_NOFILL
+    {
+        const uint4* wg16 = reinterpret_cast<const uint4*>(wg);
+        const int total = EP * chunks, valid = E * chunks;
+        constexpr int FB = 8;
+        for (int base = threadIdx.x; base < total; base += WAVES * 64 * FB) {
+            uint4 v[FB];
 #pragma unroll
-            for (int u = 0; u < PF; ++u) {  // eight 16-byte loads of x in flight per lane
-                const int c = (s0 + u) * 4 + g;
-                const bool ok = c < chunks;
-                cc[u] = ok ? c : 0;
-                b[u] = *reinterpret_cast<const bf16x8_t*>(xrow + cc[u] * 8);
-                if (!ok) b[u] = zero8;
-            }
+            for (int u = 0; u < FB; ++u) v[u] = wg16[min(base + u * WAVES * 64, valid - 1)];
 #pragma unroll
-            for (int u = 0; u < PF; ++u) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const uint4 wv = wlds[cc[u] * EP + nt * 16 + r16];
-                    bf16x8_t a;
-                    __builtin_memcpy(&a, &wv, sizeof(a));
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[u], acc[nt], 0, 0, 0);
-                }
+            for (int u = 0; u < FB; ++u) {
+                const int i = base + u * WAVES * 64;
+                const int e = i / chunks, c = i - e * chunks;
+                if (i < total) wlds[e * chunks + (c ^ (e & swz))] = i < valid ? v[u] : uint4{0u, 0u, 0u, 0u};
             }
         }
+    }
+#endif
+    __syncthreads();
+    if (!has_work) return;
+    int s0 = 0;
+    f32x4_t acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    while (true) {
+        const bool last_batch = s0 + PF >= steps;
+        const int64_t tile_next = last_batch ? tile + stride : tile;
+        const int s0_next = last_batch ? 0 : s0 + PF;
+        issue(tile_next, s0_next, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int c = (s0 + u) * 4 + g;
+            bf16x8_t bv;
+            __builtin_memcpy(&bv, &cur[u], sizeof(bv));
+            if (c >= chunks) bv = zero8;
+            const int cl = min(c, chunks - 1);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const uint4 wv = wlds[(nt * 16 + r16) * chunks + (cl ^ (r16 & swz))];
+                bf16x8_t a;
+                __builtin_memcpy(&a, &wv, sizeof(a));
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv, acc[nt], 0, 0, 0);
+            }
+        }
+        if (last_batch) {
         // this lane: token tile*16 + r16, experts nt*16 + 4g + v (ascending in (nt, v))
         float l0 = -INFINITY;
         int i0 = 2 * kWave;
@@ -401,6 +443,14 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
                 store_route(r, tok, k, topk_idx, topk_w);
             }
         }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (tile_next >= n_tiles) break;
+        }  // last batch of the tile
+#pragma unroll
+        for (int u = 0; u < PF; ++u) cur[u] = nxt[u];
+        tile = tile_next;
+        s0 = s0_next;
     }
 }
 
