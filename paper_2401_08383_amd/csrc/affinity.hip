@@ -281,8 +281,15 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
             const int shift = (bin & 1) * 16;
             const uint32_t* src = part_counts + static_cast<size_t>(l) * words + (bin >> 1);
             const size_t step = static_cast<size_t>(pairs) * words;
-#pragma unroll 4
-            for (int c = w; c < C; c += 4) cnt += (src[c * step] >> shift) & 0xffffu;
+            // 16 independent loads in flight (clamped, never branched around)
+            for (int c0 = w; c0 < C; c0 += 4 * 16) {
+                uint32_t v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = src[min(c0 + 4 * u, C - 1) * step];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    if (c0 + 4 * u < C) cnt += (v[u] >> shift) & 0xffffu;
+            }
         }
         long long orphan = 0;
         for (int c = threadIdx.x; c < C; c += 256) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
@@ -308,10 +315,20 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
         long long s = 0;
         if (pairs > 0) {  // column pe of the last pair: sum over chunks c and source experts i
             const int total = C * E;
-            for (int j = threadIdx.x; j < total; j += 256) {
-                const int c = j / E, i = j - c * E;
-                const int bin = i * E + pe;
-                s += (part_counts[(static_cast<size_t>(c) * pairs + (pairs - 1)) * words + (bin >> 1)] >> ((bin & 1) * 16)) & 0xffffu;
+            for (int j0 = threadIdx.x; j0 < total; j0 += 256 * 8) {
+                uint32_t v[8];
+                int sh[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int j = min(j0 + 256 * u, total - 1);
+                    const int c = j / E, i = j - c * E;
+                    const int bin = i * E + pe;
+                    sh[u] = (bin & 1) * 16;
+                    v[u] = part_counts[(static_cast<size_t>(c) * pairs + (pairs - 1)) * words + (bin >> 1)];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (j0 + 256 * u < total) s += (v[u] >> sh[u]) & 0xffffu;
             }
         }
         for (int c = threadIdx.x; c < C; c += 256) s += part_orphan_last[static_cast<size_t>(c) * E + pe];

@@ -21,13 +21,33 @@ constexpr int kDispWaves = kDispThreads / kWave;
 constexpr int kDispChunk = 1024;  // assignments per workgroup in count / scatter
 constexpr int kDispFusedScanBlocks = 256;  // up to this many chunks every scatter workgroup scans the count matrix itself
 
-__device__ __forceinline__ int local_expert(const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ expert_map,
-                                            int64_t a, int E, int E_local)
+constexpr int kDispRounds = kDispChunk / kDispThreads;  // assignments per thread
+
+// Local expert ids of this thread's kDispRounds assignments (a = base + r*kDispThreads + tid), -1
+// for assignments past the end, outside [0,E) or mapped to no local expert.  All global ids are
+// loaded first and all map entries next, each through a clamped (never branched-around) address:
+// two memory round trips for the whole chunk instead of two per assignment.
+__device__ __forceinline__ void load_local_experts(const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ expert_map,
+                                                   int64_t base, int64_t A, int E, int E_local, int (&e)[kDispRounds])
 {
-    const int g = topk_idx[a];
-    if (g < 0 || g >= E) return -1;
-    const int e = expert_map != nullptr ? expert_map[g] : g;
-    return (e >= 0 && e < E_local) ? e : -1;
+    int g[kDispRounds];
+#pragma unroll
+    for (int r = 0; r < kDispRounds; ++r) {
+        const int64_t a = base + r * kDispThreads + threadIdx.x;
+        g[r] = topk_idx[min(a, A - 1)];
+        if (a >= A) g[r] = -1;
+    }
+    if (expert_map != nullptr) {
+#pragma unroll
+        for (int r = 0; r < kDispRounds; ++r) {
+            const bool ok = g[r] >= 0 && g[r] < E;
+            const int m = expert_map[ok ? g[r] : 0];
+            e[r] = (ok && m >= 0 && m < E_local) ? m : -1;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < kDispRounds; ++r) e[r] = (g[r] >= 0 && g[r] < E && g[r] < E_local) ? g[r] : -1;
+    }
 }
 
 __global__ __launch_bounds__(kDispThreads) void dispatch_count_kernel(const int32_t* __restrict__ topk_idx,
@@ -39,13 +59,11 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_count_kernel(const int3
     if (threadIdx.x < EXF_MAX_EXPERTS) cnt[threadIdx.x] = 0;
     __syncthreads();
     const int64_t base = static_cast<int64_t>(blockIdx.x) * kDispChunk;
-    for (int i = threadIdx.x; i < kDispChunk; i += kDispThreads) {
-        const int64_t a = base + i;
-        if (a < A) {
-            const int e = local_expert(topk_idx, expert_map, a, E, E_local);
-            if (e >= 0) atomicAdd(&cnt[e], 1);
-        }
-    }
+    int e[kDispRounds];
+    load_local_experts(topk_idx, expert_map, base, A, E, E_local, e);
+#pragma unroll
+    for (int r = 0; r < kDispRounds; ++r)
+        if (e[r] >= 0) atomicAdd(&cnt[e[r]], 1);
     __syncthreads();
     if (threadIdx.x < E_local) block_counts[static_cast<int64_t>(blockIdx.x) * E_local + threadIdx.x] = cnt[threadIdx.x];
 }
@@ -82,22 +100,43 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     int32_t* __restrict__ src_of_sorted, int32_t* __restrict__ sorted_of_src)
 {
     __shared__ int cursor[EXF_MAX_EXPERTS];               // next free sorted position per expert
-    __shared__ int wave_cnt[kDispWaves][EXF_MAX_EXPERTS];  // per-round, per-wavefront counts
+    __shared__ int wave_cnt[kDispRounds][kDispWaves][EXF_MAX_EXPERTS];  // per-round, per-wavefront counts
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
+    int e_mine[kDispRounds];
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kDispChunk;
+    load_local_experts(topk_idx, expert_map, base, A, E, E_local, e_mine);  // in flight during the scan
     if constexpr (FUSED_SCAN) {
-        if (wave == 0) {  // lane e walks down column e of the count matrix
-            int before = 0, total = 0;
-            if (lane < E_local) {
-                const int n_blocks = gridDim.x;
-                for (int b = 0; b < n_blocks; ++b) {
-                    const int c = block_base[static_cast<int64_t>(b) * E_local + lane];
-                    if (b < static_cast<int>(blockIdx.x)) before += c;
-                    total += c;
+        // column sums of the count matrix [chunks][E_local]: over all chunks (expert totals) and over
+        // the chunks before this one; all threads load side by side, four entries each per pass
+        __shared__ int col_total[EXF_MAX_EXPERTS], col_before[EXF_MAX_EXPERTS];
+        if (threadIdx.x < EXF_MAX_EXPERTS) {
+            col_total[threadIdx.x] = 0;
+            col_before[threadIdx.x] = 0;
+        }
+        __syncthreads();
+        const int n = static_cast<int>(gridDim.x) * E_local;
+        const int mine = static_cast<int>(blockIdx.x) * E_local;  // entries below belong to earlier chunks
+        constexpr int UL = 4;
+        for (int i0 = threadIdx.x; i0 < n; i0 += kDispThreads * UL) {
+            int c[UL];
+#pragma unroll
+            for (int u = 0; u < UL; ++u) c[u] = block_base[min(i0 + u * kDispThreads, n - 1)];
+#pragma unroll
+            for (int u = 0; u < UL; ++u) {
+                const int i = i0 + u * kDispThreads;
+                if (i < n && c[u] != 0) {
+                    const int q = i % E_local;
+                    atomicAdd(&col_total[q], c[u]);
+                    if (i < mine) atomicAdd(&col_before[q], c[u]);
                 }
             }
-            const int incl = wave_inclusive_scan(lane < E_local ? total : 0);
-            if (lane < E_local) cursor[lane] = incl - total + before;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const int total = lane < E_local ? col_total[lane] : 0;
+            const int incl = wave_inclusive_scan(total);
+            if (lane < E_local) cursor[lane] = incl - total + col_before[lane];
             if (blockIdx.x == 0) {
                 if (lane < E_local) {
                     expert_counts[lane] = total;
@@ -112,33 +151,37 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     }
     __syncthreads();
 
-    const int64_t base = static_cast<int64_t>(blockIdx.x) * kDispChunk;
+    // Rank of an assignment among the chunk's assignments to the same expert = those in earlier
+    // rounds and wavefronts (per-round, per-wavefront counts, exchanged through LDS once) plus the
+    // lanes below it in its own wavefront (ballot).  Assignments are numbered round-major, so this
+    // is ascending assignment order: the sort is stable and the permutation unique.
     const unsigned long long below = (1ull << lane) - 1ull;
-    for (int round = 0; round < kDispChunk / kDispThreads; ++round) {
-        const int64_t a = base + round * kDispThreads + threadIdx.x;
-        const int e = a < A ? local_expert(topk_idx, expert_map, a, E, E_local) : -1;
-        int rank = 0;
+    int rank[kDispRounds];
+#pragma unroll
+    for (int round = 0; round < kDispRounds; ++round) {
+        const int e = e_mine[round];
+        rank[round] = 0;
         for (int q = 0; q < E_local; ++q) {
             const unsigned long long m = __ballot(e == q);
-            if (e == q) rank = __popcll(m & below);
-            if (lane == q) wave_cnt[wave][q] = __popcll(m);
+            if (e == q) rank[round] = __popcll(m & below);
+            if (lane == q) wave_cnt[round][wave][q] = __popcll(m);
         }
-        __syncthreads();
+    }
+    __syncthreads();  // counts of all rounds and wavefronts, and the cursors, are in LDS
+#pragma unroll
+    for (int round = 0; round < kDispRounds; ++round) {
+        const int64_t a = base + round * kDispThreads + threadIdx.x;
+        const int e = e_mine[round];
         if (e >= 0) {
-            int pos = cursor[e] + rank;
-            for (int w = 0; w < wave; ++w) pos += wave_cnt[w][e];
+            int pos = cursor[e] + rank[round];
+            const int* earlier = &wave_cnt[0][0][e];
+            const int n_earlier = round * kDispWaves + wave;
+            for (int i = 0; i < n_earlier; ++i) pos += earlier[i * EXF_MAX_EXPERTS];
             src_of_sorted[pos] = static_cast<int32_t>(a);
             sorted_of_src[a] = pos;
         } else if (a < A) {
             sorted_of_src[a] = -1;
         }
-        __syncthreads();
-        if (threadIdx.x < E_local) {
-            int add = 0;
-            for (int w = 0; w < kDispWaves; ++w) add += wave_cnt[w][threadIdx.x];
-            cursor[threadIdx.x] += add;
-        }
-        __syncthreads();
     }
 }
 
