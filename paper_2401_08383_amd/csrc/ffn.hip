@@ -468,13 +468,15 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
         gemm_tile<MT, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end, tile.n_tile * NT, K,
                                                               N, out, smem);
     } else if constexpr (MT > kTailRows) {
-        // remainder rows: all wavefronts side by side over the columns, kTailRows rows each.  A
+        // remainder rows: the wavefronts side by side over the columns, kTailRows rows each (two rows
+        // of wavefronts when a column strip would become narrower than one MFMA tile).  A
         // tail stage is smaller than a full one, so the same LDS ring holds a deeper pipeline -
         // which the tail needs, because it has little MFMA work per K tile to hide the loads.
         constexpr int kRing = STAGES * (MT + NT) * KT * 2;
         constexpr int kFit = kRing / ((kTailRows + NT) * KT * 2);
         constexpr int STAGES_T = kFit >= 4 ? 4 : (kFit >= 3 ? 3 : 2);
-        gemm_tile<kTailRows, NT, KT, STAGES_T, 1, WM * WN, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end,
+        constexpr int WM_T = NT / (WM * WN) >= 32 ? 1 : 2;
+        gemm_tile<kTailRows, NT, KT, STAGES_T, WM_T, WM * WN / WM_T, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end,
                                                                            tile.n_tile * NT, K, N, out, smem);
     }
 }
@@ -605,10 +607,10 @@ static int launch_f32(const void* act, const int32_t* offsets, const void* weigh
 // Tile configuration <MT, NT, KT, STAGES, WM, WN, SWZ, OCC> of the two contractions
 // (OCC = wavefronts per SIMD the register allocation must leave room for).
 #ifndef EXF_GEMM1_CFG
-#define EXF_GEMM1_CFG 256, 256, 64, 2, 2, 2, 1, 1
+#define EXF_GEMM1_CFG 256, 256, 64, 2, 2, 4, 1, 1
 #endif
 #ifndef EXF_GEMM2_CFG
-#define EXF_GEMM2_CFG 256, 128, 64, 3, 2, 2, 1, 1
+#define EXF_GEMM2_CFG 256, 128, 64, 3, 4, 2, 1, 1
 #endif
 
 // Tuning builds (-DEXF_FFN_TUNE) can skip one of the two contractions to time the other alone.
