@@ -281,95 +281,120 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         else lds_dma_16B(wgt_b + kbyte, off_w[i >= LA ? i - LA : 0], stage + MT * RB + (wave * LW + (i - LA)) * 1024);
     };
 
+    // ---- main loop ---------------------------------------------------------------------------------
+    // One software pipeline over all K steps of the tile.  MFMA operands are double-buffered in
+    // registers and fetched one K step ahead, also across K tiles.  The barrier that hands over K
+    // tile kt+1 (everyone's share of it has landed; everyone is done reading tile kt) sits in the
+    // MIDDLE of the last K step of tile kt: the MFMAs issued just before it keep the matrix cores
+    // busy while the wavefronts meet, the MFMAs after it cover the latency of the first operand
+    // fetches from the new K tile.  At the barrier the stage of tile kt is free, so tile kt+STAGES
+    // is requested at once: all STAGES stages are in flight.  The issue order is hand-placed (the
+    // scheduling barriers pin it): slot m of a K step is MFMA m, operand fetches sit in front of
+    // slots, and the (slow to issue) direct-to-LDS loads go one at a time behind the slots that
+    // follow a hand-over.
+    static_assert(KSTEPS % 2 == 0, "register double-buffering assumes an even number of K steps per K tile");
     EXF_STAMP(1);
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
+    for (int s = 0; s < STAGES; ++s)
         if (s < nk) issue(s);
-
-#ifdef EXF_TUNE_TIMING
-    long long t_sync = 0, t_comp = 0;
-#endif
-    for (int kt = 0; kt < nk; ++kt) {
-#ifdef EXF_TUNE_TIMING
-        const long long c0 = clock64();
-#endif
-        // K tile kt must have landed; up to STAGES-2 younger tiles may still be in flight
-        const int younger = min(nk - 1, kt + STAGES - 2) - kt;
-        if constexpr (STAGES >= 4) {
-            if (younger >= 2) wait_vmcnt<2 * LPW>();
-            else if (younger == 1) wait_vmcnt<LPW>();
-            else wait_vmcnt<0>();
-        } else if constexpr (STAGES == 3) {
-            if (younger >= 1) wait_vmcnt<LPW>();
-            else wait_vmcnt<0>();
-        } else {
-            wait_vmcnt<0>();
-        }
-        __syncthreads();  // everyone's share of tile kt is in LDS, and everyone is done reading tile kt-1
-#ifdef EXF_TUNE_TIMING
-        const long long c1 = clock64();
-#endif
-        // Hand-placed issue order of a K tile (the scheduling barriers pin it).  Slot m of K step ks
-        // issues MFMA m.  In front of every few slots sits one operand fetch (LDS -> registers) for
-        // the next K step: MFMA operands are double-buffered in registers.  Behind the slots of the
-        // first K steps sits one direct-to-LDS load of a later K tile at a time: a global load can
-        // take long to issue, and issued as one burst the loads would keep the wavefront - and with
-        // it its matrix cores - waiting at the head of every K tile.
-        const bool do_load = kt + STAGES - 1 < nk;
-        const unsigned char* stage = smem + (kt % STAGES) * STAGE_BYTES;
-        const unsigned char* pw = stage + wgt_base;
-        const unsigned char* pa = stage + act_base;
-        bf16x8_t fa[2][TN], fb[2][TM];
+    {
+        const int younger = min(nk, STAGES) - 1;
+        static_assert(STAGES >= 2 && STAGES <= 8 && (STAGES - 1) * LPW < 64, "pipeline depth against the 6-bit vmcnt");
+        if (STAGES >= 8 && younger >= 7) wait_vmcnt<(STAGES >= 8 ? 7 : 0) * LPW>();
+        else if (STAGES >= 7 && younger >= 6) wait_vmcnt<(STAGES >= 7 ? 6 : 0) * LPW>();
+        else if (STAGES >= 6 && younger >= 5) wait_vmcnt<(STAGES >= 6 ? 5 : 0) * LPW>();
+        else if (STAGES >= 5 && younger >= 4) wait_vmcnt<(STAGES >= 5 ? 4 : 0) * LPW>();
+        else if (STAGES >= 4 && younger >= 3) wait_vmcnt<(STAGES >= 4 ? 3 : 0) * LPW>();
+        else if (STAGES >= 3 && younger >= 2) wait_vmcnt<(STAGES >= 3 ? 2 : 0) * LPW>();
+        else if (younger >= 1) wait_vmcnt<LPW>();
+        else wait_vmcnt<0>();
+    }
+    __syncthreads();
+    bf16x8_t fa[2][TN], fb[2][TM];
+    {
+        const unsigned char* pw = smem + wgt_base;
+        const unsigned char* pa = smem + act_base;
 #pragma unroll
         for (int a = 0; a < TN; ++a) fa[0][a] = *reinterpret_cast<const bf16x8_t*>(pw + a * 32 * RB + frag_off[0]);
 #pragma unroll
         for (int b = 0; b < TM; ++b) fb[0][b] = *reinterpret_cast<const bf16x8_t*>(pa + b * 32 * RB + frag_off[0]);
-        constexpr int SLOTS = TN * TM;
-        constexpr int SPREAD = KSTEPS >= 2 ? KSTEPS / 2 : 1;  // K steps that carry the global loads
-        constexpr int LOAD_SLOTS = SPREAD * SLOTS;
-        constexpr int READ_GAP = SLOTS / (TN + TM) > 0 ? SLOTS / (TN + TM) : 1;
-        constexpr int READS_PER_SLOT = (TN + TM + SLOTS - 1) / SLOTS;
+    }
+    constexpr int SLOTS = TN * TM;
+    constexpr int HALF = SLOTS / 2;                                     // MFMAs of the last K step in front of the hand-over
+    constexpr int NFRAG = TN + TM;
+    constexpr int READ_GAP = SLOTS / NFRAG > 0 ? SLOTS / NFRAG : 1;     // inside a K tile: one fetch every READ_GAP slots
+    constexpr int READS_PER_SLOT = (NFRAG + SLOTS - 1) / SLOTS;
+    constexpr int READS_PER_SLOT_LAST = (NFRAG + (SLOTS - HALF) - 1) / (SLOTS - HALF);  // behind the hand-over
+    constexpr int LOAD_SLOTS = (KSTEPS >= 4 ? 2 : 1) * SLOTS;            // slots over which a K tile's loads are spread
+    static_assert(LOAD_SLOTS <= KSTEPS * SLOTS, "a K tile's loads must all be issued before the next hand-over");
+    for (int kt = 0; kt < nk; ++kt) {
+        const unsigned char* stage_cur = smem + (kt % STAGES) * STAGE_BYTES;
+        const unsigned char* stage_nxt = smem + ((kt + 1) % STAGES) * STAGE_BYTES;
+        const bool more = kt + 1 < nk;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
-            const int ksn = ks + 1 < KSTEPS ? ks + 1 : KSTEPS - 1;
+            const bool last = ks == KSTEPS - 1;
+            const unsigned char* pw = (last ? stage_nxt : stage_cur) + wgt_base;
+            const unsigned char* pa = (last ? stage_nxt : stage_cur) + act_base;
+            const int fo = frag_off[last ? 0 : (ks + 1 < KSTEPS ? ks + 1 : 0)];
 #pragma unroll
             for (int m = 0; m < SLOTS; ++m) {
-                if (ks + 1 < KSTEPS && m % READ_GAP == 0) {
+                if (last && m == HALF) {
+                    if (more) {  // my share of K tile kt+1 has landed; younger tiles may still be in flight
+                        const int younger = min(nk - 1, kt + STAGES - 1) - (kt + 1);
+                        if (STAGES >= 8 && younger >= 6) wait_vmcnt<(STAGES >= 8 ? 6 : 0) * LPW>();
+                        else if (STAGES >= 7 && younger >= 5) wait_vmcnt<(STAGES >= 7 ? 5 : 0) * LPW>();
+                        else if (STAGES >= 6 && younger >= 4) wait_vmcnt<(STAGES >= 6 ? 4 : 0) * LPW>();
+                        else if (STAGES >= 5 && younger >= 3) wait_vmcnt<(STAGES >= 5 ? 3 : 0) * LPW>();
+                        else if (STAGES >= 4 && younger >= 2) wait_vmcnt<(STAGES >= 4 ? 2 : 0) * LPW>();
+                        else if (STAGES >= 3 && younger >= 1) wait_vmcnt<(STAGES >= 3 ? 1 : 0) * LPW>();
+                        else wait_vmcnt<0>();
+                    }
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // my operand fetches from tile kt are complete
+                    __syncthreads();
+                }
+                // operand fetches for the next K step
+                if (!last) {
+                    if (m % READ_GAP == 0) {
 #pragma unroll
-                    for (int q = 0; q < READS_PER_SLOT; ++q) {
-                        const int r = (m / READ_GAP) * READS_PER_SLOT + q;  // fetch number r of the next K step
-                        if (r < TN) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(pw + r * 32 * RB + frag_off[ksn]);
-                        else if (r < TN + TM) fb[nxt][r - TN] = *reinterpret_cast<const bf16x8_t*>(pa + (r - TN) * 32 * RB + frag_off[ksn]);
+                        for (int q = 0; q < READS_PER_SLOT; ++q) {
+                            const int r = (m / READ_GAP) * READS_PER_SLOT + q;
+                            if (r < TN) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(pw + r * 32 * RB + fo);
+                            else if (r < NFRAG) fb[nxt][r - TN] = *reinterpret_cast<const bf16x8_t*>(pa + (r - TN) * 32 * RB + fo);
+                        }
+                    }
+                } else if (m >= HALF && more) {
+#pragma unroll
+                    for (int q = 0; q < READS_PER_SLOT_LAST; ++q) {
+                        const int r = (m - HALF) * READS_PER_SLOT_LAST + q;
+                        if (r < TN) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(pw + r * 32 * RB + fo);
+                        else if (r < NFRAG) fb[nxt][r - TN] = *reinterpret_cast<const bf16x8_t*>(pa + (r - TN) * 32 * RB + fo);
                     }
                 }
                 acc[m / TM][m % TM] =
                     __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m / TM], fb[cur][m % TM], acc[m / TM][m % TM], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
 #ifndef EXF_TUNE_NO_LOAD
-                if (ks < SPREAD) {
-                    const int g = ks * SLOTS + m;  // load i goes behind slot i*LOAD_SLOTS/LPW
+                {
+                    // slot position since the latest hand-over, and the K tile refilled there
+                    const bool after = last && m >= HALF;
+                    const int p = after ? m - HALF : (SLOTS - HALF) + ks * SLOTS + m;
+                    const int load_tile = after ? kt + STAGES : kt - 1 + STAGES;
+                    if (p < LOAD_SLOTS) {
+                        const bool do_load = load_tile < nk && (after || kt >= 1);
 #pragma unroll
-                    for (int i = 0; i < LPW; ++i)
-                        if (i * LOAD_SLOTS / LPW == g && do_load) issue_one(kt + STAGES - 1, i);
-                    __builtin_amdgcn_sched_barrier(0);
+                        for (int i = 0; i < LPW; ++i)
+                            if (i * LOAD_SLOTS / LPW == p && do_load) issue_one(load_tile, i);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
 #endif
             }
         }
-#ifdef EXF_TUNE_TIMING
-        const long long c2 = clock64();
-        t_sync += c1 - c0;
-        t_comp += c2 - c1;
-#endif
     }
-#ifdef EXF_TUNE_TIMING
-    if (blockIdx.x < 64 * 8 && (blockIdx.x % 8) == 0 && threadIdx.x == 0) {
-        exf_tune_times[(blockIdx.x / 8) * 8 + 6] = t_sync;
-        exf_tune_times[(blockIdx.x / 8) * 8 + 7] = t_comp;
-    }
-#endif
-
+    EXF_STAMP(2);
+    EXF_STAMP(3);
     // ---- epilogue -----------------------------------------------------------------------------
     // A lane holds, for output row m = .. + lane%32, the columns n = .. + 8*g + 4*(lane/32) + r.
     // Writing that straight to memory would touch 32 rows per store instruction, so every
@@ -386,9 +411,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
 #ifdef EXF_TUNE_NO_EPI
     if (acc[0][0][0] != 123.456f) return;
 #endif
-    EXF_STAMP(2);
-    __syncthreads();  // every wavefront is done reading the last K tile
-    EXF_STAMP(3);
+    // (no barrier here: behind the last hand-over nobody reads the LDS ring any more)
     unsigned char* region = smem + wave * REGION;
     const int n_wave = n0 + wn * WTN;
     // bias of the 4 columns a lane owns in every (a, g) group; the same for all of its rows
@@ -474,7 +497,10 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
         // which the tail needs, because it has little MFMA work per K tile to hide the loads.
         constexpr int kRing = STAGES * (MT + NT) * KT * 2;
         constexpr int kFit = kRing / ((kTailRows + NT) * KT * 2);
-        constexpr int STAGES_T = kFit >= 4 ? 4 : (kFit >= 3 ? 3 : 2);
+#ifndef EXF_TAIL_STAGES_MAX
+#define EXF_TAIL_STAGES_MAX 4
+#endif
+        constexpr int STAGES_T = kFit >= EXF_TAIL_STAGES_MAX ? EXF_TAIL_STAGES_MAX : (kFit >= 2 ? kFit : 2);
         constexpr int WM_T = NT / (WM * WN) >= 32 ? 1 : 2;
         gemm_tile<kTailRows, NT, KT, STAGES_T, WM_T, WM * WN / WM_T, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end,
                                                                            tile.n_tile * NT, K, N, out, smem);
