@@ -310,21 +310,30 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         else wait_vmcnt<0>();
     }
     __syncthreads();
-    bf16x8_t fa[2][TN], fb[2][TM];
-    {
-        const unsigned char* pw = smem + wgt_base;
-        const unsigned char* pa = smem + act_base;
-#pragma unroll
-        for (int a = 0; a < TN; ++a) fa[0][a] = *reinterpret_cast<const bf16x8_t*>(pw + a * 32 * RB + frag_off[0]);
-#pragma unroll
-        for (int b = 0; b < TM; ++b) fb[0][b] = *reinterpret_cast<const bf16x8_t*>(pa + b * 32 * RB + frag_off[0]);
-    }
+    // Operand register ring: FD K steps deep (fetches run FD-1 K steps ahead of the MFMAs).  Two is
+    // enough when a K step holds many MFMAs; a wavefront tile of one or two MFMAs per K step (the
+    // remainder tiles) takes four, or every K step would expose a full LDS round trip.
+#ifndef EXF_FRAG_DEPTH_SMALL
+#define EXF_FRAG_DEPTH_SMALL 4  // (2 measured slower on remainder tiles)
+#endif
     constexpr int SLOTS = TN * TM;
-    constexpr int HALF = SLOTS / 2;                                     // MFMAs of the last K step in front of the hand-over
+    constexpr int FD = (SLOTS <= 2 && KSTEPS % EXF_FRAG_DEPTH_SMALL == 0) ? EXF_FRAG_DEPTH_SMALL : 2;
+    static_assert(KSTEPS % FD == 0, "the ring index of a K step must not depend on the K tile");
+    bf16x8_t fa[FD][TN], fb[FD][TM];
+    auto fetch = [&](const unsigned char* stage, int ks, int r) {  // operand r of K step ks from a stage
+        if (r < TN) fa[ks % FD][r] = *reinterpret_cast<const bf16x8_t*>(stage + wgt_base + r * 32 * RB + frag_off[ks]);
+        else fb[ks % FD][r - TN] = *reinterpret_cast<const bf16x8_t*>(stage + act_base + (r - TN) * 32 * RB + frag_off[ks]);
+    };
     constexpr int NFRAG = TN + TM;
+#pragma unroll
+    for (int ks = 0; ks < FD - 1; ++ks)
+#pragma unroll
+        for (int r = 0; r < NFRAG; ++r) fetch(smem, ks, r);
+    constexpr int HALF = SLOTS / 2;                                     // MFMAs of the last K step in front of the hand-over
     constexpr int READ_GAP = SLOTS / NFRAG > 0 ? SLOTS / NFRAG : 1;     // inside a K tile: one fetch every READ_GAP slots
     constexpr int READS_PER_SLOT = (NFRAG + SLOTS - 1) / SLOTS;
-    constexpr int READS_PER_SLOT_LAST = (NFRAG + (SLOTS - HALF) - 1) / (SLOTS - HALF);  // behind the hand-over
+    constexpr int NFRAG_HAND = (FD - 1) * NFRAG;                        // fetches behind a hand-over: K steps 0..FD-2 of the new tile
+    constexpr int READS_PER_SLOT_LAST = (NFRAG_HAND + (SLOTS - HALF) - 1) / (SLOTS - HALF);
     constexpr int LOAD_SLOTS = (KSTEPS >= 4 ? 2 : 1) * SLOTS;            // slots over which a K tile's loads are spread
     static_assert(LOAD_SLOTS <= KSTEPS * SLOTS, "a K tile's loads must all be issued before the next hand-over");
     for (int kt = 0; kt < nk; ++kt) {
@@ -333,11 +342,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         const bool more = kt + 1 < nk;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
+            const int cur = ks % FD;
             const bool last = ks == KSTEPS - 1;
-            const unsigned char* pw = (last ? stage_nxt : stage_cur) + wgt_base;
-            const unsigned char* pa = (last ? stage_nxt : stage_cur) + act_base;
-            const int fo = frag_off[last ? 0 : (ks + 1 < KSTEPS ? ks + 1 : 0)];
 #pragma unroll
             for (int m = 0; m < SLOTS; ++m) {
                 if (last && m == HALF) {
@@ -354,22 +360,22 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // my operand fetches from tile kt are complete
                     __syncthreads();
                 }
-                // operand fetches for the next K step
-                if (!last) {
+                // operand fetches: K step ks+FD-1 of this tile, or (behind the hand-over) the first
+                // FD-1 K steps of the next tile
+                if (ks + FD - 1 < KSTEPS) {
                     if (m % READ_GAP == 0) {
 #pragma unroll
                         for (int q = 0; q < READS_PER_SLOT; ++q) {
                             const int r = (m / READ_GAP) * READS_PER_SLOT + q;
-                            if (r < TN) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(pw + r * 32 * RB + fo);
-                            else if (r < NFRAG) fb[nxt][r - TN] = *reinterpret_cast<const bf16x8_t*>(pa + (r - TN) * 32 * RB + fo);
+                            if (r < NFRAG) fetch(stage_cur, ks + FD - 1 < KSTEPS ? ks + FD - 1 : 0, r);
                         }
                     }
-                } else if (m >= HALF && more) {
+                }
+                if (last && m >= HALF && more) {
 #pragma unroll
                     for (int q = 0; q < READS_PER_SLOT_LAST; ++q) {
-                        const int r = (m - HALF) * READS_PER_SLOT_LAST + q;
-                        if (r < TN) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(pw + r * 32 * RB + fo);
-                        else if (r < NFRAG) fb[nxt][r - TN] = *reinterpret_cast<const bf16x8_t*>(pa + (r - TN) * 32 * RB + fo);
+                        const int i = (m - HALF) * READS_PER_SLOT_LAST + q;
+                        if (i < NFRAG_HAND) fetch(stage_nxt, i / NFRAG, i % NFRAG);
                     }
                 }
                 acc[m / TM][m % TM] =
