@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per moe_expert_ffn call at the benchmark configuration, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch summed over the call's two launches), each
 # scaled by what the same counter reads for the 1 GiB copy probe (FETCH x2.000, WRITE x1.000):
-# (126681.4 + 138053.2) KiB x 2 + (65536 + 16384) KiB.  See profiles/bench_config2_hbm_traffic.txt.
-FFN_TRAFFIC_BYTES = int((126681.4 + 138053.2) * 2 * 1024 + (65536 + 16384) * 1024)
+# (81593.9 + 114006.2) KiB x 2 + (65536 + 16384) KiB.  See profiles/bench_config2_hbm_traffic.txt.
+FFN_TRAFFIC_BYTES = int((81593.9 + 114006.2) * 2 * 1024 + (65536 + 16384) * 1024)
 
 
 def _events(n):
@@ -135,6 +135,8 @@ def main():
                     help="workload configuration (default 2: the one the headline metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel and large-shape measurements")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="run the affinity statistic on the layer's stream instead of a second stream beside it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives, no sharding)",
@@ -187,11 +189,31 @@ def main():
         pl_h = syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(cfg.index, 5))
         aff = AffinityRun(torch.from_numpy(trace_h).to(dev), torch.from_numpy(pl_h).to(dev), cfg.trace_E, cfg.G)
 
+    # The affinity statistic reads a routing trace and nothing of the layer: it runs on a second
+    # stream (default priority) beside the layer's kernels, forked at the start of a step and joined
+    # at its end, and fills compute units the layer leaves idle (the sparse last round of the GEMMs).
+    main_stream = torch.cuda.current_stream()
+    side_stream = torch.cuda.Stream() if (aff is not None and not args.no_overlap) else None
+
+    def affinity_fork():
+        if aff is None:
+            return
+        if side_stream is None:
+            aff.step()
+            return
+        side_stream.wait_stream(main_stream)
+        with torch.cuda.stream(side_stream):
+            aff.step()
+
+    def affinity_join():
+        if side_stream is not None:
+            main_stream.wait_stream(side_stream)
+
     def step():
+        affinity_fork()
         for lay in layers:
             lay.step()
-        if aff is not None:
-            aff.step()
+        affinity_join()
 
     for _ in range(args.warmup):
         step()
@@ -199,6 +221,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
+        affinity_fork()
         for j, lay in enumerate(layers):
             lay.gate()
             lay.dispatch()
@@ -206,8 +229,7 @@ def main():
             lay.ffn()
             ffn_ev[i][j][1].record()
             lay.combine()
-        if aff is not None:
-            aff.step()
+        affinity_join()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
