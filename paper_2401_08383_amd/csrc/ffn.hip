@@ -11,12 +11,13 @@
 //   - macro tile MT x NT x KT, WM x WN wavefronts, each owning (MT/WM) x (NT/WN) as 32x32 MFMA
 //     tiles (v_mfma_f32_32x32x16_bf16, fp32 accumulators).
 //   - global -> LDS with direct-to-LDS 16-byte loads (no staging registers), STAGES-deep ring,
-//     one workgroup barrier per K tile.  A direct-to-LDS load writes 64 lanes x 16 B
-//     contiguously, so the LDS layout is fixed; bank conflicts on the MFMA operand reads are
-//     avoided by choosing WHICH 16-byte chunk of a row each lane fetches (XOR swizzle applied on
-//     the global side).
+//     one workgroup barrier per K tile, placed in the middle of a K step so that MFMAs are in
+//     flight on both sides of it.  A direct-to-LDS load writes 64 lanes x 16 B contiguously, so
+//     the LDS layout is fixed; bank conflicts on the MFMA operand reads are avoided by choosing
+//     WHICH 16-byte chunk of a row each lane fetches (XOR swizzle applied on the global side).
 //   - the weight tile feeds the MFMA row axis and the activation tile the column axis, so a lane
-//     ends up with 4 consecutive output columns of one row -> 8-byte bf16 stores.
+//     ends up with 4 consecutive output columns of one row; the epilogue transposes through LDS
+//     and stores 16-byte chunks of contiguous row segments.
 //   - workgroup -> tile order: consecutive ids go round-robin to the 8 XCDs, so id%8 selects the
 //     XCD and every XCD walks a contiguous range of tiles ordered (expert, column tile, row tile):
 //     the workgroups resident on one XCD share an expert's activation rows and a few weight

@@ -36,6 +36,7 @@ GATE_CASES = [
     ("bf16", 2500, 512, 32, 1, 0), ("bf16", 999, 1024, 64, 2, 1), ("bf16", 16, 4096, 64, 2, 1),
     ("bf16", 33000, 256, 48, 2, 0), ("bf16", 16500, 128, 64, 1, 0),
     ("bf16", 17000, 64, 8, 1, 0), ("bf16", 20001, 200, 20, 2, 1), ("bf16", 70000, 32, 33, 1, 0),
+    ("bf16", 16400, 1088, 16, 1, 0),  # 136 16-byte pieces per row: partial XOR swizzle of the LDS-resident gate weight
 ]
 
 
@@ -170,6 +171,12 @@ def test_ffn_bf16_parity(oracle, act, bias):
     _say(f"ffn bf16 act={act} bias={bias}")
     _ffn_case(oracle, "bf16", [130, 0, 257, 1, 128, 31], 128, 320, act, bias, seed=410 + act)
     _ffn_case(oracle, "bf16", [300], 64, 64, act, bias, seed=412)
+
+
+def test_ffn_bf16_long_reduction(oracle):
+    """Many K tiles per output tile (the LDS ring wraps several times), full, masked and tail row tiles."""
+    _say("ffn bf16 long K")
+    _ffn_case(oracle, "bf16", [600, 200, 70, 0, 256], 1024, 512, 0, False, seed=430)
 
 
 def test_ffn_bf16_many_experts_skewed(oracle):
