@@ -6,11 +6,13 @@
 //                scan down each expert column) plus expert_counts / expert_offsets.  Up to 256
 //                chunks every scatter workgroup does this for itself from the small matrix; a
 //                separate one-workgroup scan kernel serves longer inputs.
-//   3. scatter : every workgroup ranks its chunk again — rank inside a wavefront from a ballot
-//                per expert (lanes with a lower id and the same expert), wavefronts ordered
-//                through LDS — which keeps equal experts in ascending assignment order
-//                (stable, hence a unique permutation), and writes both index maps.
-//   4. gather  : x_sorted[s] = x[src_of_sorted[s] / k] as 16-byte vector copies.
+//   3. place   : every workgroup takes a slice of 32 or 64 assignments of one chunk, ranks it —
+//                assignments of the chunk in front of the slice recounted from the ids, rank
+//                inside the slice from a ballot per expert (lanes with a lower id and the same
+//                expert) — which keeps equal experts in ascending assignment order (stable, hence
+//                a unique permutation), writes both index maps and copies the slice's rows
+//                x_sorted[position] = x[assignment / k] as 16-byte vector copies.
+//                (Without rows to move, dispatch_scatter_kernel ranks whole chunks instead.)
 // No step needs the host to know a data-dependent size.
 #include "common.hpp"
 
@@ -185,72 +187,176 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     }
 }
 
-// x_sorted[s] = x[src_of_sorted[s] / k] for the kept rows, in batches of `row_batch` (at most 16) sorted rows per
-// wavefront: the lanes fetch the batch's source rows first, then the wavefront streams the batch
-// as a flat sequence of 16-byte chunks (`vec_per_row` = row bytes / 16), four per lane in flight.
-__global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ src_of_sorted,
-                                                               const int32_t* __restrict__ expert_offsets, int E_local, int k,
-                                                               int vec_per_row, int64_t A, int row_batch, uint4* __restrict__ x_sorted)
+// Scatter and row move in one launch (used whenever rows are moved).  A workgroup owns MOVE
+// consecutive assignments - a slice of one 1024-assignment chunk of the count matrix.  It
+//   - derives the chunk's start positions like dispatch_scatter_kernel (column sums, or the scanned
+//     matrix), adds the assignments of its chunk that precede its slice (recounted from the ids,
+//     LDS atomics), and ranks its own slice with per-expert ballots: stable, same permutation;
+//   - writes both index maps for its slice;
+//   - copies its rows x[a / k] -> x_sorted[position]: every wavefront takes MOVE/4 rows and streams
+//     them as a flat sequence of 16-byte chunks (`vec_per_row` = row bytes / 16) with non-temporal
+//     loads and stores, four chunks per lane in flight and the next four requested before these
+//     are stored (branch-free when every row of the wavefront is kept and the chunks divide evenly).
+template <bool FUSED_SCAN, int MOVE>
+__global__ __launch_bounds__(kDispThreads) void dispatch_place_kernel(
+    const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ expert_map, int64_t A, int E, int E_local, int n_coarse,
+    const int32_t* __restrict__ block_base, int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
+    int32_t* __restrict__ src_of_sorted, int32_t* __restrict__ sorted_of_src, const uint4* __restrict__ x, int k, int vec_per_row,
+    uint4* __restrict__ x_sorted)
 {
-    constexpr int U = 4;
+    static_assert(MOVE == 32 || MOVE == 64, "a slice is ranked by one wavefront and split over four");
+    constexpr int SUBS = kDispChunk / MOVE;  // slices per chunk
+    constexpr int ROWS = MOVE / kDispWaves;  // rows a wavefront moves
+    __shared__ int cursor[EXF_MAX_EXPERTS];  // start of the chunk inside every expert's bucket
+    __shared__ int pre[EXF_MAX_EXPERTS];     // assignments of the chunk in front of the slice, per expert
+    __shared__ int pos_s[MOVE];              // sorted position of every assignment of the slice (-1: not kept)
     const int lane = lane_id();
-    const int64_t kept = min(static_cast<int64_t>(max(expert_offsets[E_local], 0)), A);
-    const int64_t n_batches = (kept + row_batch - 1) / row_batch;
-    const int64_t n_waves = static_cast<int64_t>(gridDim.x) * (blockDim.x / kWave);
-    const float rcp = 1.0f / static_cast<float>(vec_per_row);
-    for (int64_t b = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave; b < n_batches; b += n_waves) {
-        const int64_t s0 = b * row_batch;
-        const int rows = static_cast<int>(min(static_cast<int64_t>(row_batch), kept - s0));
-        const int src_row = lane < rows ? src_of_sorted[s0 + lane] / k : 0;
-        const int total = rows * vec_per_row;
-        constexpr int kPass = kWave * U;  // chunks the wavefront moves per pass
-        if (total % kPass == 0) {
-            // Every lane has a chunk in every pass: no condition anywhere near the loads, and the loads
-            // of the next pass are issued before the stores of this one (with a branch around a load the
-            // compiler waits for all outstanding memory operations at every pass).
-            const int n_pass = total / kPass;
-            auto load_pass = [&](int pass, uint4(&v)[U]) {
+    const int wave = threadIdx.x / kWave;
+    const int cc = blockIdx.x / SUBS, sub = blockIdx.x % SUBS;
+    const int64_t base = static_cast<int64_t>(cc) * kDispChunk;
+    const int first = sub * MOVE;  // the slice: assignments base + first .. base + first + MOVE - 1
+    int e_mine[kDispRounds];
+    load_local_experts(topk_idx, expert_map, base, A, E, E_local, e_mine);  // whole chunk: thread t holds base + r*256 + t
+    if (threadIdx.x < EXF_MAX_EXPERTS) pre[threadIdx.x] = 0;
+    if constexpr (FUSED_SCAN) {
+        __shared__ int col_total[EXF_MAX_EXPERTS], col_before[EXF_MAX_EXPERTS];
+        if (threadIdx.x < EXF_MAX_EXPERTS) {
+            col_total[threadIdx.x] = 0;
+            col_before[threadIdx.x] = 0;
+        }
+        __syncthreads();
+        const int n = n_coarse * E_local;
+        const int mine = cc * E_local;  // entries below belong to earlier chunks
+        constexpr int UL = 4;
+        for (int i0 = threadIdx.x; i0 < n; i0 += kDispThreads * UL) {
+            int c[UL];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int c = pass * kPass + u * kWave + lane;
-                    const int r = row_of_chunk(c, vec_per_row, rcp);
-                    const int col = c - r * vec_per_row;
-                    const int t = __shfl(src_row, r, kWave);
-                    v[u] = load_stream16(x + static_cast<int64_t>(t) * vec_per_row + col);
+            for (int u = 0; u < UL; ++u) c[u] = block_base[min(i0 + u * kDispThreads, n - 1)];
+#pragma unroll
+            for (int u = 0; u < UL; ++u) {
+                const int i = i0 + u * kDispThreads;
+                if (i < n && c[u] != 0) {
+                    const int q = i % E_local;
+                    atomicAdd(&col_total[q], c[u]);
+                    if (i < mine) atomicAdd(&col_before[q], c[u]);
                 }
-            };
-            auto store_pass = [&](int pass, const uint4(&v)[U]) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) store_stream16(x_sorted + s0 * vec_per_row + pass * kPass + u * kWave + lane, v[u]);
-            };
-            uint4 cur[U], nxt[U];
-            load_pass(0, cur);
-            for (int pass = 0; pass + 1 < n_pass; ++pass) {
-                load_pass(pass + 1, nxt);
-                store_pass(pass, cur);
-#pragma unroll
-                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
             }
-            store_pass(n_pass - 1, cur);
-            continue;
         }
-        for (int c0 = lane; c0 < total; c0 += kWave * U) {  // ragged batch: every chunk checked
-            uint4 v[U];
+        __syncthreads();
+        if (wave == 0) {
+            const int total = lane < E_local ? col_total[lane] : 0;
+            const int incl = wave_inclusive_scan(total);
+            if (lane < E_local) cursor[lane] = incl - total + col_before[lane];
+            if (blockIdx.x == 0) {
+                if (lane < E_local) {
+                    expert_counts[lane] = total;
+                    expert_offsets[lane] = incl - total;
+                }
+                if (lane == E_local - 1) expert_offsets[E_local] = incl;
+            }
+        }
+    } else {
+        if (threadIdx.x < E_local)
+            cursor[threadIdx.x] = expert_offsets[threadIdx.x] + block_base[static_cast<int64_t>(cc) * E_local + threadIdx.x];
+        __syncthreads();
+    }
+    // assignments of the chunk in front of the slice
+#pragma unroll
+    for (int r = 0; r < kDispRounds; ++r) {
+        const int i = r * kDispThreads + static_cast<int>(threadIdx.x);
+        if (i < first && e_mine[r] >= 0) atomicAdd(&pre[e_mine[r]], 1);
+    }
+    __syncthreads();
+
+    // the slice sits in one round of one wavefront
+    const int round_s = first / kDispThreads, wave_s = (first % kDispThreads) / kWave, lane_s = first % kWave;
+    if (wave == wave_s) {
+        int e = -1;
+#pragma unroll
+        for (int r = 0; r < kDispRounds; ++r)
+            if (r == round_s) e = e_mine[r];
+        const bool in_slice = lane >= lane_s && lane < lane_s + MOVE;
+        if (!in_slice) e = -1;
+        const unsigned long long below = (1ull << lane) - 1ull;
+        int rank = 0;
+        for (int q = 0; q < E_local; ++q) {
+            const unsigned long long m = __ballot(e == q);
+            if (e == q) rank = __popcll(m & below);
+        }
+        if (in_slice) {
+            const int64_t a = base + first + (lane - lane_s);
+            int pos = -1;
+            if (e >= 0) {
+                pos = cursor[e] + pre[e] + rank;
+                src_of_sorted[pos] = static_cast<int32_t>(a);
+            }
+            if (a < A) sorted_of_src[a] = pos;
+            pos_s[lane - lane_s] = pos;
+        }
+    }
+    __syncthreads();
+
+    // ---- rows: wavefront w moves rows w*ROWS .. w*ROWS+ROWS-1 of the slice -----------------------
+    constexpr int U = 4;
+    int tok = 0, dst = -1;
+    if (lane < ROWS) {
+        const int j = wave * ROWS + lane;
+        tok = static_cast<int>(min(base + first + j, A - 1) / k);
+        dst = pos_s[j];
+    }
+    const float rcp = 1.0f / static_cast<float>(vec_per_row);
+    const int total = ROWS * vec_per_row;
+    constexpr int kPass = kWave * U;  // chunks the wavefront moves per pass
+    const bool all_kept = __ballot(lane < ROWS && dst < 0) == 0ull;
+    if (all_kept && total % kPass == 0) {
+        const int n_pass = total / kPass;
+        auto load_pass = [&](int pass, uint4(&v)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int c = c0 + u * kWave;
-                const bool live = c < total;
-                const int r = live ? row_of_chunk(c, vec_per_row, rcp) : 0;
+                const int c = pass * kPass + u * kWave + lane;
+                const int r = row_of_chunk(c, vec_per_row, rcp);
                 const int col = c - r * vec_per_row;
-                const int t = __shfl(src_row, r, kWave);
-                v[u] = live ? load_stream16(x + static_cast<int64_t>(t) * vec_per_row + col) : uint4{0u, 0u, 0u, 0u};
+                const int t = __shfl(tok, r, kWave);
+                v[u] = load_stream16(x + static_cast<int64_t>(t) * vec_per_row + col);
             }
+        };
+        auto store_pass = [&](int pass, const uint4(&v)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int c = c0 + u * kWave;
-                if (c < total) store_stream16(x_sorted + s0 * vec_per_row + c, v[u]);
+                const int c = pass * kPass + u * kWave + lane;
+                const int r = row_of_chunk(c, vec_per_row, rcp);
+                const int col = c - r * vec_per_row;
+                const int p = __shfl(dst, r, kWave);
+                store_stream16(x_sorted + static_cast<int64_t>(p) * vec_per_row + col, v[u]);
             }
+        };
+        uint4 cur[U], nxt[U];
+        load_pass(0, cur);
+        for (int pass = 0; pass + 1 < n_pass; ++pass) {
+            load_pass(pass + 1, nxt);
+            store_pass(pass, cur);
+#pragma unroll
+            for (int u = 0; u < U; ++u) cur[u] = nxt[u];
         }
+        store_pass(n_pass - 1, cur);
+        return;
+    }
+    for (int c0 = lane; c0 < total; c0 += kWave * U) {  // some row not kept, or a ragged chunk count: every chunk checked
+        uint4 v[U];
+        int p[U], col[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u * kWave;
+            const bool live = c < total;
+            const int r = live ? row_of_chunk(c, vec_per_row, rcp) : 0;
+            col[u] = c - r * vec_per_row;
+            const int t = __shfl(tok, r, kWave);
+            p[u] = live ? __shfl(dst, r, kWave) : -1;
+            v[u] = p[u] >= 0 ? load_stream16(x + static_cast<int64_t>(t) * vec_per_row + col[u]) : uint4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (p[u] >= 0) store_stream16(x_sorted + static_cast<int64_t>(p[u]) * vec_per_row + col[u], v[u]);
     }
 }
 
@@ -309,21 +415,30 @@ extern "C" int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_
         hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(kWave), 0, s, block_counts, n_blocks, E_local, expert_counts,
                            expert_offsets);
     if (n_blocks > 0) {
-        if (fused)
-            hipLaunchKernelGGL(dispatch_scatter_kernel<true>, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E,
-                               E_local, block_counts, expert_counts, expert_offsets, src_of_sorted, sorted_of_src);
-        else
-            hipLaunchKernelGGL(dispatch_scatter_kernel<false>, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E,
-                               E_local, block_counts, expert_counts, expert_offsets, src_of_sorted, sorted_of_src);
-        if (x_sorted != nullptr) {
+        if (x_sorted == nullptr) {  // index maps only
+            if (fused)
+                hipLaunchKernelGGL(dispatch_scatter_kernel<true>, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E,
+                                   E_local, block_counts, expert_counts, expert_offsets, src_of_sorted, sorted_of_src);
+            else
+                hipLaunchKernelGGL(dispatch_scatter_kernel<false>, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A,
+                                   E, E_local, block_counts, expert_counts, expert_offsets, src_of_sorted, sorted_of_src);
+        } else {
+            // index maps and rows in one launch; slices of 32 assignments while that still leaves few workgroups
             const int vec_per_row = d * (dt == EXF_BF16 ? 2 : 4) / 16;
-            const int row_batch = row_batch_for(A);
-            int64_t blocks = ((A + row_batch - 1) / row_batch + 3) / 4;  // four wavefronts (row batches) per workgroup
-            if (blocks > kStreamWorkgroups) blocks = kStreamWorkgroups;
-            if (blocks < 1) blocks = 1;
-            hipLaunchKernelGGL(dispatch_gather_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
-                               static_cast<const uint4*>(x), src_of_sorted, expert_offsets, E_local, k, vec_per_row, A, row_batch,
-                               static_cast<uint4*>(x_sorted));
+            const bool small = (A + 63) / 64 < 512;
+            const int move = small ? 32 : 64;
+            const unsigned grid = static_cast<unsigned>((A + move - 1) / move);
+            const uint4* xs = static_cast<const uint4*>(x);
+            uint4* xd = static_cast<uint4*>(x_sorted);
+#define EXF_LAUNCH_PLACE(FUSED, MOVE)                                                                                             \
+    hipLaunchKernelGGL((dispatch_place_kernel<FUSED, MOVE>), dim3(grid), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E,     \
+                       E_local, n_blocks, block_counts, expert_counts, expert_offsets, src_of_sorted, sorted_of_src, xs, k,       \
+                       vec_per_row, xd)
+            if (fused && small) EXF_LAUNCH_PLACE(true, 32);
+            else if (fused) EXF_LAUNCH_PLACE(true, 64);
+            else if (small) EXF_LAUNCH_PLACE(false, 32);
+            else EXF_LAUNCH_PLACE(false, 64);
+#undef EXF_LAUNCH_PLACE
         }
     }
     return check_launch("moe_dispatch");
