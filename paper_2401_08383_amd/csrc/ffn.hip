@@ -86,7 +86,10 @@ __device__ unsigned long long exf_tune_times[8 * 64];
 // cheap tail tiles therefore fill the last round of the launch.
 constexpr int kTailRows = 64;
 __host__ __device__ constexpr int max_tail_tiles(int mt) { return mt / 2 >= kTailRows ? (mt / 2 + kTailRows - 1) / kTailRows : 1; }
-constexpr int kXcdChunk = 16;  // consecutive tiles handed to one XCD at a time
+#ifndef EXF_XCD_CHUNK
+#define EXF_XCD_CHUNK 32
+#endif
+constexpr int kXcdChunk = EXF_XCD_CHUNK;  // consecutive tiles handed to one XCD at a time (32: one per CU of the XCD)
 
 struct Tile2D {
     int expert;
