@@ -142,11 +142,31 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
     const int e_rt = __shfl(rt, src, kWave);
     const int e_full = __shfl(full_rt, src, kWave);
     const int r = j - __shfl(excl, src, kWave);
-    const int row_tile = r % e_rt;
+    // Order of the expert's tiles.  With many row tiles, consecutive tiles form blocks of kBlockRows
+    // row tiles x kBlockCols column tiles (one XCD chunk): the 32 workgroups of a block share 4
+    // activation and 8 weight panels in their L2, against 16 and 2 when the rows of a column simply
+    // follow each other.  Remaining row tiles (and small experts) run row tile fastest.
+#ifndef EXF_BLOCK_ROWS
+#define EXF_BLOCK_ROWS 4
+#endif
+    constexpr int kBlockRows = EXF_BLOCK_ROWS, kBlockCols = kXcdChunk / (EXF_BLOCK_ROWS > 0 ? EXF_BLOCK_ROWS : 1);
+    int row_tile, col_tile;
+    const int blocked_rows = (kBlockRows > 0 && !tail && n_tiles % (kBlockCols > 0 ? kBlockCols : 1) == 0) ? e_rt / kBlockRows * kBlockRows : 0;
+    if (r < blocked_rows * n_tiles) {
+        const int per_row_block = kBlockRows * n_tiles;
+        const int rbk = r / per_row_block, in_rb = r - rbk * per_row_block;
+        const int cb = in_rb / (kBlockRows * kBlockCols), in_b = in_rb - cb * (kBlockRows * kBlockCols);
+        col_tile = cb * kBlockCols + in_b / kBlockRows;
+        row_tile = rbk * kBlockRows + in_b % kBlockRows;
+    } else {
+        const int rr = r - blocked_rows * n_tiles, rows_left = e_rt - blocked_rows;
+        col_tile = rr / rows_left;
+        row_tile = blocked_rows + rr % rows_left;
+    }
     const int begin = tail ? e_lo + e_full * mt + row_tile * kTailRows : e_lo + row_tile * mt;
     // every lane holds the same values; readfirstlane tells the compiler so (scalar registers)
     out.expert = __builtin_amdgcn_readfirstlane(src);
-    out.n_tile = __builtin_amdgcn_readfirstlane(r / e_rt);
+    out.n_tile = __builtin_amdgcn_readfirstlane(col_tile);
     out.row_begin = __builtin_amdgcn_readfirstlane(begin);
     out.row_end = __builtin_amdgcn_readfirstlane(min(begin + (tail ? kTailRows : mt), e_hi));
     out.tail = tail;
