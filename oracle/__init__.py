@@ -203,3 +203,57 @@ def placement_locality_from_counts(counts, placement):
     _load().ref_placement_locality_from_counts(_p(counts, c_i64), _p(placement, c_i32), Lm1 + 1, E,
                                                _p(out, c_i64))
     return out
+
+
+# --------------------------------------------------------------------------- placement search
+# Design, "Solving Affinity's duality by Integer Programming": minimise the number of crossing
+# transitions sum_k sum_j R_{k,j} subject to load balance (every part holds E/P experts of every
+# layer) and exclusivity (every expert on exactly one part).  In terms of the co-routing counts the
+# objective is  total - sum_l sum_{i,p} counts[l][i][p] * [part_l(i) == part_{l+1}(p)],  so the
+# optimum MAXIMISES the local transitions.  The functions below enumerate; they are for tiny cases.
+def balanced_partitions(E, P):
+    """All maps expert -> part in [0,P) with exactly E/P experts per part (labelled parts)."""
+    import itertools
+
+    assert E % P == 0
+    cap = E // P
+    out = []
+
+    def rec(e, cur, left):
+        if e == E:
+            out.append(tuple(cur))
+            return
+        for p in range(P):
+            if left[p] > 0:
+                left[p] -= 1
+                cur.append(p)
+                rec(e + 1, cur, left)
+                cur.pop()
+                left[p] += 1
+
+    rec(0, [], [cap] * P)
+    del itertools
+    return out
+
+
+def placement_bruteforce(counts, P):
+    """Exhaustive optimum of the integer program on tiny instances.
+
+    counts int64 [L-1,E,E].  Tries EVERY combination of balanced partitions of the L layers
+    (no decomposition, no pruning) and returns (best_local_total, placement int32 [L,E]) for the
+    first combination, in lexicographic order, that attains the maximum of the local transitions.
+    """
+    import itertools
+
+    counts = _i64(counts)
+    Lm1, E, _ = counts.shape
+    L = Lm1 + 1
+    parts = balanced_partitions(E, P)
+    assert len(parts) ** L <= 3_000_000, "brute force is for tiny instances only"
+    best, best_pl = -1, None
+    for combo in itertools.product(parts, repeat=L):
+        pl = np.asarray(combo, dtype=np.int32)
+        total = int(placement_locality_from_counts(counts, pl).sum())
+        if total > best:
+            best, best_pl = total, pl
+    return best, best_pl
