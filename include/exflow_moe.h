@@ -195,6 +195,37 @@ int placement_locality(const int32_t* trace, const int32_t* placement, int L, in
 int exf_check_placement(const int32_t* placement_host, int L, int E, int G);
 
 /* ---------------------------------------------------------------------------------------
+ * Placement search driven by the statistic (Design, "Solving Affinity's duality by Integer
+ * Programming": minimise the crossing transitions under the load-balance and exclusivity
+ * constraints; "Staged Experts Affinity": first between nodes, then between the GPUs of a node).
+ * In terms of the co-routing counts a map keeps
+ *     local[l] = sum_{i,p} counts[l][i][p] * [ placement[l][i] == placement[l+1][p] ]
+ * transitions of layer pair l local; the objective of the integer program is the total number
+ * of counted transitions minus sum_l local[l].
+ *
+ * placement_locality_from_counts (GPU): scores a batch of B candidate maps.
+ *   counts      device int64 [L-1,E,E]   (as written by affinity_histogram)
+ *   placements  device int32 [B,L,E]     any values; maps are scored as given
+ *   local       device int64 [B,L-1]     out; exact integer sums
+ *   Nothing is written when B == 0 or L == 1.  1 <= L <= EXF_MAX_TRACE_LAYERS,
+ *   1 <= E <= EXF_MAX_EXPERTS, 0 <= B <= 2^24.  Asynchronous on `stream`, no workspace.
+ *
+ * exf_placement_search (host): counts_host is a HOST array [L-1,E,E] of non-negative counts;
+ *   placement_host [L,E] (HOST, out) receives the GPU of every expert, GPUs numbered so that node
+ *   = gpu / (G / nodes).  Requires nodes | G | E.  Stage 1 partitions the experts of every layer
+ *   over the nodes, stage 2 partitions every node's experts over its GPUs using the transitions
+ *   that stay inside the node.  A stage is solved exactly (dynamic programme over the chain of
+ *   layers) when a layer has at most 128 balanced partitions, otherwise by a greedy
+ *   layer-by-layer assignment refined by pairwise swaps, best of `restarts` (>= 1) starts drawn
+ *   from `seed`.  The result always satisfies exf_check_placement.  Deterministic for given
+ *   arguments.  The paper names no solver; this one is this library's own.
+ * ------------------------------------------------------------------------------------- */
+int placement_locality_from_counts(const int64_t* counts, const int32_t* placements, int B, int L,
+                                   int E, int64_t* local, void* stream);
+int exf_placement_search(const int64_t* counts_host, int L, int E, int G, int nodes, int restarts,
+                         uint64_t seed, int32_t* placement_host);
+
+/* ---------------------------------------------------------------------------------------
  * Measurement probes (no counterpart in the paper; used by the benchmark to report achieved
  * rates next to the data-sheet peaks and to calibrate the profiler's HBM byte counters).
  *   exf_probe_copy: dst[0..bytes) = src[0..bytes), a plain streaming copy; bytes % 16 == 0,

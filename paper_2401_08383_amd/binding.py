@@ -45,6 +45,8 @@ SIGNATURES = {
     "affinity_histogram": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "placement_locality_workspace_bytes": (_sz, [_i, _i64]),
     "placement_locality": (_i, [_vp, _vp, _i, _i64, _i, _i, _vp, _vp, _sz, _vp]),
+    "placement_locality_from_counts": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp]),
+    "exf_placement_search": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_uint64, _vp]),
     "exf_probe_copy": (_i, [_vp, _vp, _sz, _vp]),
     "exf_probe_mfma": (_i, [_i, _i, _vp, _vp]),
 }
@@ -227,6 +229,26 @@ def placement_locality(trace, placement, G, workspace=None, out=None):
         workspace = _workspace(nbytes, trace.device)
     _check(lib().placement_locality(_ptr(trace), _ptr(placement), L, N, E, G, _ptr(out), _ptr(workspace), workspace.numel(),
                                     _stream()))
+    return out
+
+
+def placement_locality_from_counts(counts, placements, out=None):
+    """counts int64 [L-1,E,E] (device), placements int32 [B,L,E] (device) -> local int64 [B,L-1] (device)."""
+    B, L, E = placements.shape
+    assert counts.shape == (L - 1, E, E) and counts.dtype == torch.int64 and placements.dtype == torch.int32
+    assert counts.is_contiguous() and placements.is_contiguous()
+    if out is None:
+        out = torch.empty((B, max(L - 1, 0)), dtype=torch.int64, device=counts.device)
+    _check(lib().placement_locality_from_counts(_ptr(counts), _ptr(placements), B, L, E, _ptr(out), _stream()))
+    return out
+
+
+def placement_search(counts_host, G, nodes=1, restarts=4, seed=0):
+    """counts_host int64 [L-1,E,E] (torch CPU) -> placement int32 [L,E] (torch CPU): the host solver."""
+    assert counts_host.device.type == "cpu" and counts_host.dtype == torch.int64 and counts_host.is_contiguous()
+    Lm1, E, _ = counts_host.shape
+    out = torch.empty((Lm1 + 1, E), dtype=torch.int32)
+    _check(lib().exf_placement_search(counts_host.data_ptr(), Lm1 + 1, E, G, nodes, restarts, seed, out.data_ptr()))
     return out
 
 

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(PKG, "libexflow_moe.so")
-SOURCES = ["api.hip", "gate.hip", "dispatch.hip", "ffn.hip", "combine.hip", "affinity.hip", "probe.hip"]
+SOURCES = ["api.hip", "gate.hip", "dispatch.hip", "ffn.hip", "combine.hip", "affinity.hip", "placement.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
