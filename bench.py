@@ -358,6 +358,27 @@ def main():
                                      "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
         result["hbm_bound_calls_config4_shapes"] = hbm
 
+        # placement search on the one-GPU-share trace (24 layers x 1M tokens, E=64, 8 GPUs on 2 nodes):
+        # counts on the GPU, host solver, GPU batch scoring of {found, default, random} from the counts
+        res4 = B.affinity_histogram(base, c4.trace_E)
+        counts4_host = res4["counts"].cpu()
+        t_s = time.perf_counter()
+        found = B.placement_search(counts4_host, c4.G, nodes=2, restarts=2, seed=1)
+        solver_s = time.perf_counter() - t_s
+        cands = torch.stack([found, torch.from_numpy(syn.contiguous_placement(c4.trace_L, c4.trace_E, c4.G)),
+                             torch.from_numpy(syn.balanced_random_placement(c4.trace_L, c4.trace_E, c4.G, 11))]).to(dev)
+        many = cands[torch.arange(4096, device=dev) % 3].contiguous()  # a search-sized batch for the timing
+        score_out = torch.empty((4096, c4.trace_L - 1), dtype=torch.int64, device=dev)
+        ms = _time_call(lambda: B.placement_locality_from_counts(res4["counts"], many, out=score_out), 20)
+        sc = B.placement_locality_from_counts(res4["counts"], cands).sum(dim=1).cpu().numpy()
+        total = float(c4.trace_N) * (c4.trace_L - 1)
+        node_sc = B.placement_locality_from_counts(res4["counts"], (cands // (c4.G // 2)).to(torch.int32).contiguous()).sum(dim=1).cpu().numpy()
+        result["placement_search"] = {
+            "trace": "24 layers x 1048576 tokens, E=64, planted affinity rho=0.7", "gpus": c4.G, "nodes": 2,
+            "host_solver_s": solver_s, "gpu_score_4096_maps_ms": ms, "maps_per_s": 4096 / (ms * 1e-3),
+            "gpu_locality": {"found": sc[0] / total, "contiguous": sc[1] / total, "random": sc[2] / total},
+            "node_locality": {"found": node_sc[0] / total, "contiguous": node_sc[1] / total, "random": node_sc[2] / total}}
+
     if not args.no_cpu_baseline and host is not None:
         result["cpu_baseline"] = cpu_baseline(cfg, host[0], host[1], host[2], host[3], trace_h, pl_h)
     else:
