@@ -24,7 +24,6 @@
 //     panels in that XCD's L2.
 // fp32 kernel: LDS-tiled 64x64x16, 4x4 outputs per thread (tiny configuration; latency bound).
 #include <math.h>
-#include <stdlib.h>
 
 #include "common.hpp"
 
@@ -65,16 +64,6 @@ __device__ __forceinline__ float gelu_tanh_fast(float z)
 
 enum Epilogue { kEpiNone = 0, kEpiGeluErf = 1, kEpiGeluTanh = 2 };
 
-#ifdef EXF_TUNE_TIMING
-__device__ unsigned long long exf_tune_times[8 * 64];
-#define EXF_STAMP(slot)                                                                   \
-    do {                                                                                  \
-        if (blockIdx.x < 64 * 8 && (blockIdx.x % 8) == 0 && threadIdx.x == 0)             \
-            exf_tune_times[(blockIdx.x / 8) * 8 + (slot)] = clock64();                    \
-    } while (0)
-#else
-#define EXF_STAMP(slot) do { } while (0)
-#endif
 
 // ---------------------------------------------------------------------------- tile lookup
 // Rows of expert e are cut into "full" row tiles of MT rows.  A remainder of at most MT/2 rows is
@@ -317,7 +306,6 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     // slots, and the (slow to issue) direct-to-LDS loads go one at a time behind the slots that
     // follow a hand-over.
     static_assert(KSTEPS % 2 == 0, "register double-buffering assumes an even number of K steps per K tile");
-    EXF_STAMP(1);
 #pragma unroll
     for (int s = 0; s < STAGES; ++s)
         if (s < nk) issue(s);
@@ -405,7 +393,6 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
                 acc[m / TM][m % TM] =
                     __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m / TM], fb[cur][m % TM], acc[m / TM][m % TM], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-#ifndef EXF_TUNE_NO_LOAD
                 {
                     // slot position since the latest hand-over, and the K tile refilled there
                     const bool after = last && m >= HALF;
@@ -419,12 +406,9 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
-#endif
             }
         }
     }
-    EXF_STAMP(2);
-    EXF_STAMP(3);
     // ---- epilogue -----------------------------------------------------------------------------
     // A lane holds, for output row m = .. + lane%32, the columns n = .. + 8*g + 4*(lane/32) + r.
     // Writing that straight to memory would touch 32 rows per store instruction, so every
@@ -438,9 +422,6 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     constexpr int RPI_OUT = 64 / CW;               // rows covered by one wavefront-wide 16-byte access
     static_assert(NWAVES * REGION <= STAGES * STAGE_BYTES, "epilogue staging must fit in the LDS ring");
     static_assert(64 % CW == 0 && (BP * 32) % RPI_OUT == 0, "row segments must tile the wavefront");
-#ifdef EXF_TUNE_NO_EPI
-    if (acc[0][0][0] != 123.456f) return;
-#endif
     // (no barrier here: behind the last hand-over nobody reads the LDS ring any more)
     unsigned char* region = smem + wave * REGION;
     const int n_wave = n0 + wn * WTN;
@@ -495,11 +476,6 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
                 *reinterpret_cast<uint4*>(out + static_cast<size_t>(m) * N + n) = val;
         }
     }
-    EXF_STAMP(4);
-#ifdef EXF_TUNE_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    EXF_STAMP(5);
-#endif
 }
 
 template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int OCC, int EPI, bool BIAS>
@@ -511,7 +487,6 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
                                                                          bf16_t* __restrict__ out)           // [A,N]
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    EXF_STAMP(0);
     Tile2D tile;
     const int n_tiles = (N + NT - 1) / NT;
     if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, tile_index_of_workgroup(blockIdx.x), tile)) return;
@@ -669,26 +644,8 @@ static int launch_f32(const void* act, const int32_t* offsets, const void* weigh
 #define EXF_GEMM2_CFG 256, 128, 64, 3, 4, 2, 1, 1
 #endif
 
-// Tuning builds (-DEXF_FFN_TUNE) can skip one of the two contractions to time the other alone.
-static bool tune_skip(int which)
-{
-#ifdef EXF_FFN_TUNE
-    const char* only = getenv("EXF_TUNE_ONLY");
-    return only != nullptr && atoi(only) != 0 && atoi(only) != which;
-#else
-    (void)which;
-    return false;
-#endif
-}
-
 }  // namespace exf
 
-#ifdef EXF_TUNE_TIMING
-extern "C" int exf_tune_read_times(unsigned long long* host)
-{
-    return hipMemcpyFromSymbol(host, HIP_SYMBOL(exf::exf_tune_times), sizeof(unsigned long long) * 8 * 64) == hipSuccess ? 0 : -5;
-}
-#endif
 
 extern "C" size_t moe_expert_ffn_workspace_bytes(int64_t A, int d, int f, int E_local, int dt)
 {
@@ -741,8 +698,8 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
         if (rc == EXF_OK) rc = launch_f32(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
     } else {
         rc = EXF_OK;
-        if (!tune_skip(1)) rc = launch_bf16<EXF_GEMM1_CFG>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s);
-        if (rc == EXF_OK && !tune_skip(2))
+        rc = launch_bf16<EXF_GEMM1_CFG>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s);
+        if (rc == EXF_OK)
             rc = launch_bf16<EXF_GEMM2_CFG>(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
     }
     if (rc != EXF_OK) return rc;
