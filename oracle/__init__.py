@@ -205,6 +205,19 @@ def placement_locality_from_counts(counts, placement):
     return out
 
 
+def routing_away(trace, placement, home):
+    """away int64 [L]: tokens whose layer-l expert sits on another GPU than their request's home."""
+    trace = _i32(trace)
+    placement = _i32(placement)
+    home = _i32(home)
+    L, N = trace.shape
+    E = placement.shape[1]
+    assert placement.shape[0] == L and home.shape == (N,)
+    out = np.zeros(L, dtype=np.int64)
+    _load().ref_routing_away(_p(trace, c_i32), _p(placement, c_i32), _p(home, c_i32), L, c_i64(N), E, _p(out, c_i64))
+    return out
+
+
 # --------------------------------------------------------------------------- placement search
 # Design, "Solving Affinity's duality by Integer Programming": minimise the number of crossing
 # transitions sum_k sum_j R_{k,j} subject to load balance (every part holds E/P experts of every

@@ -317,3 +317,28 @@ void ref_placement_locality_from_counts(const int64_t* counts, const int32_t* pl
         local_per_pair[l] = c;
     }
 }
+
+/* -------------------------------------------------------------------------------------
+ * Cross-GPU token transfers of a routing trace (Design, "Token Context Coherence in Expert
+ * Parallelism": the walk-through of the 3-layer example; Table "Comparison with state-of-the-art
+ * GPT MoE optimization methods": p = ratio of tokens involved in the Alltoall).
+ *   away[l]  = #{ n : placement[l][tr[l][n]] != home[n] }   tokens whose layer-l expert is not on
+ *              the GPU that owns their request
+ * Vanilla expert parallelism sends such a token out and back at every layer: 2 * sum_l away[l]
+ * transfers.  With coherent contexts a token travels from its home to the first expert and then
+ * only when consecutive experts sit on different GPUs: away[0] + sum_l (transitions - local[l])
+ * with local[l] of ref_placement_locality.  Entries with an invalid expert id are not counted.
+ * ---------------------------------------------------------------------------------- */
+void ref_routing_away(const int32_t* trace, const int32_t* placement, const int32_t* home, int L,
+                      int64_t N, int E, int64_t* away_per_layer)
+{
+    for (int l = 0; l < L; ++l) {
+        int64_t c = 0;
+        for (int64_t n = 0; n < N; ++n) {
+            int32_t e = trace[(int64_t)l * N + n];
+            if (e < 0 || e >= E) continue;
+            if (placement[(int64_t)l * E + e] != home[n]) c += 1;
+        }
+        away_per_layer[l] = c;
+    }
+}

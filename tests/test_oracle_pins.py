@@ -441,3 +441,58 @@ def test_locality_statistics_random_and_aligned(oracle):
     # and it beats the default contiguous placement clearly
     frac_default = oracle.placement_locality(trace, syn.contiguous_placement(L, E, G)).sum() / (N * (L - 1))
     assert frac > frac_default + 0.3
+
+
+def test_routing_away_reproduces_the_printed_transfer_counts(oracle):
+    """The walk-through's numbers from the counters alone: vanilla 2*sum(away) = 4 and 6,
+    coherent away[0] + crossings = 3 and 1, and 1 for token 1 under the panel (c) placement."""
+    with open(os.path.join(GOLDEN, "fig_compare_example.json")) as fh:
+        ex = json.load(fh)
+    L, E, G = ex["layers"], ex["experts"], ex["gpus"]
+    default = syn.contiguous_placement(L, E, G)
+    trace = np.array([t["experts"] for t in ex["tokens"]], dtype=np.int32).T.copy()   # [L, 2]
+    home = np.array([t["home_gpu"] for t in ex["tokens"]], dtype=np.int32)
+    for n in range(2):
+        tr = trace[:, n:n + 1].copy()
+        away = oracle.routing_away(tr, default, home[n:n + 1])
+        local = oracle.placement_locality(tr, default)
+        assert 2 * int(away.sum()) == ex["vanilla_transfers"][n]
+        assert int(away[0]) + (L - 1) - int(local.sum()) == ex["coherent_transfers"][n]
+    both = oracle.routing_away(trace, default, home)
+    assert 2 * int(both.sum()) == sum(ex["vanilla_transfers"])
+    pc = np.full((L, E), -1, dtype=np.int32)
+    for l in range(L):
+        on0 = ex["panel_c_gpu0"][f"layer{l}"]
+        pc[l, on0] = 0
+        rest = [e for e in range(E) if e not in on0]
+        pc[l, rest] = 1 + np.arange(len(rest)) // 2
+    tr = trace[:, 0:1].copy()
+    away = oracle.routing_away(tr, pc, home[0:1])
+    assert int(away[0]) + (L - 1) - int(oracle.placement_locality(tr, pc).sum()) == ex["panel_c_token1_transfers"]
+
+
+def test_routing_away_closed_forms(oracle):
+    L, N, E, G = 5, 4000, 8, 4
+    trace, _ = syn.planted_trace(L, N, E, 0.5, seed=83)
+    g = syn.rng(84)
+    home = g.integers(0, G, size=N).astype(np.int32)
+    pl = syn.balanced_random_placement(L, E, G, seed=85)
+    away = oracle.routing_away(trace, pl, home)
+    # the definition, vectorised independently
+    dev = np.take_along_axis(pl, trace, axis=1)
+    np.testing.assert_array_equal(away, (dev != home[None, :]).sum(axis=1))
+    # every expert on GPU 0 and every token at home on GPU 0: nothing is ever away
+    assert (oracle.routing_away(trace, np.zeros((L, E), np.int32), np.zeros(N, np.int32)) == 0).all()
+    # home outside the placement's range: everything is away
+    assert (oracle.routing_away(trace, pl, np.full(N, G, np.int32)) == N).all()
+    # invalid ids are skipped
+    bad = trace.copy()
+    bad[2, :100] = E
+    bad[3, :50] = -1
+    a2 = oracle.routing_away(bad, pl, np.full(N, G, np.int32))
+    assert a2[2] == N - 100 and a2[3] == N - 50 and a2[0] == N
+    # uniform homes, balanced placement, uniform routing: about (G-1)/G of the tokens are away
+    tr_u, _ = syn.planted_trace(L, 40000, E, 0.0, seed=86)
+    home_u = syn.rng(87).integers(0, G, size=40000).astype(np.int32)
+    frac = oracle.routing_away(tr_u, pl, home_u).sum() / (40000 * L)
+    assert abs(frac - (G - 1) / G) < 0.01
