@@ -373,6 +373,24 @@ def main():
         sc = B.placement_locality_from_counts(res4["counts"], cands).sum(dim=1).cpu().numpy()
         total = float(c4.trace_N) * (c4.trace_L - 1)
         node_sc = B.placement_locality_from_counts(res4["counts"], (cands // (c4.G // 2)).to(torch.int32).contiguous()).sum(dim=1).cpu().numpy()
+        # cross-GPU transfers of the trace (requests owned by uniformly drawn GPUs): ratio of token-layer
+        # visits that take part in an Alltoall, vanilla (out and back) against coherent contexts
+        gh = torch.Generator(device="cpu")
+        gh.manual_seed(syn.seed_for(4, 7))
+        home4 = torch.randint(0, c4.G, (c4.trace_N,), generator=gh, dtype=torch.int32).to(dev)
+        ws_rt = torch.empty(max(lib.routing_transfers_workspace_bytes(c4.trace_L, c4.trace_N), 256), dtype=torch.uint8, device=dev)
+        visits = float(c4.trace_N) * c4.trace_L
+        ratios = {}
+        for name, pl_t in (("found", cands[0]), ("contiguous", cands[1])):
+            loc_t, away_t = B.routing_transfers(base, pl_t.contiguous(), home4, c4.G, workspace=ws_rt)
+            away_sum, loc_sum, away0 = float(away_t.sum()), float(loc_t.sum()), float(away_t[0])
+            ratios[name] = {"vanilla_p": away_sum / visits, "coherent_p_star": (away0 + total - loc_sum) / visits,
+                            "transfers_vanilla": 2.0 * away_sum, "transfers_coherent": away0 + total - loc_sum}
+        ms_rt = _time_rotating(lambda i: (lambda: B.routing_transfers(traces[i], cands[0], home4, c4.G, workspace=ws_rt)), tr_sets, 30)
+        bytes_rt = bytes_tr + 4 * c4.trace_N
+        result["routing_transfers"] = {"ms": ms_rt, "GBps": bytes_rt / (ms_rt * 1e-3) / 1e9,
+                                       "frac": bytes_rt / (ms_rt * 1e-3) / 1e9 / PEAK_HBM_GBS, "bytes": bytes_rt,
+                                       "alltoall_token_ratio": ratios}
         result["placement_search"] = {
             "trace": "24 layers x 1048576 tokens, E=64, planted affinity rho=0.7", "gpus": c4.G, "nodes": 2,
             "host_solver_s": solver_s, "gpu_score_4096_maps_ms": ms, "maps_per_s": 4096 / (ms * 1e-3),

@@ -189,6 +189,27 @@ size_t placement_locality_workspace_bytes(int L, int64_t N);
 int placement_locality(const int32_t* trace, const int32_t* placement, int L, int64_t N, int E, int G,
                        int64_t* local_per_pair, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * routing_transfers — the cross-GPU token transfers of a routing trace under a placement
+ * (Design, "Token Context Coherence in Expert Parallelism": the walk-through that counts 4 and 6
+ * transfers for vanilla expert parallelism against 3 and 1 with coherent contexts; the table
+ * "Comparison with state-of-the-art GPT MoE optimization methods": p, the ratio of tokens
+ * involved in the Alltoall).  One pass over the trace yields
+ *   local_per_pair[l]  as placement_locality                                    int64 [L-1]
+ *   away_per_layer[l] = #{ n : placement[l][trace[l][n]] != home[n] }           int64 [L]
+ * where home [N] int32 (device) is the GPU that owns the request of token n (any values).
+ * Vanilla expert parallelism moves 2 * sum_l away_per_layer[l] tokens; with coherent contexts
+ * the count is away_per_layer[0] + sum_l (valid transitions of pair l - local_per_pair[l]).
+ * Entries with an invalid expert id are not counted.  (The per-destination send buffer itself
+ * is moe_dispatch with expert_map = the placement row of the layer and E_local = G: rows come
+ * out grouped by destination GPU, stable, with the send counts in expert_counts.)
+ * workspace: routing_transfers_workspace_bytes(L, N) bytes.  local_per_pair may be NULL if L == 1.
+ * ------------------------------------------------------------------------------------- */
+size_t routing_transfers_workspace_bytes(int L, int64_t N);
+int routing_transfers(const int32_t* trace, const int32_t* placement, const int32_t* home, int L,
+                      int64_t N, int E, int G, int64_t* local_per_pair, int64_t* away_per_layer,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* Host helper: placement is a HOST array [L,E].  Returns EXF_OK iff every entry is in [0,G)
  * and every device holds exactly E/G experts of every layer (the load-balance and
  * exclusivity constraints of the integer program); EXF_ERR_BAD_SHAPE otherwise. */

@@ -23,4 +23,7 @@ from .binding import (  # noqa: F401
     moe_gate_topk,
     moe_topk_from_logits,
     placement_locality,
+    placement_locality_from_counts,
+    placement_search,
+    routing_transfers,
 )

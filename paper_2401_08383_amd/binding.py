@@ -45,6 +45,8 @@ SIGNATURES = {
     "affinity_histogram": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "placement_locality_workspace_bytes": (_sz, [_i, _i64]),
     "placement_locality": (_i, [_vp, _vp, _i, _i64, _i, _i, _vp, _vp, _sz, _vp]),
+    "routing_transfers_workspace_bytes": (_sz, [_i, _i64]),
+    "routing_transfers": (_i, [_vp, _vp, _vp, _i, _i64, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "placement_locality_from_counts": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp]),
     "exf_placement_search": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_uint64, _vp]),
     "exf_probe_copy": (_i, [_vp, _vp, _sz, _vp]),
@@ -230,6 +232,23 @@ def placement_locality(trace, placement, G, workspace=None, out=None):
     _check(lib().placement_locality(_ptr(trace), _ptr(placement), L, N, E, G, _ptr(out), _ptr(workspace), workspace.numel(),
                                     _stream()))
     return out
+
+
+def routing_transfers(trace, placement, home, G, workspace=None):
+    """-> (local_per_pair int64 [L-1], away_per_layer int64 [L]) on the device."""
+    L, N = trace.shape
+    E = placement.shape[1]
+    assert placement.shape[0] == L and home.shape == (N,)
+    assert trace.dtype == placement.dtype == home.dtype == torch.int32
+    assert trace.is_contiguous() and placement.is_contiguous() and home.is_contiguous()
+    local = torch.empty(max(L - 1, 0), dtype=torch.int64, device=trace.device)
+    away = torch.empty(L, dtype=torch.int64, device=trace.device)
+    nbytes = lib().routing_transfers_workspace_bytes(L, N)
+    if workspace is None:
+        workspace = _workspace(nbytes, trace.device)
+    _check(lib().routing_transfers(_ptr(trace), _ptr(placement), _ptr(home), L, N, E, G, _ptr(local), _ptr(away), _ptr(workspace),
+                                   workspace.numel(), _stream()))
+    return local, away
 
 
 def placement_locality_from_counts(counts, placements, out=None):

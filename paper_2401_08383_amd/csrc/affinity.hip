@@ -350,16 +350,22 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
 // ------------------------------------------------------------------------------------------
 constexpr int kLocAhead = EXF_LOC_AHEAD;  // trace layers whose loads are in flight together
 
-template <int VEC>
+// HOME: additionally counts, per layer, the tokens whose expert sits on another device than
+// home[n] (the device that owns the token's request); the per-chunk partials then hold the L-1 pair
+// counts followed by the L away counts.
+template <int VEC, bool HOME>
 __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const int32_t* __restrict__ trace,
-                                                                          const int32_t* __restrict__ placement, int L, int64_t N,
-                                                                          int E, int64_t chunk, uint32_t* __restrict__ part)
+                                                                          const int32_t* __restrict__ placement,
+                                                                          const int32_t* __restrict__ home, int L, int64_t N, int E,
+                                                                          int64_t chunk, uint32_t* __restrict__ part)
 {
     extern __shared__ int32_t lds_i[];
     int32_t* pl = lds_i;                                              // [L][E]
-    uint32_t* pair_cnt = reinterpret_cast<uint32_t*>(lds_i + L * E);  // [L-1]
+    uint32_t* pair_cnt = reinterpret_cast<uint32_t*>(lds_i + L * E);  // [L-1] pairs, then (HOME) [L] away counts
+    uint32_t* away_cnt = pair_cnt + (L - 1);
+    const int n_out = (L - 1) + (HOME ? L : 0);
     for (int i = threadIdx.x; i < L * E; i += kTraceThreads) pl[i] = placement[i];
-    for (int i = threadIdx.x; i < L - 1; i += kTraceThreads) pair_cnt[i] = 0u;
+    for (int i = threadIdx.x; i < n_out; i += kTraceThreads) pair_cnt[i] = 0u;
     __syncthreads();
 
     const int lane = lane_id();
@@ -371,15 +377,21 @@ __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const i
         bool ok_prev[VEC];
         const bool in_range = n0 + VEC <= n_end;  // all tokens of this lane exist
         bool prev_clean;                           // all ids of the previous layer valid (and in range)
+        TokVec<VEC> hm;
+        if constexpr (HOME) hm = load_tokens<VEC>(home, n0, n_end);
         {
             const TokVec<VEC> t = load_tokens<VEC>(trace, n0, n_end);
             prev_clean = in_range;
+            int away = 0;
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
                 ok_prev[u] = (n0 + u < n_end) && static_cast<unsigned>(t.v[u]) < static_cast<unsigned>(E);
                 dev_prev[u] = ok_prev[u] ? pl[t.v[u]] : 0;
                 prev_clean = prev_clean && ok_prev[u];
+                if constexpr (HOME) away += __popcll(__ballot(ok_prev[u] && dev_prev[u] != hm.v[u]));
             }
+            if constexpr (HOME)
+                if (lane == 0 && away != 0) atomicAdd(&away_cnt[0], static_cast<uint32_t>(away));
         }
         auto load_layers = [&](int lb, TokVec<VEC>(&dst)[kLocAhead]) {
 #pragma unroll
@@ -401,7 +413,7 @@ __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const i
                 for (int u = 0; u < VEC; ++u) m = max(m, static_cast<unsigned>(cur[a].v[u]));
                 const bool clean = in_range && m < static_cast<unsigned>(E);
                 // wavefront total of "device unchanged" flags by ballot + popcount (scalar unit)
-                int same = 0;
+                int same = 0, away = 0;
                 if (__ballot(!(clean && prev_clean)) == 0ull) {
                     // fast path: every id of this wavefront is valid in both layers - one table
                     // look-up and one compare per transition
@@ -409,6 +421,7 @@ __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const i
                     for (int u = 0; u < VEC; ++u) {
                         const int dev = pl[l * E + cur[a].v[u]];
                         same += __popcll(__ballot(dev == dev_prev[u]));
+                        if constexpr (HOME) away += __popcll(__ballot(dev != hm.v[u]));
                         dev_prev[u] = dev;
                     }
                 } else {
@@ -417,10 +430,13 @@ __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const i
                         const bool ok = (n0 + u < n_end) && static_cast<unsigned>(cur[a].v[u]) < static_cast<unsigned>(E);
                         const int dev = ok ? pl[l * E + cur[a].v[u]] : 0;
                         same += __popcll(__ballot(ok && ok_prev[u] && dev == dev_prev[u]));
+                        if constexpr (HOME) away += __popcll(__ballot(ok && dev != hm.v[u]));
                         ok_prev[u] = ok;
                         dev_prev[u] = dev;
                     }
                 }
+                if constexpr (HOME)
+                    if (lane == 0 && away != 0) atomicAdd(&away_cnt[l], static_cast<uint32_t>(away));
                 if (clean) {  // the flags the checked path would have produced
 #pragma unroll
                     for (int u = 0; u < VEC; ++u) ok_prev[u] = true;
@@ -433,17 +449,23 @@ __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const i
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < L - 1; i += kTraceThreads) part[static_cast<size_t>(blockIdx.x) * (L - 1) + i] = pair_cnt[i];
+    for (int i = threadIdx.x; i < n_out; i += kTraceThreads) part[static_cast<size_t>(blockIdx.x) * n_out + i] = pair_cnt[i];
 }
 
-__global__ __launch_bounds__(kWave) void locality_finalize_kernel(const uint32_t* __restrict__ part, int C, int pairs,
-                                                                   int64_t* __restrict__ local_per_pair)
+// One wavefront per output element j: the first `pairs` elements go to local_per_pair, the rest
+// (present with home devices only) to away_per_layer.
+__global__ __launch_bounds__(kWave) void locality_finalize_kernel(const uint32_t* __restrict__ part, int C, int pairs, int n_out,
+                                                                   int64_t* __restrict__ local_per_pair,
+                                                                   int64_t* __restrict__ away_per_layer)
 {
-    const int l = blockIdx.x;
+    const int j = blockIdx.x;
     long long s = 0;
-    for (int c = threadIdx.x; c < C; c += kWave) s += part[static_cast<size_t>(c) * pairs + l];
+    for (int c = threadIdx.x; c < C; c += kWave) s += part[static_cast<size_t>(c) * n_out + j];
     s = wave_sum(s);
-    if (threadIdx.x == 0) local_per_pair[l] = s;
+    if (threadIdx.x == 0) {
+        if (j < pairs) local_per_pair[j] = s;
+        else away_per_layer[j - pairs] = s;
+    }
 }
 
 static int64_t locality_chunk(int64_t N, int vec)
@@ -554,13 +576,63 @@ extern "C" int placement_locality(const int32_t* trace, const int32_t* placement
     if (C > 0) {
         const size_t lds = (static_cast<size_t>(L) * E + (L - 1)) * sizeof(int32_t);
         if (vec == 4) {
-            if (int rc = allow_large_lds(locality_partial_kernel<4>, lds, "placement_locality")) return rc;
-            hipLaunchKernelGGL(locality_partial_kernel<4>, dim3(C), dim3(kTraceThreads), lds, s, trace, placement, L, N, E, chunk, part);
+            if (int rc = allow_large_lds(locality_partial_kernel<4, false>, lds, "placement_locality")) return rc;
+            hipLaunchKernelGGL((locality_partial_kernel<4, false>), dim3(C), dim3(kTraceThreads), lds, s, trace, placement, nullptr, L, N,
+                               E, chunk, part);
         } else {
-            if (int rc = allow_large_lds(locality_partial_kernel<1>, lds, "placement_locality")) return rc;
-            hipLaunchKernelGGL(locality_partial_kernel<1>, dim3(C), dim3(kTraceThreads), lds, s, trace, placement, L, N, E, chunk, part);
+            if (int rc = allow_large_lds(locality_partial_kernel<1, false>, lds, "placement_locality")) return rc;
+            hipLaunchKernelGGL((locality_partial_kernel<1, false>), dim3(C), dim3(kTraceThreads), lds, s, trace, placement, nullptr, L, N,
+                               E, chunk, part);
         }
     }
-    hipLaunchKernelGGL(locality_finalize_kernel, dim3(L - 1), dim3(kWave), 0, s, part, C, L - 1, local_per_pair);
+    hipLaunchKernelGGL(locality_finalize_kernel, dim3(L - 1), dim3(kWave), 0, s, part, C, L - 1, L - 1, local_per_pair, nullptr);
     return check_launch("placement_locality");
+}
+
+extern "C" size_t routing_transfers_workspace_bytes(int L, int64_t N)
+{
+    if (L < 1 || N < 0) return 0;
+    const int64_t chunk = exf::locality_chunk(N, 1);  // the scalar plan has the most chunks
+    const int64_t C = N > 0 ? (N + chunk - 1) / chunk : 0;
+    return exf::align_up(static_cast<size_t>(C > 0 ? C : 1) * static_cast<size_t>(2 * L - 1) * sizeof(uint32_t), 256);
+}
+
+extern "C" int routing_transfers(const int32_t* trace, const int32_t* placement, const int32_t* home, int L, int64_t N, int E, int G,
+                                 int64_t* local_per_pair, int64_t* away_per_layer, void* workspace, size_t workspace_bytes,
+                                 void* stream)
+{
+    using namespace exf;
+    if (int rc = validate_trace_args("routing_transfers", L, N, E)) return rc;
+    if (G < 1) return fail(EXF_ERR_BAD_SHAPE, "routing_transfers: G = %d < 1", G);
+    EXF_REQUIRE_PTR(placement);
+    EXF_REQUIRE_PTR(away_per_layer);
+    if (L > 1) EXF_REQUIRE_PTR(local_per_pair);
+    EXF_REQUIRE_PTR(workspace);
+    if (N > 0) {
+        EXF_REQUIRE_PTR(trace);
+        EXF_REQUIRE_PTR(home);
+    }
+    if (workspace_bytes < routing_transfers_workspace_bytes(L, N))
+        return fail(EXF_ERR_WORKSPACE_TOO_SMALL, "routing_transfers: workspace %zu < %zu bytes", workspace_bytes,
+                    routing_transfers_workspace_bytes(L, N));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int vec = (aligned16(trace) && aligned16(home) && N % 4 == 0) ? 4 : 1;
+    const int64_t chunk = locality_chunk(N, vec);
+    const int C = static_cast<int>(N > 0 ? (N + chunk - 1) / chunk : 0);
+    uint32_t* part = static_cast<uint32_t*>(workspace);
+    const int n_out = 2 * L - 1;
+    if (C > 0) {
+        const size_t lds = (static_cast<size_t>(L) * E + n_out) * sizeof(int32_t);
+        if (vec == 4) {
+            if (int rc = allow_large_lds(locality_partial_kernel<4, true>, lds, "routing_transfers")) return rc;
+            hipLaunchKernelGGL((locality_partial_kernel<4, true>), dim3(C), dim3(kTraceThreads), lds, s, trace, placement, home, L, N, E,
+                               chunk, part);
+        } else {
+            if (int rc = allow_large_lds(locality_partial_kernel<1, true>, lds, "routing_transfers")) return rc;
+            hipLaunchKernelGGL((locality_partial_kernel<1, true>), dim3(C), dim3(kTraceThreads), lds, s, trace, placement, home, L, N, E,
+                               chunk, part);
+        }
+    }
+    hipLaunchKernelGGL(locality_finalize_kernel, dim3(n_out), dim3(kWave), 0, s, part, C, L - 1, n_out, local_per_pair, away_per_layer);
+    return check_launch("routing_transfers");
 }

@@ -131,3 +131,60 @@ def test_gpu_search_pipeline_on_a_trace():
         on_trace = exf.placement_locality(tr, torch.from_numpy(cands[b]).to(dev), G).cpu().numpy()
         np.testing.assert_array_equal(scores[b], on_trace)
     assert scores[0].sum() >= scores[3].sum() > scores[1].sum()
+
+
+# ----------------------------------------------------------------------------- transfer counters
+@pytest.mark.gpu
+@pytest.mark.parametrize("L,N,E,G", [(3, 2, 8, 4), (1, 777, 8, 2), (12, 8192, 8, 4), (5, 100001, 64, 8), (24, 1 << 18, 64, 8), (6, 70003, 16, 2)])
+def test_routing_transfers_parity(L, N, E, G):
+    print(f"[case] routing_transfers L={L} N={N} E={E} G={G}", flush=True)
+    dev = "cuda:0"
+    trace, _ = syn.planted_trace(L, N, E, 0.6, seed=800 + L + E)
+    g = syn.rng(801 + N)
+    if N > 1000:  # invalid ids in a few places
+        trace[L // 2, 17:900:13] = E + 3
+        trace[0, 5:600:11] = -2
+    home = g.integers(0, G, size=N).astype(np.int32)
+    pl = syn.balanced_random_placement(L, E, G, seed=802)
+    local, away = exf.routing_transfers(torch.from_numpy(trace).to(dev), torch.from_numpy(pl).to(dev), torch.from_numpy(home).to(dev), G)
+    np.testing.assert_array_equal(away.cpu().numpy(), oracle.routing_away(trace, pl, home))
+    np.testing.assert_array_equal(local.cpu().numpy(), oracle.placement_locality(trace, pl))
+
+
+@pytest.mark.gpu
+def test_routing_transfers_paper_worked_example_on_gpu():
+    import json
+    import os
+    print("[case] routing_transfers worked example", flush=True)
+    with open(os.path.join(os.path.dirname(__file__), "golden", "fig_compare_example.json")) as fh:
+        ex = json.load(fh)
+    L, E, G = ex["layers"], ex["experts"], ex["gpus"]
+    dev = "cuda:0"
+    default = torch.from_numpy(syn.contiguous_placement(L, E, G)).to(dev)
+    for tok, vanilla, coherent in zip(ex["tokens"], ex["vanilla_transfers"], ex["coherent_transfers"]):
+        tr = torch.tensor(tok["experts"], dtype=torch.int32).reshape(L, 1).to(dev)
+        home = torch.tensor([tok["home_gpu"]], dtype=torch.int32, device=dev)
+        local, away = exf.routing_transfers(tr, default, home, G)
+        assert 2 * int(away.sum()) == vanilla                                   # printed: 4 and 6
+        assert int(away[0]) + (L - 1) - int(local.sum()) == coherent            # printed: 3 and 1
+
+
+@pytest.mark.gpu
+def test_send_buffer_is_a_dispatch_by_destination():
+    """The per-destination send buffer of the single Alltoall: moe_dispatch with the layer's
+    placement row as expert_map groups the rows by destination GPU, stable, counts = send counts."""
+    print("[case] send buffer", flush=True)
+    T, d, E, G = 3000, 128, 32, 8
+    dev = "cuda:0"
+    g = syn.rng(811)
+    x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), "bf16")
+    idx = g.integers(0, E, size=(T, 1)).astype(np.int32)
+    row = syn.balanced_random_placement(1, E, G, seed=812)[0]
+    res = exf.moe_dispatch(torch.from_numpy(x).to(torch.bfloat16).to(dev), torch.from_numpy(idx).to(dev), E, G,
+                           torch.from_numpy(row).to(dev))
+    ref = oracle.dispatch(idx, row, E, G)
+    np.testing.assert_array_equal(res.expert_counts.cpu().numpy(), np.bincount(row[idx[:, 0]], minlength=G))
+    np.testing.assert_array_equal(res.src_of_sorted.cpu().numpy(), ref["src_of_sorted"])
+    dest_sorted = row[idx[res.src_of_sorted.cpu().numpy(), 0]]
+    assert (np.diff(dest_sorted) >= 0).all()                                     # grouped by destination
+    np.testing.assert_array_equal(res.x_sorted.float().cpu().numpy(), x[ref["src_of_sorted"]])
