@@ -4,7 +4,7 @@
 // keeping several 16-byte loads in flight.
 //
 // affinity_histogram
-//   partial : a workgroup owns a chunk of tokens (< 65536) and a group of g <= 6 consecutive
+//   partial : a workgroup owns a chunk of tokens (< 65536) and a group of g <= 3 consecutive
 //             layer pairs.  A thread loads the g+1 trace columns of its tokens at once, then walks
 //             the pairs and bins every transition with one LDS atomic.  The g E x E histograms
 //             live in LDS as 16-bit counters packed two to a word (a workgroup can never count
@@ -39,7 +39,10 @@ constexpr int kXcds = 8;
 #define EXF_LOC_AHEAD 2
 #endif
 constexpr int kTraceThreads = EXF_TRACE_THREADS;
-constexpr int kAffMaxGroup = 6;                        // layer pairs per workgroup (7 columns in registers)
+#ifndef EXF_AFF_GROUP
+#define EXF_AFF_GROUP 3
+#endif
+constexpr int kAffMaxGroup = EXF_AFF_GROUP;                        // layer pairs per workgroup (4 columns in registers; 3 measured best, 29 against 34 us with 6 on a 24 x 1M trace)
 constexpr size_t kAffHistBudget = 48 * 1024;           // LDS bytes for the packed pair histograms
 constexpr int64_t kAffMaxChunk = 61440;                // tokens per workgroup: 16-bit counters cannot overflow
 constexpr int kTargetWorkgroups = EXF_TARGET_WGS;       // about one per CU
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
     uint32_t* my_hist = hist + (threadIdx.x & (copies - 1)) * g * words;
     uint32_t invalid_local = 0;
 
-    // Software pipeline over the sweeps of the chunk: the (up to seven) 16-byte column loads of the
+    // Software pipeline over the sweeps of the chunk: the (up to four) 16-byte column loads of the
     // NEXT sweep are issued before the current sweep is binned, so that the memory system is never
     // idle while the LDS atomics run.
     const int64_t sweep = static_cast<int64_t>(kTraceThreads) * VEC;
