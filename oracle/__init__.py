@@ -205,6 +205,21 @@ def placement_locality_from_counts(counts, placement):
     return out
 
 
+def multihop_pair_index(L, l, m):
+    """Position of the layer pair (l, m), l < m, in the source-layer-first order."""
+    assert 0 <= l < m < L
+    return l * L - l * (l + 1) // 2 + (m - l - 1)
+
+
+def affinity_counts_multihop(trace, E):
+    """counts int64 [L(L-1)/2, E, E] for every ordered layer pair l < m (source layer first)."""
+    trace = _i32(trace)
+    L, N = trace.shape
+    counts = np.zeros((L * (L - 1) // 2, E, E), dtype=np.int64)
+    _load().ref_affinity_counts_multihop(_p(trace, c_i32), L, c_i64(N), E, _p(counts, c_i64))
+    return counts
+
+
 def routing_away(trace, placement, home):
     """away int64 [L]: tokens whose layer-l expert sits on another GPU than their request's home."""
     trace = _i32(trace)

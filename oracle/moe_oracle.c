@@ -342,3 +342,26 @@ void ref_routing_away(const int32_t* trace, const int32_t* placement, const int3
         away_per_layer[l] = c;
     }
 }
+
+/* -------------------------------------------------------------------------------------
+ * Affinity across several layers (appendix "Extend Expert Affinity to Cross Multiple Layers":
+ * the affinity of layer l's experts to the experts of ALL following layers).  The same count
+ * as ref_affinity_counts for every ordered pair of layers l < l':
+ *   counts[p(l,l')][i][j] = #{ n : tr[l][n] == i and tr[l'][n] == j },  both ids valid,
+ * pairs numbered source layer first:  p(l,l') = l*L - l*(l+1)/2 + (l' - l - 1).
+ * ---------------------------------------------------------------------------------- */
+void ref_affinity_counts_multihop(const int32_t* trace, int L, int64_t N, int E, int64_t* counts)
+{
+    int64_t p = 0;
+    for (int l = 0; l < L; ++l)
+        for (int m = l + 1; m < L; ++m, ++p) {
+            int64_t* c = counts + p * E * E;
+            for (int64_t i = 0; i < (int64_t)E * E; ++i) c[i] = 0;
+            for (int64_t n = 0; n < N; ++n) {
+                int32_t a = trace[(int64_t)l * N + n];
+                int32_t b = trace[(int64_t)m * N + n];
+                if (a < 0 || a >= E || b < 0 || b >= E) continue;
+                c[(int64_t)a * E + b] += 1;
+            }
+        }
+}

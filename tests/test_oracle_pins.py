@@ -496,3 +496,43 @@ def test_routing_away_closed_forms(oracle):
     home_u = syn.rng(87).integers(0, G, size=40000).astype(np.int32)
     frac = oracle.routing_away(tr_u, pl, home_u).sum() / (40000 * L)
     assert abs(frac - (G - 1) / G) < 0.01
+
+
+def test_multihop_counts_pins(oracle):
+    """Appendix statistic: adjacent pairs equal the one-hop counts; every pair equals an
+    independently written scatter-add; on a deterministic chain the counts sit on the composed
+    permutations; row / column sums are the layer loads."""
+    L, N, E = 5, 3000, 8
+    trace, perms = syn.planted_trace(L, N, E, 0.6, seed=91)
+    trace[2, 10:200:7] = E        # a few invalid ids
+    trace[0, 3:90:5] = -1
+    multi = oracle.affinity_counts_multihop(trace, E)
+    assert multi.shape == (L * (L - 1) // 2, E, E)
+    one_hop, loads, _ = oracle.affinity_counts(trace, E)
+    for l in range(L - 1):
+        np.testing.assert_array_equal(multi[oracle.multihop_pair_index(L, l, l + 1)], one_hop[l])
+    for l in range(L):
+        for m in range(l + 1, L):
+            a, b = trace[l], trace[m]
+            ok = (a >= 0) & (a < E) & (b >= 0) & (b < E)
+            ref = np.zeros((E, E), dtype=np.int64)
+            np.add.at(ref, (a[ok], b[ok]), 1)
+            np.testing.assert_array_equal(multi[oracle.multihop_pair_index(L, l, m)], ref)
+    # deterministic chain: expert i of layer l leads to perm_{m-1}(...perm_l(i)) at layer m, always
+    tr1, p1 = syn.planted_trace(L, N, E, 1.0, seed=92)
+    m1 = oracle.affinity_counts_multihop(tr1, E)
+    first = np.bincount(tr1[0], minlength=E)
+    for m in range(1, L):
+        comp = np.arange(E)
+        for l in range(m):
+            comp = p1[l][comp]
+        c = m1[oracle.multihop_pair_index(L, 0, m)]
+        assert (c[np.arange(E), comp] == first).all() and c.sum() == N
+    # sums: with all ids valid, rows of (l, m) add up to the loads of layer l, columns to those of layer m
+    _, loads1, _ = oracle.affinity_counts(tr1, E)
+    for l in range(L):
+        for m in range(l + 1, L):
+            c = m1[oracle.multihop_pair_index(L, l, m)]
+            np.testing.assert_array_equal(c.sum(axis=1), loads1[l])
+            np.testing.assert_array_equal(c.sum(axis=0), loads1[m])
+    assert [oracle.multihop_pair_index(4, l, m) for l in range(4) for m in range(l + 1, 4)] == list(range(6))
