@@ -391,6 +391,14 @@ def main():
         result["routing_transfers"] = {"ms": ms_rt, "GBps": bytes_rt / (ms_rt * 1e-3) / 1e9,
                                        "frac": bytes_rt / (ms_rt * 1e-3) / 1e9 / PEAK_HBM_GBS, "bytes": bytes_rt,
                                        "alltoall_token_ratio": ratios}
+        # affinity across several layers: all 276 ordered layer pairs of the same trace
+        ws_mh = torch.empty(max(lib.affinity_multihop_workspace_bytes(c4.trace_L, c4.trace_N, c4.trace_E), 256), dtype=torch.uint8,
+                            device=dev)
+        ms_mh = _time_rotating(lambda i: (lambda: B.affinity_multihop(traces[i], c4.trace_E, want_prob=True, workspace=ws_mh)), tr_sets, 5)
+        n_pairs = c4.trace_L * (c4.trace_L - 1) // 2
+        result["affinity_multihop"] = {"ms": ms_mh, "layer_pairs": n_pairs, "pair_transitions_per_s": n_pairs * c4.trace_N / (ms_mh * 1e-3),
+                                       "trace_bytes": bytes_tr, "workspace_bytes": ws_mh.numel()}
+        del ws_mh
         result["placement_search"] = {
             "trace": "24 layers x 1048576 tokens, E=64, planted affinity rho=0.7", "gpus": c4.G, "nodes": 2,
             "host_solver_s": solver_s, "gpu_score_4096_maps_ms": ms, "maps_per_s": 4096 / (ms * 1e-3),

@@ -170,6 +170,20 @@ int affinity_histogram(const int32_t* trace, int L, int64_t N, int E, int64_t* c
                        void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * affinity_multihop — the co-routing counts of EVERY ordered layer pair l < m (appendix "Extend
+ * Expert Affinity to Cross Multiple Layers": a layer's expert affinity to all following layers).
+ *   counts     int64 [L(L-1)/2, E, E]  counts[p(l,m)][i][j] = #{ n : trace[l][n] == i and
+ *                                      trace[m][n] == j }, both ids valid; pairs numbered source
+ *                                      layer first: p(l,m) = l*L - l*(l+1)/2 + (m - l - 1)
+ *   cond_prob  fp32, same shape, optional (NULL): counts / row sum, 0 for an empty row
+ * Nothing is written when L == 1.  Shapes as affinity_histogram.
+ * workspace: affinity_multihop_workspace_bytes(L, N, E) bytes (per-chunk partial histograms).
+ * ------------------------------------------------------------------------------------- */
+size_t affinity_multihop_workspace_bytes(int L, int64_t N, int E);
+int affinity_multihop(const int32_t* trace, int L, int64_t N, int E, int64_t* counts, float* cond_prob,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * placement_locality — how many layer-to-layer transitions stay on the device that holds
  * the token, for a given expert-to-device placement (Design, "Solving Affinity's duality by
  * Integer Programming": the objective sums the crossing indicators R over tokens and the

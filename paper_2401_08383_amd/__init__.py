@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     LIB_PATH,
     SIGNATURES,
     affinity_histogram,
+    affinity_multihop,
     check_placement,
     last_error,
     lib,

@@ -45,6 +45,8 @@ SIGNATURES = {
     "affinity_histogram": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "placement_locality_workspace_bytes": (_sz, [_i, _i64]),
     "placement_locality": (_i, [_vp, _vp, _i, _i64, _i, _i, _vp, _vp, _sz, _vp]),
+    "affinity_multihop_workspace_bytes": (_sz, [_i, _i64, _i]),
+    "affinity_multihop": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _sz, _vp]),
     "routing_transfers_workspace_bytes": (_sz, [_i, _i64]),
     "routing_transfers": (_i, [_vp, _vp, _vp, _i, _i64, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "placement_locality_from_counts": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp]),
@@ -232,6 +234,20 @@ def placement_locality(trace, placement, G, workspace=None, out=None):
     _check(lib().placement_locality(_ptr(trace), _ptr(placement), L, N, E, G, _ptr(out), _ptr(workspace), workspace.numel(),
                                     _stream()))
     return out
+
+
+def affinity_multihop(trace, E, want_prob=True, workspace=None):
+    """-> dict(counts int64 [L(L-1)/2,E,E], cond_prob fp32 or None) on the device, pairs source layer first."""
+    L, N = trace.shape
+    assert trace.dtype == torch.int32 and trace.is_contiguous()
+    P = L * (L - 1) // 2
+    counts = torch.empty((P, E, E), dtype=torch.int64, device=trace.device)
+    prob = torch.empty((P, E, E), dtype=torch.float32, device=trace.device) if want_prob else None
+    nbytes = lib().affinity_multihop_workspace_bytes(L, N, E)
+    if workspace is None:
+        workspace = _workspace(nbytes, trace.device)
+    _check(lib().affinity_multihop(_ptr(trace), L, N, E, _ptr(counts), _ptr(prob), _ptr(workspace), workspace.numel(), _stream()))
+    return {"counts": counts, "cond_prob": prob}
 
 
 def routing_transfers(trace, placement, home, G, workspace=None):

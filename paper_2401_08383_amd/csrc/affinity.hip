@@ -256,6 +256,101 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
     if (threadIdx.x == 0) part_invalid[static_cast<size_t>(c) * Q + q] = *invalid_cnt;
 }
 
+// Counts for EVERY ordered layer pair l < m (the appendix statistic), pairs numbered source layer
+// first.  A workgroup owns a chunk of tokens and a group (l; m0 .. m0+g-1): it loads column l and
+// the g target columns and bins (col l, col m) - the same four-columns-for-three-pairs economy as
+// the one-hop kernel.  Groups are numbered q = 0 .. Q-1 in pair order; transitions with an invalid
+// end are skipped; the packed per-chunk partials go to part_counts[chunk][pair][words].
+template <int VEC>
+__global__ __launch_bounds__(kTraceThreads) void multihop_partial_kernel(const int32_t* __restrict__ trace, int L, int64_t N, int E,
+                                                                          int g, int Q, int copies, int words, int64_t chunk, int C,
+                                                                          uint32_t* __restrict__ part_counts)
+{
+    extern __shared__ uint32_t lds[];
+    uint32_t* hist = lds;  // [copies][g][words], two 16-bit counters per word
+    const int xcd = blockIdx.x % kXcds;
+    const int j = blockIdx.x / kXcds;
+    const int c = (j / Q) * kXcds + xcd;
+    const int q = j % Q;
+    if (c >= C) return;
+    for (int i = threadIdx.x; i < copies * g * words; i += kTraceThreads) lds[i] = 0u;
+    __syncthreads();
+
+    // group q -> source layer l, first target m0, number of pairs
+    int l = 0, before = 0, pair_base = 0;
+    for (;; ++l) {
+        const int targets = L - 1 - l;
+        const int groups = (targets + g - 1) / g;
+        if (q < before + groups) break;
+        before += groups;
+        pair_base += targets;
+    }
+    const int m0 = l + 1 + (q - before) * g;
+    const int my_pairs = min(g, L - m0);
+    pair_base += m0 - (l + 1);
+    const int total_pairs = L * (L - 1) / 2;
+
+    const int64_t n_begin = static_cast<int64_t>(c) * chunk;
+    const int64_t n_end = min(N, n_begin + chunk);
+    uint32_t* my_hist = hist + (threadIdx.x & (copies - 1)) * g * words;
+    const int64_t sweep = static_cast<int64_t>(kTraceThreads) * VEC;
+    auto load_cols = [&](int64_t n0, TokVec<VEC>(&col)[kAffMaxGroup + 1]) {  // clamped, never skipped
+        col[0] = load_tokens<VEC>(trace + static_cast<int64_t>(l) * N, n0, n_end);
+#pragma unroll
+        for (int s = 1; s <= kAffMaxGroup; ++s)
+            col[s] = load_tokens<VEC>(trace + static_cast<int64_t>(min(m0 + s - 1, L - 1)) * N, n0, n_end);
+    };
+    TokVec<VEC> col[kAffMaxGroup + 1], nxt[kAffMaxGroup + 1];
+    load_cols(n_begin + static_cast<int64_t>(threadIdx.x) * VEC, col);
+    for (int64_t base = n_begin; base < n_end; base += sweep) {
+        const int64_t n0 = base + static_cast<int64_t>(threadIdx.x) * VEC;
+        load_cols(n0 + sweep, nxt);
+        bool clean = n0 + VEC <= n_end;
+#pragma unroll
+        for (int s = 0; s <= kAffMaxGroup; ++s) {
+            unsigned m = 0;
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) m = max(m, static_cast<unsigned>(col[s].v[u]));
+            clean = clean && m < static_cast<unsigned>(E);  // (clamped duplicate columns repeat a checked one)
+        }
+        if (__ballot(!clean) == 0ull) {
+#pragma unroll
+            for (int s = 1; s <= kAffMaxGroup; ++s) {
+                if (s > my_pairs) break;
+                uint32_t* h = my_hist + (s - 1) * words;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) {
+                    const int bin = col[0].v[u] * E + col[s].v[u];
+                    atomicAdd(&h[bin >> 1], 1u << ((bin & 1) * 16));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 1; s <= kAffMaxGroup; ++s) {
+                if (s > my_pairs) break;
+                uint32_t* h = my_hist + (s - 1) * words;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) {
+                    const int a = col[0].v[u], b = col[s].v[u];
+                    if (n0 + u < n_end && static_cast<unsigned>(a) < static_cast<unsigned>(E) &&
+                        static_cast<unsigned>(b) < static_cast<unsigned>(E)) {
+                        const int bin = a * E + b;
+                        atomicAdd(&h[bin >> 1], (bin & 1) ? 0x10000u : 1u);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s <= kAffMaxGroup; ++s) col[s] = nxt[s];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < my_pairs * words; i += kTraceThreads) {
+        uint32_t sum = 0;
+        for (int r = 0; r < copies; ++r) sum += hist[r * g * words + i];
+        part_counts[(static_cast<size_t>(c) * total_pairs + pair_base) * words + i] = sum;
+    }
+}
+
 // Workgroups of 256 threads.  The first (L-1)*E take one (pair l, source expert i) row each:
 // wavefront w sums the chunks c = w, w+4, ... of bin (i, p = lane), the four partial sums meet in
 // LDS -> counts, row sum, load of (l, i), conditional probabilities.  The next E workgroups take one
@@ -295,7 +390,8 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
             }
         }
         long long orphan = 0;
-        for (int c = threadIdx.x; c < C; c += 256) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
+        if (loads != nullptr)  // (the multi-hop statistic has no orphan tallies)
+            for (int c = threadIdx.x; c < C; c += 256) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
         orphan = wave_sum(orphan);
         red[w][p] = cnt;
         if (p == 0) orphan_red[w] = orphan;
@@ -547,6 +643,87 @@ extern "C" int affinity_histogram(const int32_t* trace, int L, int64_t N, int E,
     hipLaunchKernelGGL(affinity_finalize_kernel, dim3(fin_grid), dim3(256), 0, s, part_counts, part_orphan_next, part_orphan_last,
                        part_invalid, p.C, p.Q, L, E, p.words, counts, loads, cond_prob, n_invalid);
     return check_launch("affinity_histogram");
+}
+
+namespace exf {
+struct MultihopPlan {
+    int g, Q, copies, words, C, vec, pairs;
+    int64_t chunk;
+    size_t total_bytes;
+};
+static MultihopPlan make_multihop_plan(int L, int64_t N, int E, bool aligned)
+{
+    MultihopPlan p;
+    p.pairs = L * (L - 1) / 2;
+    p.words = (E * E + 1) / 2;
+    const size_t hist_bytes = static_cast<size_t>(p.words) * sizeof(uint32_t);
+    int g = static_cast<int>(kAffHistBudget / hist_bytes);
+    if (g > kAffMaxGroup) g = kAffMaxGroup;
+    if (g < 1) g = 1;
+    p.g = g;
+    p.copies = 1;
+    while (p.copies < 16 && hist_bytes * g * (p.copies * 2) <= kAffHistBudget) p.copies *= 2;
+    p.Q = 0;
+    for (int l = 0; l + 1 < L; ++l) p.Q += (L - 1 - l + g - 1) / g;
+    if (p.Q < 1) p.Q = 1;
+    p.vec = (aligned && N % 4 == 0) ? 4 : 1;
+    const int64_t sweep = static_cast<int64_t>(kTraceThreads) * p.vec;
+    int c_target = kTargetWorkgroups / p.Q;
+    if (c_target < 1) c_target = 1;
+    int64_t chunk = (N + c_target - 1) / c_target;
+    chunk = (chunk + sweep - 1) / sweep * sweep;
+    if (chunk < sweep) chunk = sweep;
+    if (chunk > kAffMaxChunk) chunk = kAffMaxChunk / sweep * sweep;
+    p.chunk = chunk;
+    p.C = static_cast<int>(N > 0 ? (N + chunk - 1) / chunk : 0);
+    p.total_bytes = align_up(static_cast<size_t>(p.C > 0 ? p.C : 1) * (p.pairs > 0 ? p.pairs : 1) * p.words * sizeof(uint32_t), 256);
+    return p;
+}
+}  // namespace exf
+
+extern "C" size_t affinity_multihop_workspace_bytes(int L, int64_t N, int E)
+{
+    if (L < 1 || N < 0 || E < 1 || E > EXF_MAX_EXPERTS) return 0;
+    const size_t a = exf::make_multihop_plan(L, N, E, true).total_bytes;
+    const size_t b = exf::make_multihop_plan(L, N, E, false).total_bytes;
+    return a > b ? a : b;
+}
+
+extern "C" int affinity_multihop(const int32_t* trace, int L, int64_t N, int E, int64_t* counts, float* cond_prob, void* workspace,
+                                 size_t workspace_bytes, void* stream)
+{
+    using namespace exf;
+    if (int rc = validate_trace_args("affinity_multihop", L, N, E)) return rc;
+    if (L == 1) return EXF_OK;  // no pair, no output element
+    if (N > 0) EXF_REQUIRE_PTR(trace);
+    EXF_REQUIRE_PTR(counts);
+    EXF_REQUIRE_PTR(workspace);
+    const MultihopPlan p = make_multihop_plan(L, N, E, aligned16(trace));
+    if (workspace_bytes < p.total_bytes)
+        return fail(EXF_ERR_WORKSPACE_TOO_SMALL, "affinity_multihop: workspace %zu < %zu bytes", workspace_bytes, p.total_bytes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t* part_counts = static_cast<uint32_t*>(workspace);
+    if (p.C > 0) {
+        const int c_pad = (p.C + kXcds - 1) / kXcds * kXcds;
+        const int64_t grid = static_cast<int64_t>(c_pad) * p.Q;
+        if (grid >= (1ll << 31)) return fail(EXF_ERR_BAD_SHAPE, "affinity_multihop: too many workgroups");
+        const size_t lds = static_cast<size_t>(p.copies) * p.g * p.words * sizeof(uint32_t);
+        if (p.vec == 4) {
+            if (int rc = allow_large_lds(multihop_partial_kernel<4>, lds, "affinity_multihop")) return rc;
+            hipLaunchKernelGGL(multihop_partial_kernel<4>, dim3(static_cast<unsigned>(grid)), dim3(kTraceThreads), lds, s, trace, L, N, E,
+                               p.g, p.Q, p.copies, p.words, p.chunk, p.C, part_counts);
+        } else {
+            if (int rc = allow_large_lds(multihop_partial_kernel<1>, lds, "affinity_multihop")) return rc;
+            hipLaunchKernelGGL(multihop_partial_kernel<1>, dim3(static_cast<unsigned>(grid)), dim3(kTraceThreads), lds, s, trace, L, N, E,
+                               p.g, p.Q, p.copies, p.words, p.chunk, p.C, part_counts);
+        }
+    }
+    // one workgroup per (pair, source expert) row: sums the chunks, forms the conditional probabilities
+    // (the finalize kernel of the one-hop statistic, told that there are pairs+1 "layers" and no loads)
+    const unsigned fin_grid = static_cast<unsigned>(p.pairs * E);
+    hipLaunchKernelGGL(affinity_finalize_kernel, dim3(fin_grid), dim3(256), 0, s, part_counts, nullptr, nullptr, nullptr, p.C, 1,
+                       p.pairs + 1, E, p.words, counts, nullptr, cond_prob, nullptr);
+    return check_launch("affinity_multihop");
 }
 
 extern "C" size_t placement_locality_workspace_bytes(int L, int64_t N)

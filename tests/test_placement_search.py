@@ -188,3 +188,26 @@ def test_send_buffer_is_a_dispatch_by_destination():
     dest_sorted = row[idx[res.src_of_sorted.cpu().numpy(), 0]]
     assert (np.diff(dest_sorted) >= 0).all()                                     # grouped by destination
     np.testing.assert_array_equal(res.x_sorted.float().cpu().numpy(), x[ref["src_of_sorted"]])
+
+
+# ----------------------------------------------------------------------------- multi-hop affinity
+@pytest.mark.gpu
+@pytest.mark.parametrize("L,N,E", [(2, 512, 8), (5, 8192, 8), (12, 16384, 32), (7, 100001, 64), (24, 70000, 64), (4, 70003, 16), (1, 100, 8)])
+def test_affinity_multihop_parity(L, N, E):
+    print(f"[case] affinity_multihop L={L} N={N} E={E}", flush=True)
+    trace, _ = syn.planted_trace(L, N, E, 0.7, seed=850 + L + E)
+    if N > 1000 and L > 2:
+        trace[1, 7:700:9] = E
+        trace[L - 1, 2:300:5] = -3
+    res = exf.affinity_multihop(torch.from_numpy(trace).to("cuda:0"), E)
+    ref = oracle.affinity_counts_multihop(trace, E)
+    got = res["counts"].cpu().numpy()
+    np.testing.assert_array_equal(got, ref)
+    if L > 1:
+        rows = ref.sum(axis=2, keepdims=True).astype(np.float64)
+        prob = np.divide(ref, rows, out=np.zeros(ref.shape, dtype=np.float64), where=rows > 0).astype(np.float32)
+        np.testing.assert_allclose(res["cond_prob"].cpu().numpy(), prob, rtol=1e-6, atol=0)
+        # adjacent pairs are the one-hop statistic of the other entry point
+        one = exf.affinity_histogram(torch.from_numpy(trace).to("cuda:0"), E)["counts"].cpu().numpy()
+        for l in range(L - 1):
+            np.testing.assert_array_equal(got[oracle.multihop_pair_index(L, l, l + 1)], one[l])
