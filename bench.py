@@ -135,6 +135,9 @@ def main():
                     help="workload configuration (default 2: the one the headline metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel and large-shape measurements")
+    ap.add_argument("--unfused", action="store_true",
+                    help="bf16 configurations: sorted copies of the activations and a separate combine pass "
+                         "(moe_expert_ffn + moe_combine) instead of moe_expert_ffn_fused")
     ap.add_argument("--no-overlap", action="store_true",
                     help="run the affinity statistic on the layer's stream instead of a second stream beside it")
     args = ap.parse_args()
@@ -156,6 +159,7 @@ def main():
 
     cfg = syn.CONFIGS[args.config]
     bf16 = cfg.dtype == "bf16"
+    fused = bf16 and not args.unfused  # the fused entry point is bf16 only
 
     def to_device(a):
         t = torch.from_numpy(a)
@@ -181,7 +185,7 @@ def main():
             idx4_h, map4_h = syn.local_routing(cfg, syn.seed_for(4, 4, 1))
             kwargs["topk_idx"] = torch.from_numpy(idx4_h).to(dev)
             kwargs["expert_map"] = torch.from_numpy(map4_h).to(dev)
-        layers.append(MoELayerRun(to_device(x_h), to_device(wg_h), w1_d, w2_d, cfg.k, cfg.renormalize, **kwargs))
+        layers.append(MoELayerRun(to_device(x_h), to_device(wg_h), w1_d, w2_d, cfg.k, cfg.renormalize, fused=fused, **kwargs))
     layer = layers[0]
     aff = None
     if cfg.trace_L > 0:
@@ -239,15 +243,16 @@ def main():
     ffn_flops = 4.0 * A * cfg.d * cfg.f
     elem = 2 if bf16 else 4
     achieved_tf = ffn_flops / (ffn_ms * 1e-3) / 1e12
+    ffn_entry = "moe_expert_ffn_fused" if fused else "moe_expert_ffn"
     if cfg.index == 5:
         # weight-bandwidth bound: every expert that owns a row streams W1 and W2 once
         ffn_bytes = 2.0 * cfg.E_local * cfg.d * cfg.f * elem + 2.0 * A * cfg.d * elem
         achieved = ffn_bytes / (ffn_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "grouped_gemm_bf16_kernel (moe_expert_ffn: both contractions)", "achieved": achieved,
+        roofline = {"bound": "hbm", "kernel": f"grouped_gemm_bf16_kernel ({ffn_entry}: both contractions)", "achieved": achieved,
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": None,
                     "ms_per_launch": ffn_ms, "bytes_per_launch": ffn_bytes}
     else:
-        roofline = {"bound": "mfma", "kernel": "grouped_gemm_bf16_kernel (moe_expert_ffn: both contractions)"
+        roofline = {"bound": "mfma", "kernel": f"grouped_gemm_bf16_kernel ({ffn_entry}: both contractions)"
                     if bf16 else "grouped_gemm_f32_kernel (moe_expert_ffn, fp32 vector ALU: latency-bound tiny case)",
                     "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS if bf16 else 157.3, "unit": "TFLOP/s",
                     "frac": achieved_tf / (PEAK_BF16_TFLOPS if bf16 else 157.3),
@@ -277,7 +282,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": workloads[cfg.index], "tokens": cfg.T, "d_model": cfg.d, "d_ff": cfg.f, "experts": cfg.E,
                    "local_experts": cfg.E_local, "top_k": cfg.k, "layers_per_step": cfg.layers, "trace_layers": cfg.trace_L,
-                   "trace_tokens": cfg.trace_N},
+                   "trace_tokens": cfg.trace_N, "ffn_entry": ffn_entry},
         "roofline": roofline,
     }
     achieved = achieved_tf

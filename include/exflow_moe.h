@@ -141,6 +141,30 @@ int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offsets, const vo
                    int dt, void* y_sorted, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * moe_expert_ffn_fused — expert FFN and gate-weighted combine on the tokens where they lie
+ * (the same mathematics as moe_expert_ffn followed by moe_combine; Background, "Expert Model").
+ * The first contraction reads row src_of_sorted[s] / k of x for sorted row s, so moe_dispatch
+ * can be called with x_sorted = NULL (index-only) and no sorted copy of the activations exists.
+ * With k = 1 the second contraction multiplies its fp32 result by the token's gate weight and
+ * writes it to the token's own row of `out` (one rounding to bf16); rows of tokens whose
+ * assignment was not kept (sorted_of_src[t] < 0) are set to zero.  With k > 1 the second
+ * contraction writes sorted rows into the workspace and the combine kernel follows.
+ *
+ *   out[t][:] = sum_{j<k, sorted_of_src[t*k+j] >= 0} topk_w[t][j] * FFN_{e(t,j)}( x[t][:] )
+ *
+ *   x [T,d] bf16;  src_of_sorted [T*k], sorted_of_src [T*k], expert_offsets [E_local+1] as
+ *   written by moe_dispatch;  topk_w [T,k] fp32;  weights and biases as for moe_expert_ffn;
+ *   out [T,d] bf16, must not overlap x.  bf16 only (dt = EXF_BF16), d and f multiples of 64.
+ * workspace: moe_expert_ffn_fused_workspace_bytes(T, k, d, f, E_local, dt) bytes.
+ * ------------------------------------------------------------------------------------- */
+size_t moe_expert_ffn_fused_workspace_bytes(int64_t T, int k, int d, int f, int E_local, int dt);
+int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src,
+                         const float* topk_w, const int32_t* expert_offsets, const void* w1,
+                         const void* b1, const void* w2, const void* b2, int64_t T, int k, int d, int f,
+                         int E_local, int act, int dt, void* out, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * moe_combine — gate-weighted combination of the expert outputs (Background, "Expert
  * Model": a soft gate combines the experts' outputs).
  *   out[t][:] = sum_{j<k} topk_w[t][j] * y_sorted[ sorted_of_src[t*k+j] ][:]   (j ascending,

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     moe_combine,
     moe_dispatch,
     moe_expert_ffn,
+    moe_expert_ffn_fused,
     moe_gate_topk,
     moe_topk_from_logits,
     placement_locality,

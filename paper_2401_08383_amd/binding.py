@@ -40,6 +40,8 @@ SIGNATURES = {
     "moe_dispatch": (_i, [_vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moe_expert_ffn_workspace_bytes": (_sz, [_i64, _i, _i, _i, _i]),
     "moe_expert_ffn": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]),
+    "moe_expert_ffn_fused_workspace_bytes": (_sz, [_i64, _i, _i, _i, _i, _i]),
+    "moe_expert_ffn_fused": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]),
     "moe_combine": (_i, [_vp, _vp, _vp, _i64, _i, _i, _i, _vp, _vp]),
     "affinity_histogram_workspace_bytes": (_sz, [_i, _i64, _i]),
     "affinity_histogram": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -186,6 +188,29 @@ def moe_expert_ffn(x_sorted, expert_offsets, w1, w2, b1=None, b2=None, act=EXF_A
         workspace = _workspace(nbytes, x_sorted.device)
     _check(lib().moe_expert_ffn(_ptr(x_sorted), _ptr(expert_offsets), _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), A, d, f,
                                 E_local, act, dt, _ptr(out), _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def moe_expert_ffn_fused(x, src_of_sorted, sorted_of_src, topk_w, expert_offsets, w1, w2, b1=None, b2=None,
+                         act=EXF_ACT_GELU_ERF, out=None, workspace=None):
+    """Expert FFN + combine straight from / to the unsorted token rows (bf16)."""
+    T, d = x.shape
+    k = topk_w.shape[1]
+    E_local, f, d2 = w1.shape
+    assert d2 == d and tuple(w2.shape) == (E_local, d, f) and expert_offsets.numel() == E_local + 1
+    assert x.is_contiguous() and w1.is_contiguous() and w2.is_contiguous() and topk_w.is_contiguous()
+    assert tuple(topk_w.shape) == (T, k) and topk_w.dtype == torch.float32
+    assert src_of_sorted.numel() == T * k and sorted_of_src.numel() == T * k
+    assert src_of_sorted.dtype == torch.int32 and sorted_of_src.dtype == torch.int32 and expert_offsets.dtype == torch.int32
+    dt = dtype_code(x)
+    if out is None:
+        out = torch.empty((T, d), dtype=x.dtype, device=x.device)
+    nbytes = lib().moe_expert_ffn_fused_workspace_bytes(T, k, d, f, E_local, dt)
+    if workspace is None:
+        workspace = _workspace(nbytes, x.device)
+    _check(lib().moe_expert_ffn_fused(_ptr(x), _ptr(src_of_sorted), _ptr(sorted_of_src), _ptr(topk_w), _ptr(expert_offsets),
+                                      _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), T, k, d, f, E_local, act, dt, _ptr(out),
+                                      _ptr(workspace), workspace.numel(), _stream()))
     return out
 
 

@@ -205,11 +205,25 @@ __device__ __forceinline__ void wait_vmcnt()
 #endif
 }
 
+// Optional row indirections of the bf16 grouped GEMM; all members null / zero = sorted rows on both sides.
+// They let the contraction read the tokens where they lie (no sorted copy of the activations) and
+// let the second contraction of a top-1 layer write the gate-weighted result straight to the
+// token's own row (no sorted copy of the outputs, no separate combine pass).
+struct RowMap {
+    const int32_t* a_row;     // operand row of sorted row s is a_row[s] / a_div        (null: row s)
+    int a_div;
+    const int32_t* out_row;   // output row of sorted row s is out_row[s]; every output row is the
+    const float* out_scale;   //   target of at most one s and is scaled by out_scale[out_row[s]] in
+                              //   fp32 before the single rounding to bf16              (null: row s, no scale)
+    const int32_t* unrouted;  // [n_unrouted]: output row t with unrouted[t] < 0 is set to zero
+    int n_unrouted;
+};
+
 // One output tile: rows [row_begin,row_end) (at most MT) x columns [n0, n0+NT) of expert weights wexp.
 template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int EPI, bool BIAS>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const bf16_t* __restrict__ wexp,
                                           const bf16_t* __restrict__ bias_e, int row_begin, int row_end, int n0, int K, int N,
-                                          bf16_t* __restrict__ out, unsigned char* smem)
+                                          bf16_t* __restrict__ out, unsigned char* smem, const RowMap& map)
 {
     constexpr int NWAVES = WM * WN;
     constexpr int RB = KT * 2;              // bytes per tile row
@@ -241,7 +255,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     for (int i = 0; i < LA; ++i) {
         const int row = (wave * LA + i) * RPI + lane / CPR;
         const int chunk = (lane % CPR) ^ chunk_swizzle<KT, SWZ>(row);
-        const int r = min(row_begin + row, row_end - 1);  // rows past the tile end re-read the last valid row
+        int r = min(row_begin + row, row_end - 1);  // rows past the tile end re-read the last valid row
+        if (map.a_row != nullptr) r = map.a_row[r] / map.a_div;
         off_a[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
     }
 #pragma unroll
@@ -437,8 +452,27 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
                 for (int r = 0; r < 4; ++r)
                     bias_v[a][g][r] = bf16_to_f32(bexp[min(n_wave + a * 32 + g * 8 + (lane >> 5) * 4 + r, N - 1)]);
     }
+    constexpr int NIT = BP * 32 / RPI_OUT;          // store instructions per pass
+    const bool scatter = EPI == kEpiNone && map.out_row != nullptr;
 #pragma unroll
     for (int pass = 0; pass < TM / BP; ++pass) {
+        const int m_pass = row_begin + wm * WTM + pass * BP * 32;
+        // scattered output: target rows of this lane's stores and gate weights of this lane's values
+        int dst[NIT];
+        float scale[BP];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) dst[it] = m_pass + it * RPI_OUT + lane / CW;
+#pragma unroll
+        for (int bl = 0; bl < BP; ++bl) scale[bl] = 1.0f;
+        if constexpr (EPI == kEpiNone) {
+            if (scatter) {
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) dst[it] = map.out_row[min(dst[it], row_end - 1)];
+#pragma unroll
+                for (int bl = 0; bl < BP; ++bl)
+                    scale[bl] = map.out_scale[map.out_row[min(m_pass + bl * 32 + (lane & 31), row_end - 1)]];
+            }
+        }
 #pragma unroll
         for (int bl = 0; bl < BP; ++bl) {
             const int b = pass * BP + bl;
@@ -454,6 +488,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
                         if constexpr (BIAS) z += bias_v[a][g][r];
                         if constexpr (EPI == kEpiGeluErf) z = gelu_erf_fast(z);
                         if constexpr (EPI == kEpiGeluTanh) z = gelu_tanh_fast(z);
+                        if constexpr (EPI == kEpiNone) z *= scale[bl];
                         v[r] = z;
                     }
                     uint2 packed;
@@ -464,16 +499,15 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
             }
         }
         // same wavefront reads back what it just wrote (LDS operations of a wavefront execute in order)
-        const int m_pass = row_begin + wm * WTM + pass * BP * 32;
 #pragma unroll
-        for (int it = 0; it < BP * 32 / RPI_OUT; ++it) {
+        for (int it = 0; it < NIT; ++it) {
             const int r = it * RPI_OUT + lane / CW;
             const int c = lane % CW;
             const uint4 val = *reinterpret_cast<const uint4*>(region + r * S + c * 16);
             const int m = m_pass + r;
             const int n = n_wave + c * 8;
             if (m < row_end && n < N)  // N % 8 == 0: a chunk is entirely inside or outside
-                *reinterpret_cast<uint4*>(out + static_cast<size_t>(m) * N + n) = val;
+                *reinterpret_cast<uint4*>(out + static_cast<size_t>(dst[it]) * N + n) = val;
         }
     }
 }
@@ -484,9 +518,28 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
                                                                          const bf16_t* __restrict__ weight,  // [E_local,N,K]
                                                                          const bf16_t* __restrict__ bias,    // [E_local,N] or null
                                                                          int max_rows, int K, int N, int E_local,
-                                                                         bf16_t* __restrict__ out)           // [A,N]
+                                                                         bf16_t* __restrict__ out,           // [A,N]
+                                                                         const RowMap map)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    if (map.unrouted != nullptr) {
+        // output rows no sorted row writes (dropped or remote assignments): one wavefront looks at 64
+        // rows at a time and clears those it finds, all lanes together
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+        const int lane = lane_id();
+        const int64_t stride = static_cast<int64_t>(gridDim.x) * (WM * WN) * kWave;
+        for (int64_t first = (static_cast<int64_t>(blockIdx.x) * (WM * WN) + wave) * kWave; first < map.n_unrouted; first += stride) {
+            const int64_t t = first + lane;
+            const int pos = t < map.n_unrouted ? map.unrouted[t] : 0;
+            unsigned long long todo = __ballot(pos < 0);
+            while (todo != 0) {
+                const int b = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                uint4* row = reinterpret_cast<uint4*>(out + static_cast<size_t>(first + b) * N);
+                for (int c = lane; c < N / 8; c += kWave) row[c] = make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+    }
     Tile2D tile;
     const int n_tiles = (N + NT - 1) / NT;
     if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, tile_index_of_workgroup(blockIdx.x), tile)) return;
@@ -494,7 +547,7 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
     const bf16_t* bias_e = BIAS ? bias + static_cast<size_t>(tile.expert) * N : nullptr;
     if (!tile.tail || MT <= kTailRows) {
         gemm_tile<MT, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end, tile.n_tile * NT, K,
-                                                              N, out, smem);
+                                                              N, out, smem, map);
     } else if constexpr (MT > kTailRows) {
         // remainder rows: the wavefronts side by side over the columns, kTailRows rows each (two rows
         // of wavefronts when a column strip would become narrower than one MFMA tile).  A
@@ -508,7 +561,7 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
         constexpr int STAGES_T = kFit >= EXF_TAIL_STAGES_MAX ? EXF_TAIL_STAGES_MAX : (kFit >= 2 ? kFit : 2);
         constexpr int WM_T = NT / (WM * WN) >= 32 ? 1 : 2;
         gemm_tile<kTailRows, NT, KT, STAGES_T, WM_T, WM * WN / WM_T, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end,
-                                                                           tile.n_tile * NT, K, N, out, smem);
+                                                                           tile.n_tile * NT, K, N, out, smem, map);
     }
 }
 
@@ -580,7 +633,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
 // ---------------------------------------------------------------------------- host launchers
 template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int OCC>
 static int launch_bf16(const void* act, const int32_t* offsets, const void* weight, const void* bias, int64_t A, int K, int N,
-                       int E_local, int epi, void* out, hipStream_t stream)
+                       int E_local, int epi, void* out, hipStream_t stream, const RowMap& map = RowMap{})
 {
     constexpr size_t lds = static_cast<size_t>(STAGES) * (MT + NT) * KT * 2;
     // worst case: A/MT unmasked row tiles plus, for every expert, its tail tiles or one masked tile
@@ -600,7 +653,8 @@ static int launch_bf16(const void* act, const int32_t* offsets, const void* weig
         }                                                                                                                       \
         hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(WM* WN * 64), lds, stream,                              \
                            static_cast<const bf16_t*>(act), offsets, static_cast<const bf16_t*>(weight),                        \
-                           static_cast<const bf16_t*>(bias), static_cast<int>(A), K, N, E_local, static_cast<bf16_t*>(out));    \
+                           static_cast<const bf16_t*>(bias), static_cast<int>(A), K, N, E_local, static_cast<bf16_t*>(out),     \
+                           map);                                                                                                \
     } while (0)
     if (bias == nullptr) {
         if (epi == kEpiNone) EXF_LAUNCH_BF16(kEpiNone, false);
@@ -704,4 +758,83 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
     }
     if (rc != EXF_OK) return rc;
     return check_launch("moe_expert_ffn");
+}
+
+extern "C" int moe_combine(const void* y_sorted, const int32_t* sorted_of_src, const float* topk_w, int64_t T, int d, int k,
+                           int dt, void* out, void* stream);
+
+extern "C" size_t moe_expert_ffn_fused_workspace_bytes(int64_t T, int k, int d, int f, int E_local, int dt)
+{
+    (void)E_local;
+    if (T < 0 || k < 1 || k > EXF_MAX_TOPK || d < 1 || f < 1 || dt != EXF_BF16) return 0;
+    const size_t A = static_cast<size_t>(T > 0 ? T : 1) * static_cast<size_t>(k);
+    size_t bytes = exf::align_up(A * static_cast<size_t>(f) * 2, 256);          // hidden activations [A,f]
+    if (k > 1) bytes += exf::align_up(A * static_cast<size_t>(d) * 2, 256);     // sorted expert outputs [A,d]
+    return bytes;
+}
+
+extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src, const float* topk_w,
+                                    const int32_t* expert_offsets, const void* w1, const void* b1, const void* w2, const void* b2,
+                                    int64_t T, int k, int d, int f, int E_local, int act, int dt, void* out, void* workspace,
+                                    size_t workspace_bytes, void* stream)
+{
+    using namespace exf;
+    if (dt != EXF_BF16) return fail(EXF_ERR_BAD_DTYPE, "moe_expert_ffn_fused: dt = %d (bf16 only)", dt);
+    if (act != EXF_ACT_GELU_ERF && act != EXF_ACT_GELU_TANH) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: act = %d", act);
+    if (k < 1 || k > EXF_MAX_TOPK) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: k = %d outside [1,%d]", k, EXF_MAX_TOPK);
+    if (T < 0 || T * k >= (1ll << 31))
+        return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: T = %lld, T*k outside [0,2^31)", static_cast<long long>(T));
+    if (E_local < 1 || E_local > EXF_MAX_EXPERTS)
+        return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: E_local = %d outside [1,%d]", E_local, EXF_MAX_EXPERTS);
+    if (d < 64 || d % 64 != 0 || f < 64 || f % 64 != 0)
+        return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: d = %d and f = %d must be positive multiples of 64", d, f);
+    const int64_t A = T * k;
+    {  // rows are addressed with 32-bit byte offsets
+        const unsigned long long widest = static_cast<unsigned long long>(d > f ? d : f);
+        if (static_cast<unsigned long long>(A) * widest * 2ull >= (1ull << 32) ||
+            static_cast<unsigned long long>(d) * static_cast<unsigned long long>(f) * 2ull >= (1ull << 32))
+            return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: T*k*max(d,f) and d*f must stay below 2^31 elements");
+    }
+    if (T == 0) return EXF_OK;
+    EXF_REQUIRE_PTR(x);
+    EXF_REQUIRE_PTR(src_of_sorted);
+    EXF_REQUIRE_PTR(sorted_of_src);
+    EXF_REQUIRE_PTR(topk_w);
+    EXF_REQUIRE_PTR(expert_offsets);
+    EXF_REQUIRE_PTR(w1);
+    EXF_REQUIRE_PTR(w2);
+    EXF_REQUIRE_PTR(out);
+    EXF_REQUIRE_PTR(workspace);
+    EXF_REQUIRE_ALIGNED(x);
+    EXF_REQUIRE_ALIGNED(w1);
+    EXF_REQUIRE_ALIGNED(w2);
+    EXF_REQUIRE_ALIGNED(out);
+    EXF_REQUIRE_ALIGNED(workspace);
+    if (x == out) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: out must not alias x");
+    const size_t need = moe_expert_ffn_fused_workspace_bytes(T, k, d, f, E_local, dt);
+    if (workspace_bytes < need) return fail(EXF_ERR_WORKSPACE_TOO_SMALL, "moe_expert_ffn_fused: workspace %zu < %zu bytes", workspace_bytes, need);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int epi = act == EXF_ACT_GELU_ERF ? kEpiGeluErf : kEpiGeluTanh;
+    unsigned char* hidden = static_cast<unsigned char*>(workspace);
+    RowMap gather{};
+    gather.a_row = src_of_sorted;
+    gather.a_div = k;
+    int rc = launch_bf16<EXF_GEMM1_CFG>(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather);
+    if (rc != EXF_OK) return rc;
+    if (k == 1) {
+        RowMap scatter{};
+        scatter.out_row = src_of_sorted;  // k = 1: the flat assignment index is the token
+        scatter.out_scale = topk_w;
+        scatter.unrouted = sorted_of_src;
+        scatter.n_unrouted = static_cast<int>(T);
+        rc = launch_bf16<EXF_GEMM2_CFG>(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, out, s, scatter);
+        if (rc != EXF_OK) return rc;
+        return check_launch("moe_expert_ffn_fused");
+    }
+    unsigned char* y_sorted = hidden + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
+    rc = launch_bf16<EXF_GEMM2_CFG>(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
+    if (rc != EXF_OK) return rc;
+    rc = check_launch("moe_expert_ffn_fused");
+    if (rc != EXF_OK) return rc;
+    return moe_combine(y_sorted, sorted_of_src, topk_w, T, d, k, dt, out, stream);
 }

@@ -2,8 +2,10 @@
 
 ``MoELayerRun`` holds every output and workspace of one MoE layer pass
 (gate -> dispatch -> expert FFN -> combine, all enqueued on the current stream with no host
-synchronisation in between); ``AffinityRun`` does the same for affinity_histogram and
-placement_locality over a device-resident trace.  Argument marshalling only.
+synchronisation in between; with ``fused=True`` the dispatch is index-only and
+moe_expert_ffn_fused reads and writes the unsorted token rows, so no combine call follows);
+``AffinityRun`` does the same for affinity_histogram and placement_locality over a
+device-resident trace.  Argument marshalling only.
 """
 from __future__ import annotations
 
@@ -14,8 +16,9 @@ from . import binding as B
 
 class MoELayerRun:
     def __init__(self, x, w_gate, w1, w2, k, renormalize=False, expert_map=None, E_local=None, topk_idx=None,
-                 act=B.EXF_ACT_GELU_ERF):
+                 act=B.EXF_ACT_GELU_ERF, fused=False):
         self.lib = B.lib()
+        self.fused = bool(fused)
         self.x, self.w_gate, self.w1, self.w2 = x, w_gate, w1, w2
         self.T, self.d = x.shape
         self.E = w_gate.shape[0]
@@ -30,17 +33,22 @@ class MoELayerRun:
         A = self.A = self.T * k
         self.topk_idx = torch.empty((self.T, k), dtype=torch.int32, device=dev)
         self.topk_w = torch.empty((self.T, k), dtype=torch.float32, device=dev)
-        self.x_sorted = torch.empty((A, self.d), dtype=x.dtype, device=dev)
+        self.x_sorted = None if self.fused else torch.empty((A, self.d), dtype=x.dtype, device=dev)
         self.src_of_sorted = torch.empty(A, dtype=torch.int32, device=dev)
         self.sorted_of_src = torch.empty(A, dtype=torch.int32, device=dev)
         self.expert_counts = torch.empty(self.E_local, dtype=torch.int32, device=dev)
         self.expert_offsets = torch.empty(self.E_local + 1, dtype=torch.int32, device=dev)
-        self.y_sorted = torch.empty((A, self.d), dtype=x.dtype, device=dev)
+        self.y_sorted = None if self.fused else torch.empty((A, self.d), dtype=x.dtype, device=dev)
         self.out = torch.empty((self.T, self.d), dtype=x.dtype, device=dev)
         self.ws_dispatch = torch.empty(max(self.lib.moe_dispatch_workspace_bytes(self.T, k, self.E_local), 256),
                                        dtype=torch.uint8, device=dev)
-        self.ws_ffn = torch.empty(max(self.lib.moe_expert_ffn_workspace_bytes(A, self.d, self.f, self.E_local, self.dt), 256),
-                                  dtype=torch.uint8, device=dev)
+        if self.fused:
+            ffn_bytes = self.lib.moe_expert_ffn_fused_workspace_bytes(self.T, k, self.d, self.f, self.E_local, self.dt)
+            if ffn_bytes == 0:
+                raise ValueError("moe_expert_ffn_fused does not take this shape / dtype")
+        else:
+            ffn_bytes = self.lib.moe_expert_ffn_workspace_bytes(A, self.d, self.f, self.E_local, self.dt)
+        self.ws_ffn = torch.empty(max(ffn_bytes, 256), dtype=torch.uint8, device=dev)
 
     # each method enqueues one entry point on the current stream
     def gate(self):
@@ -50,17 +58,26 @@ class MoELayerRun:
     def dispatch(self):
         idx = self.forced_idx if self.forced_idx is not None else self.topk_idx
         B._check(self.lib.moe_dispatch(self.x.data_ptr(), idx.data_ptr(), B._ptr(self.expert_map), self.T, self.d, self.k,
-                                       self.E, self.E_local, self.dt, self.x_sorted.data_ptr(), self.src_of_sorted.data_ptr(),
+                                       self.E, self.E_local, self.dt, B._ptr(self.x_sorted), self.src_of_sorted.data_ptr(),
                                        self.sorted_of_src.data_ptr(), self.expert_counts.data_ptr(),
                                        self.expert_offsets.data_ptr(), self.ws_dispatch.data_ptr(), self.ws_dispatch.numel(),
                                        B._stream()))
 
     def ffn(self):
+        if self.fused:
+            B._check(self.lib.moe_expert_ffn_fused(self.x.data_ptr(), self.src_of_sorted.data_ptr(),
+                                                   self.sorted_of_src.data_ptr(), self.topk_w.data_ptr(),
+                                                   self.expert_offsets.data_ptr(), self.w1.data_ptr(), None, self.w2.data_ptr(),
+                                                   None, self.T, self.k, self.d, self.f, self.E_local, self.act, self.dt,
+                                                   self.out.data_ptr(), self.ws_ffn.data_ptr(), self.ws_ffn.numel(), B._stream()))
+            return
         B._check(self.lib.moe_expert_ffn(self.x_sorted.data_ptr(), self.expert_offsets.data_ptr(), self.w1.data_ptr(), None,
                                          self.w2.data_ptr(), None, self.A, self.d, self.f, self.E_local, self.act, self.dt,
                                          self.y_sorted.data_ptr(), self.ws_ffn.data_ptr(), self.ws_ffn.numel(), B._stream()))
 
     def combine(self):
+        if self.fused:
+            return
         B._check(self.lib.moe_combine(self.y_sorted.data_ptr(), self.sorted_of_src.data_ptr(), self.topk_w.data_ptr(), self.T,
                                       self.d, self.k, self.dt, self.out.data_ptr(), B._stream()))
 

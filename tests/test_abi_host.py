@@ -35,6 +35,7 @@ def test_library_exports_every_declared_symbol():
 def test_host_validation_rejects_before_launch():
     lib = exf.lib()
     one = ctypes.c_void_p(4096)  # a non-null, 16-byte aligned dummy; never dereferenced on these paths
+    two = ctypes.c_void_p(8192)
     odd = ctypes.c_void_p(4100)
     cases = [
         (lambda: lib.moe_gate_topk(one, one, 4, 64, 8, 1, 0, 7, None, one, one, None), B.EXF_ERR_BAD_DTYPE),
@@ -62,6 +63,21 @@ def test_host_validation_rejects_before_launch():
          B.EXF_ERR_WORKSPACE_TOO_SMALL),
         (lambda: lib.moe_expert_ffn(one, None, one, None, one, None, 4, 64, 256, 8, 0, B.EXF_F32, one, one, 1 << 20, None),
          B.EXF_ERR_NULL_PTR),
+        # moe_expert_ffn_fused(x, src_of_sorted, sorted_of_src, topk_w, offsets, w1, b1, w2, b2, T, k, d, f, E_local, act, dt, out, ws, ws_bytes, stream)
+        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 1, 64, 256, 8, 0, B.EXF_F32, two, one, 1 << 20, None),
+         B.EXF_ERR_BAD_DTYPE),
+        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 3, 64, 256, 8, 0, B.EXF_BF16, two, one, 1 << 20, None),
+         B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 1, 96, 256, 8, 0, B.EXF_BF16, two, one, 1 << 20, None),
+         B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 1, 64, 256, 8, 0, B.EXF_BF16, one, one, 1 << 20, None),
+         B.EXF_ERR_BAD_SHAPE),  # out aliases x
+        (lambda: lib.moe_expert_ffn_fused(one, one, None, one, one, one, None, one, None, 4, 1, 64, 256, 8, 0, B.EXF_BF16, two, one, 1 << 20, None),
+         B.EXF_ERR_NULL_PTR),
+        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 1, 64, 256, 8, 0, B.EXF_BF16, two, one, 16, None),
+         B.EXF_ERR_WORKSPACE_TOO_SMALL),
+        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 2, 64, 256, 8, 0, B.EXF_BF16, two, one, 4 * 2 * 256 * 2, None),
+         B.EXF_ERR_WORKSPACE_TOO_SMALL),  # top-2 also needs room for the sorted expert outputs
         (lambda: lib.moe_combine(one, one, one, 4, 64, 3, B.EXF_BF16, one, None), B.EXF_ERR_BAD_SHAPE),
         (lambda: lib.moe_combine(one, one, one, 4, 63, 1, B.EXF_F32, one, None), B.EXF_ERR_BAD_SHAPE),
         (lambda: lib.moe_combine(one, one, None, 4, 64, 1, B.EXF_F32, one, None), B.EXF_ERR_NULL_PTR),
@@ -86,6 +102,8 @@ def test_empty_inputs_are_ok_without_a_gpu():
     assert lib.moe_topk_from_logits(None, 0, 8, 1, 0, None, None, None) == B.EXF_OK
     assert lib.moe_expert_ffn(None, None, None, None, None, None, 0, 64, 256, 8, 0, B.EXF_BF16, None, None, 0, None) == B.EXF_OK
     assert lib.moe_combine(None, None, None, 0, 64, 1, B.EXF_BF16, None, None) == B.EXF_OK
+    assert lib.moe_expert_ffn_fused(None, None, None, None, None, None, None, None, None, 0, 1, 64, 256, 8, 0, B.EXF_BF16, None, None,
+                                    0, None) == B.EXF_OK
     assert lib.placement_locality(None, None, 1, 100, 8, 2, None, one, 0, None) == B.EXF_OK  # L = 1: no pair
 
 
@@ -95,6 +113,9 @@ def test_workspace_sizes():
     assert lib.moe_dispatch_workspace_bytes(32768, 1, 8) % 256 == 0
     assert lib.moe_expert_ffn_workspace_bytes(8192, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2
     assert lib.moe_expert_ffn_workspace_bytes(512, 64, 256, 8, B.EXF_F32) == 512 * 256 * 4
+    assert lib.moe_expert_ffn_fused_workspace_bytes(8192, 1, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2
+    assert lib.moe_expert_ffn_fused_workspace_bytes(256, 2, 4096, 16384, 64, B.EXF_BF16) == 512 * (16384 + 4096) * 2
+    assert lib.moe_expert_ffn_fused_workspace_bytes(256, 1, 64, 256, 8, B.EXF_F32) == 0  # bf16 only
     ws = lib.affinity_histogram_workspace_bytes(24, 1 << 20, 64)
     assert 0 < ws < 64 << 20  # partial histograms stay far below the 100 MB trace
     assert lib.placement_locality_workspace_bytes(24, 1 << 20) > 0

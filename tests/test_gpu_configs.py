@@ -89,6 +89,40 @@ def _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=None, expert_map=
     return ref
 
 
+def _check_fused(oracle, cfg, plain, x, w1, w2, ref, rows_per_expert, seed, expert_map=None, forced_idx=None):
+    """The same layer through moe_expert_ffn_fused (index-only dispatch): sampled tokens against the
+    oracle's gather -> FFN -> combine, every token against the three-call path (which differs by one
+    extra rounding of the expert output when k = 1 and not at all when k > 1)."""
+    k = cfg.k
+    fused = MoELayerRun(plain.x, plain.w_gate, plain.w1, plain.w2, k, cfg.renormalize, expert_map=plain.expert_map,
+                        topk_idx=plain.forced_idx, fused=True)
+    fused.out.fill_(7.0)
+    fused.topk_idx.copy_(plain.topk_idx)  # the gate is not what differs: take its result as the plain run has it
+    fused.topk_w.copy_(plain.topk_w)
+    fused.dispatch()
+    fused.ffn()
+    fused.combine()
+    np.testing.assert_array_equal(fused.sorted_of_src.cpu().numpy(), ref["sorted_of_src"])
+    np.testing.assert_array_equal(fused.expert_offsets.cpu().numpy(), ref["offsets"])
+    out = to_host(fused.out)
+    out_plain = to_host(plain.out)
+    if k == 1:
+        assert (np.abs(out - out_plain) <= 2.0 ** -7 * np.abs(out_plain) + 1e-30).all(), "fused against the three-call path"
+    else:
+        np.testing.assert_array_equal(out, out_plain)
+    unrouted = (ref["sorted_of_src"].reshape(cfg.T, k) < 0).all(axis=1)
+    assert (out[unrouted] == 0).all()
+    if k != 1 or not isinstance(w1, np.ndarray):
+        return
+    rows = _sample_rows(ref["offsets"], rows_per_expert, seed)
+    toks = ref["src_of_sorted"][rows]
+    w = fused.topk_w.cpu().numpy()
+    xs = x[ref["src_of_sorted"]]
+    y_ref = oracle.expert_ffn_rows(xs, ref["offsets"], w1, None, w2, None, 0, rows)
+    out_ref = w[toks, 0][:, None].astype(np.float64) * y_ref
+    assert np.abs(out[toks] - out_ref).max() <= OUT_RTOL[cfg.dtype] * np.abs(out_ref).max(), "fused layer output rows"
+
+
 def _check_affinity(oracle, cfg, trace, placement):
     aff = AffinityRun(torch.from_numpy(trace).to(DEV), torch.from_numpy(placement).to(DEV), cfg.trace_E, cfg.G)
     aff.step()
@@ -113,6 +147,7 @@ def test_config2_gpt_moe_350m(oracle):
     layer.step()
     ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, rows_per_expert=6, seed=21)
     assert ref["counts"].min() > 800  # the synthetic gate is roughly balanced, as trained models are
+    _check_fused(oracle, cfg, layer, x, w1, w2, ref, rows_per_expert=6, seed=22)
     trace, perms = syn.config_trace(cfg)
     frac = _check_affinity(oracle, cfg, trace, syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(2, 5)))
     assert abs(frac - 1 / cfg.G) < 0.15  # few (88) hot transitions: a wide band around 1/G
@@ -146,6 +181,7 @@ def test_config3_xl_skewed(oracle):
     _say("  oracle on sampled rows")
     ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=forced, rows_per_expert=1, seed=31)
     assert ref["counts"].max() > 10 * max(1, ref["counts"].min())  # skewed loads
+    _check_fused(oracle, cfg, layer, x, w1, w2, ref, rows_per_expert=1, seed=32)
     _check_affinity(oracle, cfg, trace, syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(3, 5)))
 
 
@@ -169,6 +205,7 @@ def test_config4_one_gpu_share(oracle):
     layer.combine()
     ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=idx, expert_map=expert_map, rows_per_expert=3, seed=41)
     assert ref["kept"] == cfg.T
+    _check_fused(oracle, cfg, layer, x, w1, w2, ref, rows_per_expert=3, seed=43)
     # the same layer fed with the gate's own routing: 7 of 8 tokens belong to other GPUs and are dropped here
     layer2 = MoELayerRun(xd, wgd, layer.w1, layer.w2, 1, False, expert_map=layer.expert_map)
     layer2.step()
@@ -176,6 +213,7 @@ def test_config4_one_gpu_share(oracle):
     assert 0 < ref2["kept"] < cfg.T // 4
     dropped = ref2["sorted_of_src"] < 0
     assert (to_host(layer2.out)[dropped] == 0).all()
+    _check_fused(oracle, cfg, layer2, x, w1, w2, ref2, rows_per_expert=2, seed=44)
     _say("  affinity on the 24 x 1M trace")
     trace, _ = syn.config_trace(cfg)
     frac = _check_affinity(oracle, cfg, trace, syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(4, 5)))
@@ -207,6 +245,8 @@ def test_config5_decode_top2(oracle):
         offs = ref["offsets"]
         rows = np.array([int(offs[e]) for e in sorted(keep)] + [int(offs[e + 1]) - 1 for e in sorted(keep)], dtype=np.int64)
         _check_layer_rows(oracle, cfg, layer, x, wg, w1, w2, rows)
+        if l == 0:
+            _check_fused(oracle, cfg, layer, x, w1, w2, ref, rows_per_expert=0, seed=0)
 
 
 def _check_layer_rows(oracle, cfg, layer, x, wg, w1_dev, w2_dev, rows):

@@ -257,6 +257,82 @@ def test_layer_small_end_to_end(oracle, cfg_id, dtype, T, d, f, E, k, renorm):
     assert_close_max(to_host(out), out_ref, OUT_RTOL[dtype], "layer output")
 
 
+# ----------------------------------------------------------------------------- fused FFN + combine
+def _fused_case(oracle, T, d, f, E, E_local, k, act, bias, seed, skew=False):
+    """moe_dispatch (index-only) -> moe_expert_ffn_fused against oracle gather -> FFN -> combine."""
+    g = syn.rng(seed)
+    x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), "bf16")
+    w1 = syn.quantize(g.standard_normal((E_local, f, d), dtype=np.float32) * np.float32(0.05), "bf16")
+    w2 = syn.quantize(g.standard_normal((E_local, d, f), dtype=np.float32) * np.float32(0.05), "bf16")
+    b1 = syn.quantize(g.standard_normal((E_local, f), dtype=np.float32) * np.float32(0.1), "bf16") if bias else None
+    b2 = syn.quantize(g.standard_normal((E_local, d), dtype=np.float32) * np.float32(0.1), "bf16") if bias else None
+    if skew:  # a few heavy experts, several empty ones
+        p = 1.0 / np.arange(1, E + 1) ** 1.5
+        idx = np.stack([g.choice(E, size=k, replace=False, p=p / p.sum()) for _ in range(T)]).astype(np.int32)
+    else:
+        idx = np.stack([g.choice(E, size=k, replace=False) for _ in range(T)]).astype(np.int32)
+    gate = g.random((T, k), dtype=np.float32) + np.float32(0.05)
+    expert_map = None
+    if E_local < E:  # the first E_local of a shuffled list of experts live here; the others' tokens are dropped
+        expert_map = np.full(E, -1, dtype=np.int32)
+        expert_map[g.permutation(E)[:E_local]] = np.arange(E_local, dtype=np.int32)
+    xd = to_dev(x, "bf16")
+    disp = exf.moe_dispatch(xd, torch.from_numpy(idx).to(DEV), E, E_local=E_local,
+                            expert_map=None if expert_map is None else torch.from_numpy(expert_map).to(DEV), gather=False)
+    out = torch.full((T, d), 7.0, dtype=torch.bfloat16, device=DEV)
+    exf.moe_expert_ffn_fused(xd, disp.src_of_sorted, disp.sorted_of_src, torch.from_numpy(gate).to(DEV), disp.expert_offsets,
+                             to_dev(w1, "bf16"), to_dev(w2, "bf16"), None if b1 is None else to_dev(b1, "bf16"),
+                             None if b2 is None else to_dev(b2, "bf16"), act, out=out)
+    ref_d = oracle.dispatch(idx, expert_map, E, E_local)
+    expected_dispatch_compare(disp, ref_d, T * k)
+    xs_ref = oracle.gather_rows(x, ref_d["src_of_sorted"], k)
+    y_ref = oracle.expert_ffn(xs_ref, ref_d["offsets"], w1, b1, w2, b2, act)
+    out_ref = oracle.combine(y_ref, ref_d["sorted_of_src"], gate)
+    got = to_host(out)
+    unrouted = (ref_d["sorted_of_src"].reshape(T, k) < 0).all(axis=1)
+    assert (got[unrouted] == 0).all(), "rows of tokens without a kept assignment must be zero"
+    assert_close_max(got, out_ref, OUT_RTOL["bf16"], "fused layer output")
+    return int(unrouted.sum())
+
+
+@pytest.mark.parametrize("act", [0, 1])
+@pytest.mark.parametrize("bias", [False, True])
+def test_ffn_fused_top1_parity(oracle, act, bias):
+    _say(f"ffn fused top-1 act={act} bias={bias}")
+    assert _fused_case(oracle, 700, 128, 320, 6, 6, 1, act, bias, seed=700 + act) == 0
+    assert _fused_case(oracle, 1500, 64, 128, 16, 5, 1, act, bias, seed=702) > 0  # most tokens belong to other GPUs
+
+
+def test_ffn_fused_top1_skewed_and_tiny(oracle):
+    _say("ffn fused top-1 skewed / tiny")
+    _fused_case(oracle, 3000, 256, 512, 32, 32, 1, 0, False, seed=710, skew=True)
+    _fused_case(oracle, 1, 64, 64, 4, 4, 1, 0, False, seed=711)
+    _fused_case(oracle, 67, 64, 64, 8, 1, 1, 0, True, seed=712)  # one resident expert, seven of eight tokens unrouted
+
+
+@pytest.mark.parametrize("E_local", [8, 3])
+def test_ffn_fused_top2_parity(oracle, E_local):
+    _say(f"ffn fused top-2 E_local={E_local}")
+    _fused_case(oracle, 900, 128, 256, 8, E_local, 2, 0, True, seed=720 + E_local)
+
+
+def test_ffn_fused_no_kept_assignment_clears_output(oracle):
+    """Every token routed to an expert that lives elsewhere: the output is all zeros."""
+    T, d, f = 300, 64, 128
+    g = syn.rng(730)
+    x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), "bf16")
+    w1 = to_dev(np.zeros((2, f, d), dtype=np.float32), "bf16")
+    w2 = to_dev(np.zeros((2, d, f), dtype=np.float32), "bf16")
+    idx = np.full((T, 1), 3, dtype=np.int32)
+    expert_map = np.array([0, 1, -1, -1], dtype=np.int32)
+    disp = exf.moe_dispatch(to_dev(x, "bf16"), torch.from_numpy(idx).to(DEV), 4, E_local=2,
+                            expert_map=torch.from_numpy(expert_map).to(DEV), gather=False)
+    out = torch.full((T, d), 7.0, dtype=torch.bfloat16, device=DEV)
+    exf.moe_expert_ffn_fused(to_dev(x, "bf16"), disp.src_of_sorted, disp.sorted_of_src, torch.ones((T, 1), device=DEV),
+                             disp.expert_offsets, w1, w2, out=out)
+    assert (to_host(out) == 0).all()
+
+
 # ----------------------------------------------------------------------------- affinity / locality
 def _affinity_case(oracle, trace, E, placement=None, G=1):
     L, N = trace.shape
