@@ -22,6 +22,8 @@
 //     XCD and every XCD walks a contiguous range of tiles ordered (expert, column tile, row tile):
 //     the workgroups resident on one XCD share an expert's activation rows and a few weight
 //     panels in that XCD's L2.
+//   - remainder ("tail") tiles of the second contraction are cut into K slices when there are few of
+//     them, and a small kernel adds the slices (see TileSchedule).
 // fp32 kernel: LDS-tiled 64x64x16, 4x4 outputs per thread (tiny configuration; latency bound).
 #include <math.h>
 
@@ -70,9 +72,8 @@ enum Epilogue { kEpiNone = 0, kEpiGeluErf = 1, kEpiGeluTanh = 2 };
 // cut into "tail" row tiles of kTailRows rows, so that a small remainder costs in proportion to
 // its size instead of a whole tile; a larger remainder becomes one more full tile whose missing
 // rows are masked (a tail tile does a quarter of the MFMA work of a 256-row tile but loads the
-// same weight panel, so three or four of them cost more than the one masked tile).  Tile order:
-// all full tiles as (expert, column tile, row tile), then all tail tiles in the same way; the
-// cheap tail tiles therefore fill the last round of the launch.
+// same weight panel, so three or four of them cost more than the one masked tile).  Both kinds are
+// numbered (expert, column tile, row tile); locate_tile() says which kind a launch runs first.
 constexpr int kTailRows = 64;
 __host__ __device__ constexpr int max_tail_tiles(int mt) { return mt / 2 >= kTailRows ? (mt / 2 + kTailRows - 1) / kTailRows : 1; }
 #ifndef EXF_XCD_CHUNK
@@ -85,7 +86,31 @@ struct Tile2D {
     int row_begin, row_end;
     int n_tile;
     bool tail;
+    int kt_begin, kt_end;  // K tiles [kt_begin, kt_end) of the reduction this workgroup sums
+    int slot;              // >= 0: the sum goes to partial-sum slot `slot` (a K slice of a tail tile)
 };
+
+// Tail tiles hold a quarter of the rows of a full tile but walk the same reduction: one takes nearly
+// half as long as a full tile (28 against 62 us in the second contraction of 8192 tokens) while only
+// a few compute units have one.
+// When there are few of them, each is therefore cut into `split` K slices that run side by side as
+// workgroups of their own; a slice writes its fp32 partial sums to a slot of the workspace and a
+// small second kernel adds the slices and applies the epilogue.  split * (number of tail tiles)
+// never exceeds kSplitUnits, which bounds the slots.
+constexpr int kSplitUnits = 256;    // one slice per compute unit
+constexpr int kSplitMaxCols = 256;  // widest tile a partial-sum slot is sized for
+constexpr size_t kSplitBytes = static_cast<size_t>(kSplitUnits) * kTailRows * kSplitMaxCols * sizeof(float);
+#ifndef EXF_SPLIT_MIN_KTILES
+#define EXF_SPLIT_MIN_KTILES 4
+#endif
+constexpr int kSplitMinKTiles = EXF_SPLIT_MIN_KTILES;  // shortest K slice worth a workgroup
+constexpr int kSplitMax = 8;                            // most K slices per tail tile
+#ifndef EXF_TAILS_FIRST
+#define EXF_TAILS_FIRST 1
+#endif
+#ifndef EXF_SPLIT_GEMM1
+#define EXF_SPLIT_GEMM1 0  // K slices in the first contraction too: measured slower (its reduction is the short one)
+#endif
 
 // Workgroup id -> tile index.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
 // id % 8 is the XCD and id / 8 the position in that XCD's queue; chunks of kXcdChunk consecutive
@@ -97,39 +122,57 @@ __device__ __forceinline__ int tile_index_of_workgroup(int wg)
     return ((slot / kXcdChunk) * kXcdCount + xcd) * kXcdChunk + slot % kXcdChunk;
 }
 
-__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles, int max_rows,
-                                            int idx, Tile2D& out)
+// Per-expert tile counts (lane e = expert e) and their running sums; the same in every workgroup.
+struct TileSchedule {
+    int lo, hi;              // this lane's expert: clamped row range
+    int full_rt, tail_rt;    //   its full and tail row tiles
+    int full_incl, tail_incl;
+    int total_full, total_tail;
+    int split;               // K slices per tail tile
+};
+
+__device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles,
+                                                     int max_rows, int nk, bool may_split)
+{
+    TileSchedule sc;
+    const int lane = lane_id();
+    sc.lo = 0;
+    sc.hi = 0;
+    if (lane < E_local) {  // clamped so that a corrupt offsets array can never index past the buffers
+        sc.lo = min(max(offsets[lane], 0), max_rows);
+        sc.hi = min(max(offsets[lane + 1], sc.lo), max_rows);
+    }
+    const int cnt = sc.hi - sc.lo;
+    sc.full_rt = cnt / mt;
+    sc.tail_rt = (cnt - sc.full_rt * mt + kTailRows - 1) / kTailRows;
+    if (sc.tail_rt > max_tail_tiles(mt)) {
+        sc.full_rt += 1;
+        sc.tail_rt = 0;
+    }
+    sc.full_incl = wave_inclusive_scan(sc.full_rt * n_tiles);
+    sc.tail_incl = wave_inclusive_scan(sc.tail_rt * n_tiles);
+    sc.total_full = __shfl(sc.full_incl, kWave - 1, kWave);
+    sc.total_tail = __shfl(sc.tail_incl, kWave - 1, kWave);
+    int split = 1;
+    if (may_split && sc.total_tail > 0) split = max(1, min(min(kSplitUnits / sc.total_tail, nk / kSplitMinKTiles), kSplitMax));
+    sc.split = __builtin_amdgcn_readfirstlane(split);
+    return sc;
+}
+
+// Tile j of the full (tail = false) or tail tiles -> expert, rows, column tile.
+__device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local, int mt, int n_tiles, bool tail, int j, Tile2D& out)
 {
     const int lane = lane_id();
-    int lo = 0, hi = 0;
-    if (lane < E_local) {  // clamped so that a corrupt offsets array can never index past the buffers
-        lo = min(max(offsets[lane], 0), max_rows);
-        hi = min(max(offsets[lane + 1], lo), max_rows);
-    }
-    const int cnt = hi - lo;
-    int full_rt = cnt / mt;
-    int tail_rt = (cnt - full_rt * mt + kTailRows - 1) / kTailRows;
-    if (tail_rt > max_tail_tiles(mt)) {
-        full_rt += 1;
-        tail_rt = 0;
-    }
-    const int full_incl = wave_inclusive_scan(full_rt * n_tiles);
-    const int tail_incl = wave_inclusive_scan(tail_rt * n_tiles);
-    const int total_full = __shfl(full_incl, kWave - 1, kWave);
-    const int total = total_full + __shfl(tail_incl, kWave - 1, kWave);
-    if (idx >= total) return false;
-    const bool tail = idx >= total_full;
-    const int j = tail ? idx - total_full : idx;
-    const int incl = tail ? tail_incl : full_incl;
-    const int rt = tail ? tail_rt : full_rt;
+    const int incl = tail ? sc.tail_incl : sc.full_incl;
+    const int rt = tail ? sc.tail_rt : sc.full_rt;
     const int excl = incl - rt * n_tiles;
     const unsigned long long m = __ballot(lane < E_local && j >= excl && j < incl);
     if (m == 0ull) return false;
     const int src = __ffsll(static_cast<long long>(m)) - 1;
-    const int e_lo = __shfl(lo, src, kWave);
-    const int e_hi = __shfl(hi, src, kWave);
+    const int e_lo = __shfl(sc.lo, src, kWave);
+    const int e_hi = __shfl(sc.hi, src, kWave);
     const int e_rt = __shfl(rt, src, kWave);
-    const int e_full = __shfl(full_rt, src, kWave);
+    const int e_full = __shfl(sc.full_rt, src, kWave);
     const int r = j - __shfl(excl, src, kWave);
     // Order of the expert's tiles.  With many row tiles, consecutive tiles form blocks of kBlockRows
     // row tiles x kBlockCols column tiles (one XCD chunk): the 32 workgroups of a block share 4
@@ -159,6 +202,33 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
     out.row_begin = __builtin_amdgcn_readfirstlane(begin);
     out.row_end = __builtin_amdgcn_readfirstlane(min(begin + (tail ? kTailRows : mt), e_hi));
     out.tail = tail;
+    return true;
+}
+
+// Work item idx of a launch.  Few tail items (at most one per compute unit, K slices counted): they
+// go first, slice fastest, so that the launch ends with whole rounds of full tiles - behind the full
+// tiles the few compute units that get a tail tile at the very end would decide when the launch is
+// over.  Many tail items: they go last and fill the ragged end of the last round of full tiles.
+__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles, int max_rows,
+                                            int nk, bool may_split, int idx, Tile2D& out)
+{
+    const TileSchedule sc = scan_experts(offsets, E_local, mt, n_tiles, max_rows, nk, may_split);
+    const int tail_units = sc.total_tail * sc.split;
+    if (idx >= sc.total_full + tail_units) return false;
+    const bool tails_first = EXF_TAILS_FIRST && tail_units <= kSplitUnits;
+    const bool tail = tails_first ? idx < tail_units : idx >= sc.total_full;
+    const int u = tails_first ? idx : idx - sc.total_full;
+    const int full_idx = tails_first ? idx - tail_units : idx;
+    if (!decode_tile(sc, E_local, mt, n_tiles, tail, tail ? u / sc.split : full_idx, out)) return false;
+    out.kt_begin = 0;
+    out.kt_end = nk;
+    out.slot = -1;
+    if (tail && sc.split > 1) {
+        const int slice = u % sc.split;
+        out.kt_begin = __builtin_amdgcn_readfirstlane(slice * nk / sc.split);
+        out.kt_end = __builtin_amdgcn_readfirstlane((slice + 1) * nk / sc.split);
+        out.slot = __builtin_amdgcn_readfirstlane(u);
+    }
     return true;
 }
 
@@ -219,11 +289,20 @@ struct RowMap {
     int n_unrouted;
 };
 
-// One output tile: rows [row_begin,row_end) (at most MT) x columns [n0, n0+NT) of expert weights wexp.
-template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int EPI, bool BIAS>
+// One output tile: rows [row_begin,row_end) (at most MT) x columns [n0, n0+NT) of expert weights wexp,
+// summed over K tiles [kt_begin, kt_end).  With `partial` set (SPLIT instantiations only) the fp32
+// sums are written there, in the order partial_index() gives, and no epilogue runs.
+template <int TN, int TM>
+__device__ __forceinline__ int partial_index(int wave, int a, int b, int g, int lane)
+{
+    return ((((wave * TN + a) * TM + b) * 4 + g) * kWave) + lane;  // in units of float4: a store covers 1 KiB
+}
+
+template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int EPI, bool BIAS, bool SPLIT>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const bf16_t* __restrict__ wexp,
                                           const bf16_t* __restrict__ bias_e, int row_begin, int row_end, int n0, int K, int N,
-                                          bf16_t* __restrict__ out, unsigned char* smem, const RowMap& map)
+                                          bf16_t* __restrict__ out, unsigned char* smem, const RowMap& map, int kt_begin,
+                                          int kt_end, float4* __restrict__ partial)
 {
     constexpr int NWAVES = WM * WN;
     constexpr int RB = KT * 2;              // bytes per tile row
@@ -266,8 +345,9 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         const int r = min(n0 + row, N - 1);
         off_w[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
     }
-    const unsigned char* act_b = uniform_ptr(reinterpret_cast<const unsigned char*>(act));
-    const unsigned char* wgt_b = uniform_ptr(reinterpret_cast<const unsigned char*>(wexp));
+    const size_t k_skip = static_cast<size_t>(kt_begin) * (KT * 2);  // bytes of a row in front of this K range
+    const unsigned char* act_b = uniform_ptr(reinterpret_cast<const unsigned char*>(act) + k_skip);
+    const unsigned char* wgt_b = uniform_ptr(reinterpret_cast<const unsigned char*>(wexp) + k_skip);
 
     // ---- per-lane LDS byte offsets of the MFMA operand reads -------------------------------
     // operand row = base + lane%32; K step ks uses logical chunk 2*ks + lane/32
@@ -289,7 +369,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    const int nk = K / KT;
+    const int nk = kt_end - kt_begin;
     const uint32_t smem_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) unsigned char*)smem));  // LDS byte address of the ring
     auto issue = [&](int kt) {
@@ -424,6 +504,19 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
             }
         }
     }
+    if constexpr (SPLIT) {
+        if (partial != nullptr) {  // a K slice: hand the raw sums to the kernel that adds the slices
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        partial[partial_index<TN, TM>(wave, a, b, g, lane)] =
+                            make_float4(acc[a][b][g * 4 + 0], acc[a][b][g * 4 + 1], acc[a][b][g * 4 + 2], acc[a][b][g * 4 + 3]);
+            return;
+        }
+    }
     // ---- epilogue -----------------------------------------------------------------------------
     // A lane holds, for output row m = .. + lane%32, the columns n = .. + 8*g + 4*(lane/32) + r.
     // Writing that straight to memory would touch 32 rows per store instruction, so every
@@ -519,7 +612,8 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
                                                                          const bf16_t* __restrict__ bias,    // [E_local,N] or null
                                                                          int max_rows, int K, int N, int E_local,
                                                                          bf16_t* __restrict__ out,           // [A,N]
-                                                                         const RowMap map)
+                                                                         const RowMap map,
+                                                                         float4* __restrict__ partial)       // K-slice sums or null
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     if (map.unrouted != nullptr) {
@@ -542,12 +636,14 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
     }
     Tile2D tile;
     const int n_tiles = (N + NT - 1) / NT;
-    if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, tile_index_of_workgroup(blockIdx.x), tile)) return;
+    if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, K / KT, partial != nullptr && MT > kTailRows,
+                     tile_index_of_workgroup(blockIdx.x), tile))
+        return;
     const bf16_t* wexp = weight + static_cast<size_t>(tile.expert) * N * K;
     const bf16_t* bias_e = BIAS ? bias + static_cast<size_t>(tile.expert) * N : nullptr;
     if (!tile.tail || MT <= kTailRows) {
-        gemm_tile<MT, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end, tile.n_tile * NT, K,
-                                                              N, out, smem, map);
+        gemm_tile<MT, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS, false>(act, wexp, bias_e, tile.row_begin, tile.row_end,
+                                                                     tile.n_tile * NT, K, N, out, smem, map, 0, K / KT, nullptr);
     } else if constexpr (MT > kTailRows) {
         // remainder rows: the wavefronts side by side over the columns, kTailRows rows each (two rows
         // of wavefronts when a column strip would become narrower than one MFMA tile).  A
@@ -560,9 +656,74 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
 #endif
         constexpr int STAGES_T = kFit >= EXF_TAIL_STAGES_MAX ? EXF_TAIL_STAGES_MAX : (kFit >= 2 ? kFit : 2);
         constexpr int WM_T = NT / (WM * WN) >= 32 ? 1 : 2;
-        gemm_tile<kTailRows, NT, KT, STAGES_T, WM_T, WM * WN / WM_T, SWZ, EPI, BIAS>(act, wexp, bias_e, tile.row_begin, tile.row_end,
-                                                                           tile.n_tile * NT, K, N, out, smem, map);
+        float4* slot = tile.slot >= 0 ? partial + static_cast<size_t>(tile.slot) * (kTailRows * NT / 4) : nullptr;
+        gemm_tile<kTailRows, NT, KT, STAGES_T, WM_T, WM * WN / WM_T, SWZ, EPI, BIAS, true>(
+            act, wexp, bias_e, tile.row_begin, tile.row_end, tile.n_tile * NT, K, N, out, smem, map, tile.kt_begin, tile.kt_end, slot);
     }
+}
+
+// Adds the K slices of every tail tile and applies the epilogue the slices skipped.  A workgroup owns
+// one group of four columns per lane (a, b, g of the accumulator layout) of one tail tile; its threads
+// take the elements the same (wavefront, lane) held in the GEMM, so the slices are read back as they
+// were written (1 KiB per wavefront and load), all slices requested at once, and summed in slice
+// order.  Does nothing when the launch before it did not split (the same schedule is derived from
+// expert_offsets).
+template <int MT, int NT, int KT, int WM, int WN, int EPI, bool BIAS>
+__global__ __launch_bounds__(WM* WN * 64) void tail_reduce_bf16_kernel(const int32_t* __restrict__ offsets,
+                                                                        const bf16_t* __restrict__ bias,  // [E_local,N] or null
+                                                                        int max_rows, int K, int N, int E_local,
+                                                                        const float4* __restrict__ partial,
+                                                                        bf16_t* __restrict__ out, const RowMap map)
+{
+    constexpr int WM_T = NT / (WM * WN) >= 32 ? 1 : 2, WN_T = WM * WN / WM_T;
+    constexpr int WTM = kTailRows / WM_T, WTN = NT / WN_T;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int GROUPS = TN * TM * 4;
+    constexpr int SLOT = kTailRows * NT / 4;  // float4 per slice
+    const int n_tiles = (N + NT - 1) / NT;
+    const TileSchedule sc = scan_experts(offsets, E_local, MT, n_tiles, max_rows, K / KT, true);
+    const int j = blockIdx.x / GROUPS, q = blockIdx.x % GROUPS;
+    if (sc.split <= 1 || j >= sc.total_tail) return;
+    Tile2D tile;
+    if (!decode_tile(sc, E_local, MT, n_tiles, true, j, tile)) return;
+    const int a = q / (TM * 4), b = (q / 4) % TM, g = q % 4;
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int wm = wave / WN_T, wn = wave % WN_T;
+    const float4* mine = partial + static_cast<size_t>(j) * sc.split * SLOT + partial_index<TN, TM>(wave, a, b, g, lane);
+    float4 v[kSplitMax];
+#pragma unroll
+    for (int sl = 0; sl < kSplitMax; ++sl) v[sl] = mine[static_cast<size_t>(min(sl, sc.split - 1)) * SLOT];
+    float z[4] = {v[0].x, v[0].y, v[0].z, v[0].w};
+#pragma unroll
+    for (int sl = 1; sl < kSplitMax; ++sl) {
+        if (sl < sc.split) {
+            z[0] += v[sl].x;
+            z[1] += v[sl].y;
+            z[2] += v[sl].z;
+            z[3] += v[sl].w;
+        }
+    }
+    const int m = tile.row_begin + wm * WTM + b * 32 + (lane & 31);
+    const int n = tile.n_tile * NT + wn * WTN + a * 32 + g * 8 + (lane >> 5) * 4;
+    int dst = m;
+    float scale = 1.0f;
+    if (EPI == kEpiNone && map.out_row != nullptr) {
+        dst = map.out_row[min(m, tile.row_end - 1)];
+        scale = map.out_scale[dst];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        if constexpr (BIAS) z[r] += bf16_to_f32(bias[static_cast<size_t>(tile.expert) * N + min(n + r, N - 1)]);
+        if constexpr (EPI == kEpiGeluErf) z[r] = gelu_erf_fast(z[r]);
+        if constexpr (EPI == kEpiGeluTanh) z[r] = gelu_tanh_fast(z[r]);
+        if constexpr (EPI == kEpiNone) z[r] *= scale;
+    }
+    uint2 packed;
+    packed.x = pack_bf16x2(z[0], z[1]);
+    packed.y = pack_bf16x2(z[2], z[3]);
+    if (m < tile.row_end && n < N)  // N % 8 == 0: the four columns are inside or outside together
+        *reinterpret_cast<uint2*>(out + static_cast<size_t>(dst) * N + n) = packed;
 }
 
 // ---------------------------------------------------------------------------- fp32 kernel
@@ -633,13 +794,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
 // ---------------------------------------------------------------------------- host launchers
 template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int OCC>
 static int launch_bf16(const void* act, const int32_t* offsets, const void* weight, const void* bias, int64_t A, int K, int N,
-                       int E_local, int epi, void* out, hipStream_t stream, const RowMap& map = RowMap{})
+                       int E_local, int epi, void* out, hipStream_t stream, const RowMap& map = RowMap{}, void* partial = nullptr)
 {
     constexpr size_t lds = static_cast<size_t>(STAGES) * (MT + NT) * KT * 2;
-    // worst case: A/MT unmasked row tiles plus, for every expert, its tail tiles or one masked tile
-    const int64_t row_tiles = A / MT + static_cast<int64_t>(E_local) * max_tail_tiles(MT);
+    static_assert(NT <= kSplitMaxCols, "a partial-sum slot holds kTailRows x kSplitMaxCols values");
+    // worst case: A/MT unmasked row tiles plus, for every expert, its tail tiles or one masked tile;
+    // cutting tail tiles into K slices adds fewer than kSplitUnits work items
     const int64_t n_tiles = (N + NT - 1) / NT;
-    const int64_t ub = row_tiles * n_tiles;
+    const int64_t row_tiles = A / MT + static_cast<int64_t>(E_local) * max_tail_tiles(MT);
+    const int64_t ub = row_tiles * n_tiles + (partial != nullptr ? kSplitUnits : 0);
     const int64_t round = static_cast<int64_t>(kXcdCount) * kXcdChunk;
     const int64_t grid = (ub + round - 1) / round * round;
     if (grid >= (1ll << 31)) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn: too many tiles");
@@ -654,7 +817,12 @@ static int launch_bf16(const void* act, const int32_t* offsets, const void* weig
         hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(WM* WN * 64), lds, stream,                              \
                            static_cast<const bf16_t*>(act), offsets, static_cast<const bf16_t*>(weight),                        \
                            static_cast<const bf16_t*>(bias), static_cast<int>(A), K, N, E_local, static_cast<bf16_t*>(out),     \
-                           map);                                                                                                \
+                           map, static_cast<float4*>(partial));                                                                 \
+        if (partial != nullptr && MT > kTailRows && K / KT >= 2 * kSplitMinKTiles)                                              \
+            hipLaunchKernelGGL((tail_reduce_bf16_kernel<MT, NT, KT, WM, WN, EPI, BIAS>),                                        \
+                               dim3(kSplitUnits / 2 * (kTailRows * NT / (WM * WN * 64 * 4))),                                   \
+                               dim3(WM* WN * 64), 0, stream, offsets, static_cast<const bf16_t*>(bias), static_cast<int>(A), K, \
+                               N, E_local, static_cast<const float4*>(partial), static_cast<bf16_t*>(out), map);                \
     } while (0)
     if (bias == nullptr) {
         if (epi == kEpiNone) EXF_LAUNCH_BF16(kEpiNone, false);
@@ -707,7 +875,8 @@ extern "C" size_t moe_expert_ffn_workspace_bytes(int64_t A, int d, int f, int E_
     (void)E_local;
     if (A < 0 || f < 1 || (dt != EXF_F32 && dt != EXF_BF16)) return 0;
     const size_t elem = dt == EXF_BF16 ? 2 : 4;
-    return exf::align_up(static_cast<size_t>(A > 0 ? A : 1) * static_cast<size_t>(f) * elem, 256);
+    const size_t hidden = exf::align_up(static_cast<size_t>(A > 0 ? A : 1) * static_cast<size_t>(f) * elem, 256);
+    return hidden + (dt == EXF_BF16 ? exf::kSplitBytes : 0);  // bf16: + the partial sums of K-sliced tail tiles
 }
 
 extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offsets, const void* w1, const void* b1, const void* w2,
@@ -751,10 +920,12 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
         rc = launch_f32(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s);
         if (rc == EXF_OK) rc = launch_f32(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
     } else {
-        rc = EXF_OK;
-        rc = launch_bf16<EXF_GEMM1_CFG>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s);
+        void* partial = static_cast<unsigned char*>(workspace) + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
+        rc = launch_bf16<EXF_GEMM1_CFG>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s, RowMap{},
+                                        EXF_SPLIT_GEMM1 ? partial : nullptr);
         if (rc == EXF_OK)
-            rc = launch_bf16<EXF_GEMM2_CFG>(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
+            rc = launch_bf16<EXF_GEMM2_CFG>(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s, RowMap{},
+                                            partial);
     }
     if (rc != EXF_OK) return rc;
     return check_launch("moe_expert_ffn");
@@ -770,7 +941,7 @@ extern "C" size_t moe_expert_ffn_fused_workspace_bytes(int64_t T, int k, int d, 
     const size_t A = static_cast<size_t>(T > 0 ? T : 1) * static_cast<size_t>(k);
     size_t bytes = exf::align_up(A * static_cast<size_t>(f) * 2, 256);          // hidden activations [A,f]
     if (k > 1) bytes += exf::align_up(A * static_cast<size_t>(d) * 2, 256);     // sorted expert outputs [A,d]
-    return bytes;
+    return bytes + exf::kSplitBytes;                                            // partial sums of K-sliced tail tiles
 }
 
 extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src, const float* topk_w,
@@ -819,7 +990,10 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
     RowMap gather{};
     gather.a_row = src_of_sorted;
     gather.a_div = k;
-    int rc = launch_bf16<EXF_GEMM1_CFG>(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather);
+    unsigned char* y_sorted = hidden + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
+    void* partial = y_sorted + (k > 1 ? align_up(static_cast<size_t>(A) * static_cast<size_t>(d) * 2, 256) : 0);
+    int rc = launch_bf16<EXF_GEMM1_CFG>(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather,
+                                        EXF_SPLIT_GEMM1 ? partial : nullptr);
     if (rc != EXF_OK) return rc;
     if (k == 1) {
         RowMap scatter{};
@@ -827,12 +1001,11 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
         scatter.out_scale = topk_w;
         scatter.unrouted = sorted_of_src;
         scatter.n_unrouted = static_cast<int>(T);
-        rc = launch_bf16<EXF_GEMM2_CFG>(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, out, s, scatter);
+        rc = launch_bf16<EXF_GEMM2_CFG>(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, out, s, scatter, partial);
         if (rc != EXF_OK) return rc;
         return check_launch("moe_expert_ffn_fused");
     }
-    unsigned char* y_sorted = hidden + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
-    rc = launch_bf16<EXF_GEMM2_CFG>(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
+    rc = launch_bf16<EXF_GEMM2_CFG>(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s, RowMap{}, partial);
     if (rc != EXF_OK) return rc;
     rc = check_launch("moe_expert_ffn_fused");
     if (rc != EXF_OK) return rc;

@@ -76,7 +76,8 @@ def test_host_validation_rejects_before_launch():
          B.EXF_ERR_NULL_PTR),
         (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 1, 64, 256, 8, 0, B.EXF_BF16, two, one, 16, None),
          B.EXF_ERR_WORKSPACE_TOO_SMALL),
-        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 2, 64, 256, 8, 0, B.EXF_BF16, two, one, 4 * 2 * 256 * 2, None),
+        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 2, 64, 256, 8, 0, B.EXF_BF16, two, one,
+                                          4 * 2 * 256 * 2 + 256 * 64 * 256 * 4, None),
          B.EXF_ERR_WORKSPACE_TOO_SMALL),  # top-2 also needs room for the sorted expert outputs
         (lambda: lib.moe_combine(one, one, one, 4, 64, 3, B.EXF_BF16, one, None), B.EXF_ERR_BAD_SHAPE),
         (lambda: lib.moe_combine(one, one, one, 4, 63, 1, B.EXF_F32, one, None), B.EXF_ERR_BAD_SHAPE),
@@ -111,10 +112,11 @@ def test_workspace_sizes():
     lib = exf.lib()
     assert lib.moe_dispatch_workspace_bytes(0, 1, 8) >= 32
     assert lib.moe_dispatch_workspace_bytes(32768, 1, 8) % 256 == 0
-    assert lib.moe_expert_ffn_workspace_bytes(8192, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2
+    split = 256 * 64 * 256 * 4  # bf16: room for the partial sums of K-sliced remainder tiles
+    assert lib.moe_expert_ffn_workspace_bytes(8192, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2 + split
     assert lib.moe_expert_ffn_workspace_bytes(512, 64, 256, 8, B.EXF_F32) == 512 * 256 * 4
-    assert lib.moe_expert_ffn_fused_workspace_bytes(8192, 1, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2
-    assert lib.moe_expert_ffn_fused_workspace_bytes(256, 2, 4096, 16384, 64, B.EXF_BF16) == 512 * (16384 + 4096) * 2
+    assert lib.moe_expert_ffn_fused_workspace_bytes(8192, 1, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2 + split
+    assert lib.moe_expert_ffn_fused_workspace_bytes(256, 2, 4096, 16384, 64, B.EXF_BF16) == 512 * (16384 + 4096) * 2 + split
     assert lib.moe_expert_ffn_fused_workspace_bytes(256, 1, 64, 256, 8, B.EXF_F32) == 0  # bf16 only
     ws = lib.affinity_histogram_workspace_bytes(24, 1 << 20, 64)
     assert 0 < ws < 64 << 20  # partial histograms stay far below the 100 MB trace

@@ -179,6 +179,14 @@ def test_ffn_bf16_long_reduction(oracle):
     _ffn_case(oracle, "bf16", [600, 200, 70, 0, 256], 1024, 512, 0, False, seed=430)
 
 
+@pytest.mark.parametrize("bias", [False, True])
+def test_ffn_bf16_remainder_tiles_in_k_slices(oracle, bias):
+    """Few remainder tiles and a long second reduction: they run as K slices added by a second kernel."""
+    _say(f"ffn bf16 K-sliced remainder tiles bias={bias}")
+    _ffn_case(oracle, "bf16", [70, 300, 5], 128, 1024, 0, bias, seed=440)          # 4 tail tiles x 4 slices
+    _ffn_case(oracle, "bf16", [257, 0, 129, 64, 1], 256, 2048, 1, bias, seed=441)  # 8 slices, two column tiles
+
+
 def test_ffn_bf16_many_experts_skewed(oracle):
     _say("ffn bf16 skewed 32 experts")
     tr, _ = syn.planted_trace(1, 3000, 32, 0.0, seed=420, marginal="zipf")
@@ -305,6 +313,7 @@ def test_ffn_fused_top1_parity(oracle, act, bias):
 
 def test_ffn_fused_top1_skewed_and_tiny(oracle):
     _say("ffn fused top-1 skewed / tiny")
+    _fused_case(oracle, 900, 128, 1024, 6, 6, 1, 0, True, seed=713)  # remainder tiles in K slices, scattered by the adding kernel
     _fused_case(oracle, 3000, 256, 512, 32, 32, 1, 0, False, seed=710, skew=True)
     _fused_case(oracle, 1, 64, 64, 4, 4, 1, 0, False, seed=711)
     _fused_case(oracle, 67, 64, 64, 8, 1, 1, 0, True, seed=712)  # one resident expert, seven of eight tokens unrouted
