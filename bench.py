@@ -32,11 +32,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM-side bytes per moe_expert_ffn call at the benchmark configuration, from two rocprofv3 --pmc
-# runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch summed over the call's two launches), each
+# HBM-side bytes per moe_expert_ffn_fused call at the benchmark configuration, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch summed over the call's three launches), each
 # scaled by what the same counter reads for the 1 GiB copy probe (FETCH x2.000, WRITE x1.000):
-# (81593.9 + 114006.2) KiB x 2 + (65536 + 16384) KiB.  See profiles/bench_config2_hbm_traffic.txt.
-FFN_TRAFFIC_BYTES = int((81593.9 + 114006.2) * 2 * 1024 + (65536 + 16384) * 1024)
+# (73565.0 + 116047.2 + 3875.2) KiB x 2 + (65536 + 23692 + 744) KiB.  See profiles/bench_config2_hbm_traffic.txt.
+FFN_TRAFFIC_BYTES = int((73565.0 + 116047.2 + 3875.2) * 2 * 1024 + (65536 + 23692 + 744) * 1024)
 
 
 def _events(n):
@@ -256,7 +256,7 @@ def main():
                     if bf16 else "grouped_gemm_f32_kernel (moe_expert_ffn, fp32 vector ALU: latency-bound tiny case)",
                     "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS if bf16 else 157.3, "unit": "TFLOP/s",
                     "frac": achieved_tf / (PEAK_BF16_TFLOPS if bf16 else 157.3),
-                    "traffic": FFN_TRAFFIC_BYTES if cfg.index == 2 else None, "ms_per_launch": ffn_ms, "flops_per_launch": ffn_flops}
+                    "traffic": FFN_TRAFFIC_BYTES if (cfg.index == 2 and fused) else None, "ms_per_launch": ffn_ms, "flops_per_launch": ffn_flops}
     workloads = {
         1: "configs[0] tiny fp32: d_model=64 d_ff=256 E=8 top-1 T=512; 2-layer x 512-token trace",
         2: "configs[1] GPT-MoE-350M-shaped: d_model=1024 d_ff=4096 E=8 top-1 T=8192 bf16; affinity on a 12-layer x 8192-token "
