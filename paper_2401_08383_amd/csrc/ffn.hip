@@ -866,6 +866,22 @@ static int launch_f32(const void* act, const int32_t* offsets, const void* weigh
 #define EXF_GEMM2_CFG 256, 128, 64, 3, 4, 2, 1, 1
 #endif
 
+// The second contraction has few output columns (N = d).  With 256x128 tiles it offers twice as many
+// tiles, which a short batch needs to fill the chip; the 256x256 tile of the first contraction moves
+// a third less operand data per flop through the L2s and is taken once it, too, gives every compute
+// unit at least EXF_WIDE_ROUNDS tiles.
+#ifndef EXF_WIDE_ROUNDS
+#define EXF_WIDE_ROUNDS 2
+#endif
+static int launch_second_contraction(const void* act, const int32_t* offsets, const void* weight, const void* bias, int64_t A,
+                                     int K, int N, int E_local, void* out, hipStream_t stream, const RowMap& map, void* partial)
+{
+    const int64_t wide_tiles = (A / 256) * ((N + 255) / 256);
+    if (EXF_WIDE_ROUNDS > 0 && wide_tiles >= static_cast<int64_t>(EXF_WIDE_ROUNDS) * kSplitUnits)
+        return launch_bf16<EXF_GEMM1_CFG>(act, offsets, weight, bias, A, K, N, E_local, kEpiNone, out, stream, map, partial);
+    return launch_bf16<EXF_GEMM2_CFG>(act, offsets, weight, bias, A, K, N, E_local, kEpiNone, out, stream, map, partial);
+}
+
 }  // namespace exf
 
 
@@ -924,8 +940,7 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
         rc = launch_bf16<EXF_GEMM1_CFG>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s, RowMap{},
                                         EXF_SPLIT_GEMM1 ? partial : nullptr);
         if (rc == EXF_OK)
-            rc = launch_bf16<EXF_GEMM2_CFG>(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s, RowMap{},
-                                            partial);
+            rc = launch_second_contraction(workspace, expert_offsets, w2, b2, A, f, d, E_local, y_sorted, s, RowMap{}, partial);
     }
     if (rc != EXF_OK) return rc;
     return check_launch("moe_expert_ffn");
@@ -1001,11 +1016,11 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
         scatter.out_scale = topk_w;
         scatter.unrouted = sorted_of_src;
         scatter.n_unrouted = static_cast<int>(T);
-        rc = launch_bf16<EXF_GEMM2_CFG>(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, out, s, scatter, partial);
+        rc = launch_second_contraction(hidden, expert_offsets, w2, b2, A, f, d, E_local, out, s, scatter, partial);
         if (rc != EXF_OK) return rc;
         return check_launch("moe_expert_ffn_fused");
     }
-    rc = launch_bf16<EXF_GEMM2_CFG>(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s, RowMap{}, partial);
+    rc = launch_second_contraction(hidden, expert_offsets, w2, b2, A, f, d, E_local, y_sorted, s, RowMap{}, partial);
     if (rc != EXF_OK) return rc;
     rc = check_launch("moe_expert_ffn_fused");
     if (rc != EXF_OK) return rc;

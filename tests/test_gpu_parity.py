@@ -187,6 +187,17 @@ def test_ffn_bf16_remainder_tiles_in_k_slices(oracle, bias):
     _ffn_case(oracle, "bf16", [257, 0, 129, 64, 1], 256, 2048, 1, bias, seed=441)  # 8 slices, two column tiles
 
 
+def test_ffn_bf16_wide_second_contraction(oracle):
+    """Enough rows and output columns that the second contraction takes its 256x256 tile (with K-sliced
+    remainder tiles); sampled rows of every expert against the oracle."""
+    _say("ffn bf16 wide second contraction")
+    counts = [9000, 70, 7430]
+    off = np.concatenate([[0], np.cumsum(counts)])
+    g = syn.rng(450)
+    rows = np.unique(np.concatenate([off[:-1], off[1:] - 1, g.integers(0, off[-1], size=40)]))
+    _ffn_case(oracle, "bf16", counts, 2048, 512, 0, True, seed=451, rows=rows)
+
+
 def test_ffn_bf16_many_experts_skewed(oracle):
     _say("ffn bf16 skewed 32 experts")
     tr, _ = syn.planted_trace(1, 3000, 32, 0.0, seed=420, marginal="zipf")
