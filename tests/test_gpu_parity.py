@@ -86,6 +86,10 @@ def _run_dispatch(oracle, x, idx, E, E_local, expert_map, dtype):
     kept = ref["kept"]
     xs = to_host(res.x_sorted)[:kept]
     np.testing.assert_array_equal(xs, x[ref["src_of_sorted"] // k])  # a pure copy: bit-exact
+    # index-only mode (no sorted rows; short batches take a single launch): the same maps
+    only = exf.moe_dispatch(to_dev(x, dtype), dev_i32(idx), E, E_local, None if expert_map is None else dev_i32(expert_map),
+                            gather=False)
+    expected_dispatch_compare(only, ref, T * k)
     return res, ref
 
 
