@@ -3,9 +3,11 @@
  * context-coherent Mixture-of-Experts inference with inter-layer expert affinity
  * (arXiv 2401.08383).
  *
- * Two groups of calls:
- *   MoE expert layer : moe_gate_topk -> moe_dispatch -> moe_expert_ffn -> moe_combine
- *   affinity statistic: affinity_histogram, placement_locality
+ * Three groups of calls:
+ *   MoE expert layer  : moe_gate_topk -> moe_dispatch -> moe_expert_ffn -> moe_combine, or
+ *                       moe_gate_topk -> moe_dispatch (index maps only) -> moe_expert_ffn_fused
+ *   affinity statistic: affinity_histogram, affinity_multihop, placement_locality, routing_transfers
+ *   placement search  : placement_locality_from_counts (GPU scoring), exf_placement_search (host)
  *
  * Conventions that hold for every call
  *   - Returns EXF_OK (0) or a negative EXF_ERR_* code; exf_last_error() gives the text of the
@@ -133,7 +135,8 @@ int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* expert_m
  *   b1 [E_local,f] dt or NULL;  b2 [E_local,d] dt or NULL;  y_sorted [A,d] dt.
  * bf16: the hidden activations are rounded to bf16 once, between the two contractions.
  * Shapes: d, f multiples of 64 (bf16) / 4 (fp32); 1 <= E_local <= EXF_MAX_EXPERTS.
- * workspace: moe_expert_ffn_workspace_bytes(A, d, f, E_local, dt) bytes (the [A,f] hidden).
+ * workspace: moe_expert_ffn_workspace_bytes(A, d, f, E_local, dt) bytes (the [A,f] hidden; bf16:
+ * plus 16 MiB for the partial sums of remainder tiles that are cut along the reduction).
  * ------------------------------------------------------------------------------------- */
 size_t moe_expert_ffn_workspace_bytes(int64_t A, int d, int f, int E_local, int dt);
 int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offsets, const void* w1, const void* b1,
