@@ -29,23 +29,12 @@
 namespace exf {
 
 constexpr int kXcds = 8;
-#ifndef EXF_TRACE_THREADS
-#define EXF_TRACE_THREADS 1024
-#endif
-#ifndef EXF_TARGET_WGS
-#define EXF_TARGET_WGS 256
-#endif
-#ifndef EXF_LOC_AHEAD
-#define EXF_LOC_AHEAD 2
-#endif
-constexpr int kTraceThreads = EXF_TRACE_THREADS;
-#ifndef EXF_AFF_GROUP
-#define EXF_AFF_GROUP 3
-#endif
-constexpr int kAffMaxGroup = EXF_AFF_GROUP;                        // layer pairs per workgroup (4 columns in registers; 3 measured best, 29 against 34 us with 6 on a 24 x 1M trace)
-constexpr size_t kAffHistBudget = 48 * 1024;           // LDS bytes for the packed pair histograms
-constexpr int64_t kAffMaxChunk = 61440;                // tokens per workgroup: 16-bit counters cannot overflow
-constexpr int kTargetWorkgroups = EXF_TARGET_WGS;       // about one per CU
+constexpr int kTraceThreads = 1024;
+constexpr int kAffMaxGroup = 3;                 // layer pairs per workgroup (4 columns in registers; 3 measured best,
+                                                // 29 against 34 us with 6 on a 24 x 1M trace)
+constexpr size_t kAffHistBudget = 48 * 1024;    // LDS bytes for the packed pair histograms
+constexpr int64_t kAffMaxChunk = 61440;         // tokens per workgroup: 16-bit counters cannot overflow
+constexpr int kTargetWorkgroups = 256;          // about one per CU
 
 struct AffinityPlan {
     int g;           // layer pairs per workgroup
@@ -447,7 +436,7 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
 }
 
 // ------------------------------------------------------------------------------------------
-constexpr int kLocAhead = EXF_LOC_AHEAD;  // trace layers whose loads are in flight together
+constexpr int kLocAhead = 2;  // trace layers whose loads are in flight together
 
 // HOME: additionally counts, per layer, the tokens whose expert sits on another device than
 // home[n] (the device that owns the token's request); the per-chunk partials then hold the L-1 pair

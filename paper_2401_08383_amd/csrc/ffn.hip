@@ -76,10 +76,7 @@ enum Epilogue { kEpiNone = 0, kEpiGeluErf = 1, kEpiGeluTanh = 2 };
 // numbered (expert, column tile, row tile); locate_tile() says which kind a launch runs first.
 constexpr int kTailRows = 64;
 __host__ __device__ constexpr int max_tail_tiles(int mt) { return mt / 2 >= kTailRows ? (mt / 2 + kTailRows - 1) / kTailRows : 1; }
-#ifndef EXF_XCD_CHUNK
-#define EXF_XCD_CHUNK 32
-#endif
-constexpr int kXcdChunk = EXF_XCD_CHUNK;  // consecutive tiles handed to one XCD at a time (32: one per CU of the XCD)
+constexpr int kXcdChunk = 32;  // consecutive tiles handed to one XCD at a time: one per compute unit of the XCD
 
 struct Tile2D {
     int expert;
@@ -100,17 +97,11 @@ struct Tile2D {
 constexpr int kSplitUnits = 256;    // one slice per compute unit
 constexpr int kSplitMaxCols = 256;  // widest tile a partial-sum slot is sized for
 constexpr size_t kSplitBytes = static_cast<size_t>(kSplitUnits) * kTailRows * kSplitMaxCols * sizeof(float);
-#ifndef EXF_SPLIT_MIN_KTILES
-#define EXF_SPLIT_MIN_KTILES 4
-#endif
-constexpr int kSplitMinKTiles = EXF_SPLIT_MIN_KTILES;  // shortest K slice worth a workgroup
-constexpr int kSplitMax = 8;                            // most K slices per tail tile
-#ifndef EXF_TAILS_FIRST
-#define EXF_TAILS_FIRST 1
-#endif
-#ifndef EXF_SPLIT_GEMM1
-#define EXF_SPLIT_GEMM1 0  // K slices in the first contraction too: measured slower (its reduction is the short one)
-#endif
+constexpr int kSplitMinKTiles = 4;  // shortest K slice worth a workgroup (2 and 8 measured the same)
+constexpr int kSplitMax = 8;        // most K slices per tail tile
+// Only the second contraction slices: its reduction is the long one, and in the first contraction the
+// kernel that adds the slices (and applies GELU) cost more than the slices saved.
+constexpr bool kSplitFirstContraction = false;
 
 // Workgroup id -> tile index.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
 // id % 8 is the XCD and id / 8 the position in that XCD's queue; chunks of kXcdChunk consecutive
@@ -178,12 +169,9 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
     // row tiles x kBlockCols column tiles (one XCD chunk): the 32 workgroups of a block share 4
     // activation and 8 weight panels in their L2, against 16 and 2 when the rows of a column simply
     // follow each other.  Remaining row tiles (and small experts) run row tile fastest.
-#ifndef EXF_BLOCK_ROWS
-#define EXF_BLOCK_ROWS 4
-#endif
-    constexpr int kBlockRows = EXF_BLOCK_ROWS, kBlockCols = kXcdChunk / (EXF_BLOCK_ROWS > 0 ? EXF_BLOCK_ROWS : 1);
+    constexpr int kBlockRows = 4, kBlockCols = kXcdChunk / kBlockRows;
     int row_tile, col_tile;
-    const int blocked_rows = (kBlockRows > 0 && !tail && n_tiles % (kBlockCols > 0 ? kBlockCols : 1) == 0) ? e_rt / kBlockRows * kBlockRows : 0;
+    const int blocked_rows = (!tail && n_tiles % kBlockCols == 0) ? e_rt / kBlockRows * kBlockRows : 0;
     if (r < blocked_rows * n_tiles) {
         const int per_row_block = kBlockRows * n_tiles;
         const int rbk = r / per_row_block, in_rb = r - rbk * per_row_block;
@@ -215,7 +203,7 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
     const TileSchedule sc = scan_experts(offsets, E_local, mt, n_tiles, max_rows, nk, may_split);
     const int tail_units = sc.total_tail * sc.split;
     if (idx >= sc.total_full + tail_units) return false;
-    const bool tails_first = EXF_TAILS_FIRST && tail_units <= kSplitUnits;
+    const bool tails_first = tail_units <= kSplitUnits;
     const bool tail = tails_first ? idx < tail_units : idx >= sc.total_full;
     const int u = tails_first ? idx : idx - sc.total_full;
     const int full_idx = tails_first ? idx - tail_units : idx;
@@ -420,11 +408,9 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     // Operand register ring: FD K steps deep (fetches run FD-1 K steps ahead of the MFMAs).  Two is
     // enough when a K step holds many MFMAs; a wavefront tile of one or two MFMAs per K step (the
     // remainder tiles) takes four, or every K step would expose a full LDS round trip.
-#ifndef EXF_FRAG_DEPTH_SMALL
-#define EXF_FRAG_DEPTH_SMALL 4  // (2 measured slower on remainder tiles)
-#endif
+    constexpr int kFragDepthSmall = 4;  // (2 measured slower on remainder tiles)
     constexpr int SLOTS = TN * TM;
-    constexpr int FD = (SLOTS <= 2 && KSTEPS % EXF_FRAG_DEPTH_SMALL == 0) ? EXF_FRAG_DEPTH_SMALL : 2;
+    constexpr int FD = (SLOTS <= 2 && KSTEPS % kFragDepthSmall == 0) ? kFragDepthSmall : 2;
     static_assert(KSTEPS % FD == 0, "the ring index of a K step must not depend on the K tile");
     bf16x8_t fa[FD][TN], fb[FD][TM];
     auto fetch = [&](const unsigned char* stage, int ks, int r) {  // operand r of K step ks from a stage
@@ -651,10 +637,8 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
         // which the tail needs, because it has little MFMA work per K tile to hide the loads.
         constexpr int kRing = STAGES * (MT + NT) * KT * 2;
         constexpr int kFit = kRing / ((kTailRows + NT) * KT * 2);
-#ifndef EXF_TAIL_STAGES_MAX
-#define EXF_TAIL_STAGES_MAX 4
-#endif
-        constexpr int STAGES_T = kFit >= EXF_TAIL_STAGES_MAX ? EXF_TAIL_STAGES_MAX : (kFit >= 2 ? kFit : 2);
+        constexpr int kTailStagesMax = 4;  // (5 and 6, also with the whole 160 KB of LDS, measured slower)
+        constexpr int STAGES_T = kFit >= kTailStagesMax ? kTailStagesMax : (kFit >= 2 ? kFit : 2);
         constexpr int WM_T = NT / (WM * WN) >= 32 ? 1 : 2;
         float4* slot = tile.slot >= 0 ? partial + static_cast<size_t>(tile.slot) * (kTailRows * NT / 4) : nullptr;
         gemm_tile<kTailRows, NT, KT, STAGES_T, WM_T, WM * WN / WM_T, SWZ, EPI, BIAS, true>(
@@ -869,15 +853,13 @@ static int launch_f32(const void* act, const int32_t* offsets, const void* weigh
 // The second contraction has few output columns (N = d).  With 256x128 tiles it offers twice as many
 // tiles, which a short batch needs to fill the chip; the 256x256 tile of the first contraction moves
 // a third less operand data per flop through the L2s and is taken once it, too, gives every compute
-// unit at least EXF_WIDE_ROUNDS tiles.
-#ifndef EXF_WIDE_ROUNDS
-#define EXF_WIDE_ROUNDS 2
-#endif
+// unit at least kWideRounds tiles.
+constexpr int kWideRounds = 2;  // (1 measured the same on 16384 and 32768 tokens)
 static int launch_second_contraction(const void* act, const int32_t* offsets, const void* weight, const void* bias, int64_t A,
                                      int K, int N, int E_local, void* out, hipStream_t stream, const RowMap& map, void* partial)
 {
     const int64_t wide_tiles = (A / 256) * ((N + 255) / 256);
-    if (EXF_WIDE_ROUNDS > 0 && wide_tiles >= static_cast<int64_t>(EXF_WIDE_ROUNDS) * kSplitUnits)
+    if (wide_tiles >= static_cast<int64_t>(kWideRounds) * kSplitUnits)
         return launch_bf16<EXF_GEMM1_CFG>(act, offsets, weight, bias, A, K, N, E_local, kEpiNone, out, stream, map, partial);
     return launch_bf16<EXF_GEMM2_CFG>(act, offsets, weight, bias, A, K, N, E_local, kEpiNone, out, stream, map, partial);
 }
@@ -938,7 +920,7 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
     } else {
         void* partial = static_cast<unsigned char*>(workspace) + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
         rc = launch_bf16<EXF_GEMM1_CFG>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s, RowMap{},
-                                        EXF_SPLIT_GEMM1 ? partial : nullptr);
+                                        kSplitFirstContraction ? partial : nullptr);
         if (rc == EXF_OK)
             rc = launch_second_contraction(workspace, expert_offsets, w2, b2, A, f, d, E_local, y_sorted, s, RowMap{}, partial);
     }
@@ -1008,7 +990,7 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
     unsigned char* y_sorted = hidden + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
     void* partial = y_sorted + (k > 1 ? align_up(static_cast<size_t>(A) * static_cast<size_t>(d) * 2, 256) : 0);
     int rc = launch_bf16<EXF_GEMM1_CFG>(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather,
-                                        EXF_SPLIT_GEMM1 ? partial : nullptr);
+                                        kSplitFirstContraction ? partial : nullptr);
     if (rc != EXF_OK) return rc;
     if (k == 1) {
         RowMap scatter{};

@@ -327,10 +327,7 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
     // the end are clamped; the operand is zeroed when it is used) and a scheduling barrier keeps
     // them in front of the MFMAs, so PF loads per lane are in flight while the matrix cores work;
     // left to itself the compiler sinks every load down to its MFMA.
-#ifndef EXF_GATE_PF
-#define EXF_GATE_PF 4
-#endif
-    constexpr int PF = EXF_GATE_PF;
+    constexpr int PF = 4;
     typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_v;
     auto issue = [&](int64_t tl, int s0, i32x4_v(&b)[PF]) {
         const int64_t t = min(min(tl, n_tiles - 1) * 16 + r16, T - 1);
@@ -345,7 +342,6 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
     issue(tile, 0, cur);  // the first x loads travel while W_gate is copied
 
     // W_gate -> LDS, eight 16-byte loads in flight per thread (a plain loop runs one at a time)
-#ifndef EXF_GATE_NOFILL
     {
         const uint4* wg16 = reinterpret_cast<const uint4*>(wg);
         const int total = EP * chunks, valid = E * chunks;
@@ -362,7 +358,6 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
             }
         }
     }
-#endif
     __syncthreads();
     if (!has_work) return;
     int s0 = 0;
