@@ -200,6 +200,11 @@ def test_ffn_bf16_wide_second_contraction(oracle):
     g = syn.rng(450)
     rows = np.unique(np.concatenate([off[:-1], off[1:] - 1, g.integers(0, off[-1], size=40)]))
     _ffn_case(oracle, "bf16", counts, 2048, 512, 0, True, seed=451, rows=rows)
+    # output width that is no multiple of the tile width (4 tiles of 256 columns and one of 64)
+    counts = [20000, 6600]
+    off = np.concatenate([[0], np.cumsum(counts)])
+    rows = np.unique(np.concatenate([off[:-1], off[1:] - 1, g.integers(0, off[-1], size=30)]))
+    _ffn_case(oracle, "bf16", counts, 1088, 128, 1, False, seed=452, rows=rows)
 
 
 def test_ffn_bf16_many_experts_skewed(oracle):
