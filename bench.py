@@ -3,8 +3,10 @@
 
 A step = one pass of the whole hot path over one synthetic batch of the GPT-MoE-350M-shaped
 configuration (d_model 1024, d_ff 4096, 8 experts, top-1, 8192 tokens, bf16, fp32 accumulation):
-gate+top-k -> dispatch -> grouped expert FFN -> combine, then affinity_histogram and
-placement_locality over the configuration's 12-layer x 8192-token routing trace.
+gate+top-k -> dispatch -> grouped expert FFN -> combine (bf16: index-only dispatch and
+moe_expert_ffn_fused), and the affinity statistic (co-routing counts, loads, conditional
+probabilities and the locality numerators of a placement: affinity_statistics, one pass) over the
+configuration's 12-layer x 8192-token routing trace.
 Inputs are resident in HBM before the timed region; no allocation happens inside it.
 
 `--config N` times another of the five workload configurations the same way (the decode-shaped
@@ -138,8 +140,11 @@ def main():
     ap.add_argument("--unfused", action="store_true",
                     help="bf16 configurations: sorted copies of the activations and a separate combine pass "
                          "(moe_expert_ffn + moe_combine) instead of moe_expert_ffn_fused")
-    ap.add_argument("--no-overlap", action="store_true",
-                    help="run the affinity statistic on the layer's stream instead of a second stream beside it")
+    ap.add_argument("--two-pass-affinity", action="store_true",
+                    help="affinity_histogram + placement_locality (two passes over the trace) instead of affinity_statistics")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run the affinity statistic on a second stream beside the layer (forked and joined every step) "
+                         "instead of on the layer's stream")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives, no sharding)",
@@ -191,13 +196,15 @@ def main():
     if cfg.trace_L > 0:
         trace_h, _ = syn.config_trace(cfg)
         pl_h = syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(cfg.index, 5))
-        aff = AffinityRun(torch.from_numpy(trace_h).to(dev), torch.from_numpy(pl_h).to(dev), cfg.trace_E, cfg.G)
+        aff = AffinityRun(torch.from_numpy(trace_h).to(dev), torch.from_numpy(pl_h).to(dev), cfg.trace_E, cfg.G,
+                          one_pass=not args.two_pass_affinity)
 
-    # The affinity statistic reads a routing trace and nothing of the layer: it runs on a second
-    # stream (default priority) beside the layer's kernels, forked at the start of a step and joined
-    # at its end, and fills compute units the layer leaves idle (the sparse last round of the GEMMs).
+    # The affinity statistic reads a routing trace and nothing of the layer.  By default its two
+    # launches go to the layer's stream; --overlap puts them on a second stream (default priority),
+    # forked at the start of a step and joined at its end - measured slower at this configuration (the
+    # two cross-stream waits cost more than the 10 us of statistic they hide).
     main_stream = torch.cuda.current_stream()
-    side_stream = torch.cuda.Stream() if (aff is not None and not args.no_overlap) else None
+    side_stream = torch.cuda.Stream() if (aff is not None and args.overlap) else None
 
     def affinity_fork():
         if aff is None:
@@ -282,7 +289,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": workloads[cfg.index], "tokens": cfg.T, "d_model": cfg.d, "d_ff": cfg.f, "experts": cfg.E,
                    "local_experts": cfg.E_local, "top_k": cfg.k, "layers_per_step": cfg.layers, "trace_layers": cfg.trace_L,
-                   "trace_tokens": cfg.trace_N, "ffn_entry": ffn_entry},
+                   "trace_tokens": cfg.trace_N, "ffn_entry": ffn_entry,
+                   "affinity_entry": "affinity_histogram + placement_locality" if args.two_pass_affinity else "affinity_statistics"},
         "roofline": roofline,
     }
     achieved = achieved_tf
@@ -295,6 +303,7 @@ def main():
         per["ffn_ms"] = _time_call(layer.ffn, 30)
         per["combine_ms"] = _time_call(layer.combine, 50)
         if aff is not None:
+            per["affinity_statistics_ms"] = _time_call(aff.statistics, 50)
             per["affinity_histogram_ms"] = _time_call(aff.histogram, 50)
             per["placement_locality_ms"] = _time_call(aff.locality, 50)
         layer_ms = per["gate_ms"] + per["dispatch_ms"] + per["ffn_ms"] + per["combine_ms"]
@@ -361,6 +370,9 @@ def main():
         ms = _time_rotating(lambda i: (lambda: aff4.locality(traces[i])), tr_sets, 30)
         hbm["placement_locality"] = {"ms": ms, "GBps": bytes_tr / (ms * 1e-3) / 1e9, "frac": bytes_tr / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                      "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
+        ms = _time_rotating(lambda i: (lambda: aff4.statistics(traces[i])), tr_sets, 30)
+        hbm["affinity_statistics"] = {"ms": ms, "GBps": bytes_tr / (ms * 1e-3) / 1e9, "frac": bytes_tr / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                      "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
         result["hbm_bound_calls_config4_shapes"] = hbm
 
         # placement search on the one-GPU-share trace (24 layers x 1M tokens, E=64, 8 GPUs on 2 nodes):

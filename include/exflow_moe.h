@@ -6,7 +6,8 @@
  * Three groups of calls:
  *   MoE expert layer  : moe_gate_topk -> moe_dispatch -> moe_expert_ffn -> moe_combine, or
  *                       moe_gate_topk -> moe_dispatch (index maps only) -> moe_expert_ffn_fused
- *   affinity statistic: affinity_histogram, affinity_multihop, placement_locality, routing_transfers
+ *   affinity statistic: affinity_histogram, placement_locality (both in one pass: affinity_statistics),
+ *                       affinity_multihop, routing_transfers
  *   placement search  : placement_locality_from_counts (GPU scoring), exf_placement_search (host)
  *
  * Conventions that hold for every call
@@ -229,6 +230,21 @@ int affinity_multihop(const int32_t* trace, int L, int64_t N, int E, int64_t* co
 size_t placement_locality_workspace_bytes(int L, int64_t N);
 int placement_locality(const int32_t* trace, const int32_t* placement, int L, int64_t N, int E, int G,
                        int64_t* local_per_pair, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * affinity_statistics — affinity_histogram and the locality numerators of placement_locality
+ * from ONE pass over the trace (same passages as those two calls).  The locality numerator of a
+ * layer pair is a function of its co-routing counts,
+ *   local_per_pair[l] = sum_{i,p} counts[l][i][p] * [ placement[l][i] == placement[l+1][p] ],
+ * so the launch that sums the per-chunk histograms adds it up as well and the trace is not read
+ * a second time.  Outputs, shapes and the treatment of invalid ids are those of the two calls;
+ * loads, cond_prob and n_invalid may be NULL; local_per_pair [L-1] int64 is overwritten.
+ * workspace: affinity_statistics_workspace_bytes(L, N, E) bytes.
+ * ------------------------------------------------------------------------------------- */
+size_t affinity_statistics_workspace_bytes(int L, int64_t N, int E);
+int affinity_statistics(const int32_t* trace, const int32_t* placement, int L, int64_t N, int E, int G,
+                        int64_t* counts, int64_t* loads, float* cond_prob, int64_t* n_invalid,
+                        int64_t* local_per_pair, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * routing_transfers — the cross-GPU token transfers of a routing trace under a placement

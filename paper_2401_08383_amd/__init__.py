@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     SIGNATURES,
     affinity_histogram,
     affinity_multihop,
+    affinity_statistics,
     check_placement,
     last_error,
     lib,

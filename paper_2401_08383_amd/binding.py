@@ -45,6 +45,8 @@ SIGNATURES = {
     "moe_combine": (_i, [_vp, _vp, _vp, _i64, _i, _i, _i, _vp, _vp]),
     "affinity_histogram_workspace_bytes": (_sz, [_i, _i64, _i]),
     "affinity_histogram": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "affinity_statistics_workspace_bytes": (_sz, [_i, _i64, _i]),
+    "affinity_statistics": (_i, [_vp, _vp, _i, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "placement_locality_workspace_bytes": (_sz, [_i, _i64]),
     "placement_locality": (_i, [_vp, _vp, _i, _i64, _i, _i, _vp, _vp, _sz, _vp]),
     "affinity_multihop_workspace_bytes": (_sz, [_i, _i64, _i]),
@@ -242,6 +244,30 @@ def affinity_histogram(trace, E, want_loads=True, want_prob=True, want_invalid=T
         workspace = _workspace(nbytes, dev)
     _check(lib().affinity_histogram(_ptr(trace), L, N, E, _ptr(out["counts"]), _ptr(out["loads"]), _ptr(out["cond_prob"]),
                                     _ptr(out["n_invalid"]), _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def affinity_statistics(trace, placement, G, want_loads=True, want_prob=True, want_invalid=True, workspace=None, out=None):
+    """One pass over the trace -> dict(counts, loads, cond_prob, n_invalid, local_per_pair) of device tensors."""
+    L, N = trace.shape
+    E = placement.shape[1]
+    assert placement.shape[0] == L and placement.dtype == torch.int32 and trace.dtype == torch.int32
+    assert trace.is_contiguous() and placement.is_contiguous()
+    dev = trace.device
+    if out is None:
+        out = dict(
+            counts=torch.empty((max(L - 1, 0), E, E), dtype=torch.int64, device=dev),
+            loads=torch.empty((L, E), dtype=torch.int64, device=dev) if want_loads else None,
+            cond_prob=torch.empty((max(L - 1, 0), E, E), dtype=torch.float32, device=dev) if want_prob else None,
+            n_invalid=torch.empty(1, dtype=torch.int64, device=dev) if want_invalid else None,
+            local_per_pair=torch.empty(max(L - 1, 0), dtype=torch.int64, device=dev),
+        )
+    nbytes = lib().affinity_statistics_workspace_bytes(L, N, E)
+    if workspace is None:
+        workspace = _workspace(nbytes, dev)
+    _check(lib().affinity_statistics(_ptr(trace), _ptr(placement), L, N, E, G, _ptr(out["counts"]), _ptr(out["loads"]),
+                                     _ptr(out["cond_prob"]), _ptr(out["n_invalid"]), _ptr(out["local_per_pair"]), _ptr(workspace),
+                                     workspace.numel(), _stream()))
     return out
 
 

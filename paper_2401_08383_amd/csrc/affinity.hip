@@ -44,7 +44,7 @@ struct AffinityPlan {
     int64_t chunk;   // tokens per workgroup
     int C;           // token chunks
     int vec;         // 4 if 16-byte trace loads are possible, else 1
-    size_t off_counts, off_orphan_next, off_orphan_last, off_invalid, total_bytes;
+    size_t off_counts, off_orphan_next, off_orphan_last, off_invalid, off_local, total_bytes;
 };
 
 static AffinityPlan make_affinity_plan(int L, int64_t N, int E, bool aligned)
@@ -80,6 +80,8 @@ static AffinityPlan make_affinity_plan(int L, int64_t N, int E, bool aligned)
     off += align_up(static_cast<size_t>(p.C) * E * sizeof(uint32_t), 256);
     p.off_invalid = off;
     off += align_up(static_cast<size_t>(p.C) * p.Q * sizeof(uint32_t), 256);
+    p.off_local = off;  // per chunk and pair: transitions that stay on their device (affinity_statistics)
+    off += align_up(static_cast<size_t>(p.C) * (pairs > 0 ? pairs : 1) * sizeof(uint32_t), 256);
     p.total_bytes = off > 0 ? off : 256;
     return p;
 }
@@ -119,13 +121,17 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
                                                                           uint32_t* __restrict__ part_counts,
                                                                           uint32_t* __restrict__ part_orphan_next,
                                                                           uint32_t* __restrict__ part_orphan_last,
-                                                                          uint32_t* __restrict__ part_invalid)
+                                                                          uint32_t* __restrict__ part_invalid,
+                                                                          const int32_t* __restrict__ placement,  // [L,E] or null
+                                                                          uint32_t* __restrict__ part_local)      // with placement
 {
     extern __shared__ uint32_t lds[];
     uint32_t* hist = lds;                                 // [copies][g][words], two 16-bit counters per word
     uint32_t* orphan_next = hist + copies * g * words;    // [g][E]   valid id whose successor is invalid
     uint32_t* orphan_last = orphan_next + g * E;          // [E]      valid id of the final layer whose predecessor is invalid
     uint32_t* invalid_cnt = orphan_last + E;              // [1]
+    uint32_t* stay_cnt = invalid_cnt + 1;                 // [g]      transitions whose two experts share a device
+    int32_t* device = reinterpret_cast<int32_t*>(stay_cnt + g);  // [g+1][E] placement rows of this group's layers
 
     // XCD-aware decomposition: consecutive workgroup ids are dealt round-robin to the XCDs, so
     // the XCD is blockIdx % 8; all pair groups of one token chunk are given to the same XCD.
@@ -135,13 +141,15 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
     const int q = j % Q;
     if (c >= C) return;
 
-    const int lds_words = copies * g * words + g * E + E + 1;
+    const int lds_words = copies * g * words + g * E + E + 1 + g;
     for (int i = threadIdx.x; i < lds_words; i += kTraceThreads) lds[i] = 0u;
-    __syncthreads();
-
     const int pairs = L - 1;
     const int l0 = q * g;                                  // first column of this group
     const int l1 = pairs > 0 ? min(l0 + g, pairs) : 0;     // last column (pairs l0 .. l1-1)
+    if (placement != nullptr)
+        for (int i = threadIdx.x; i < (l1 - l0 + 1) * E; i += kTraceThreads) device[i] = placement[l0 * E + i];
+    __syncthreads();
+
     const bool owns_last = (l1 == L - 1);
     const int64_t n_begin = static_cast<int64_t>(c) * chunk;
     const int64_t n_end = min(N, n_begin + chunk);
@@ -231,12 +239,29 @@ __global__ __launch_bounds__(kTraceThreads) void affinity_partial_kernel(const i
     if (invalid_local) atomicAdd(invalid_cnt, invalid_local);
     __syncthreads();
 
-    // flush: sum the replicas (packed halves cannot carry: a bin holds at most `chunk` < 65536)
+    // flush: sum the replicas (packed halves cannot carry: a bin holds at most `chunk` < 65536); with a
+    // placement, also count per pair the transitions of the bins whose two experts share a device
     const int my_pairs = l1 - l0;
     for (int i = threadIdx.x; i < my_pairs * words; i += kTraceThreads) {
         uint32_t s = 0;
         for (int r = 0; r < copies; ++r) s += hist[r * g * words + i];
         part_counts[(static_cast<size_t>(c) * pairs + l0) * words + i] = s;
+        if (placement != nullptr) {
+            const int pr = i / words, wd = i - pr * words;
+            const int32_t* here = device + pr * E;
+            const int32_t* there = here + E;
+            uint32_t stay = 0;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int bin = 2 * wd + h;
+                if (bin < E * E && here[bin / E] == there[bin % E]) stay += (s >> (16 * h)) & 0xffffu;
+            }
+            if (stay != 0) atomicAdd(&stay_cnt[pr], stay);
+        }
+    }
+    if (placement != nullptr) {
+        __syncthreads();
+        if (static_cast<int>(threadIdx.x) < my_pairs) part_local[static_cast<size_t>(c) * pairs + l0 + threadIdx.x] = stay_cnt[threadIdx.x];
     }
     for (int i = threadIdx.x; i < my_pairs * E; i += kTraceThreads)
         part_orphan_next[(static_cast<size_t>(c) * pairs + l0) * E + i] = orphan_next[i];
@@ -344,14 +369,16 @@ __global__ __launch_bounds__(kTraceThreads) void multihop_partial_kernel(const i
 // wavefront w sums the chunks c = w, w+4, ... of bin (i, p = lane), the four partial sums meet in
 // LDS -> counts, row sum, load of (l, i), conditional probabilities.  The next E workgroups take one
 // expert p of the FINAL layer each: its load is the column sum of the last pair (taken from the
-// partials, so that no result of another workgroup is needed) plus the orphans.  The last workgroup
-// adds up the invalid tally.
+// partials, so that no result of another workgroup is needed) plus the orphans.  One workgroup
+// adds up the invalid tally.  With a placement, L-1 more workgroups form the locality numerators.
 __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* __restrict__ part_counts,
                                                                 const uint32_t* __restrict__ part_orphan_next,
                                                                 const uint32_t* __restrict__ part_orphan_last,
                                                                 const uint32_t* __restrict__ part_invalid, int C, int Q, int L, int E,
                                                                 int words, int64_t* __restrict__ counts, int64_t* __restrict__ loads,
-                                                                float* __restrict__ cond_prob, int64_t* __restrict__ n_invalid)
+                                                                float* __restrict__ cond_prob, int64_t* __restrict__ n_invalid,
+                                                                const uint32_t* __restrict__ part_local,  // [C][L-1] or null
+                                                                int64_t* __restrict__ local)              // [L-1] (with part_local)
 {
     __shared__ long long red[4][kWave];
     __shared__ long long orphan_red[4];
@@ -424,7 +451,7 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
         if (p == 0) orphan_red[w] = s;
         __syncthreads();
         if (threadIdx.x == 0) loads[static_cast<size_t>(L - 1) * E + pe] = orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
-    } else {
+    } else if (static_cast<int>(blockIdx.x) == row_blocks + E) {
         if (n_invalid == nullptr) return;
         long long inv = 0;
         for (int i = threadIdx.x; i < C * Q; i += 256) inv += part_invalid[i];
@@ -432,6 +459,16 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
         if (p == 0) orphan_red[w] = inv;
         __syncthreads();
         if (threadIdx.x == 0) *n_invalid = orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
+    } else {
+        // locality numerator of pair l: the per-chunk counts of the first launch added up
+        if (part_local == nullptr) return;
+        const int l = blockIdx.x - (row_blocks + E + 1);
+        long long stay = 0;
+        for (int c = threadIdx.x; c < C; c += 256) stay += part_local[static_cast<size_t>(c) * pairs + l];
+        stay = wave_sum(stay);
+        if (p == 0) orphan_red[w] = stay;
+        __syncthreads();
+        if (threadIdx.x == 0) local[l] = orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
     }
 }
 
@@ -596,6 +633,49 @@ extern "C" size_t affinity_histogram_workspace_bytes(int L, int64_t N, int E)
     return a > b ? a : b;
 }
 
+namespace exf {
+
+// affinity_histogram and affinity_statistics: the same two launches.  With a placement every
+// workgroup of the first launch also counts, per pair, the transitions of its finished histogram whose
+// two experts share a device, and the second launch has one more workgroup per pair to add these up.
+static int run_affinity(const char* fn, const int32_t* trace, const int32_t* placement, int L, int64_t N, int E, int64_t* counts,
+                        int64_t* loads, float* cond_prob, int64_t* n_invalid, int64_t* local_per_pair, void* workspace,
+                        size_t workspace_bytes, void* stream)
+{
+    const AffinityPlan p = make_affinity_plan(L, N, E, aligned16(trace));
+    if (workspace_bytes < p.total_bytes) return fail(EXF_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total_bytes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    uint32_t* part_counts = reinterpret_cast<uint32_t*>(ws + p.off_counts);
+    uint32_t* part_orphan_next = reinterpret_cast<uint32_t*>(ws + p.off_orphan_next);
+    uint32_t* part_orphan_last = reinterpret_cast<uint32_t*>(ws + p.off_orphan_last);
+    uint32_t* part_invalid = reinterpret_cast<uint32_t*>(ws + p.off_invalid);
+    uint32_t* part_local = placement != nullptr ? reinterpret_cast<uint32_t*>(ws + p.off_local) : nullptr;
+    if (p.C > 0) {
+        const int c_pad = (p.C + kXcds - 1) / kXcds * kXcds;
+        const unsigned grid = static_cast<unsigned>(c_pad) * p.Q;
+        const size_t lds = (static_cast<size_t>(p.copies) * p.g * p.words + static_cast<size_t>(p.g) * E + E + 1 + p.g +
+                            static_cast<size_t>(p.g + 1) * E) * sizeof(uint32_t);
+        if (p.vec == 4) {
+            if (int rc = allow_large_lds(affinity_partial_kernel<4>, lds, fn)) return rc;
+            hipLaunchKernelGGL(affinity_partial_kernel<4>, dim3(grid), dim3(kTraceThreads), lds, s, trace, L, N, E, p.g, p.Q, p.copies,
+                               p.words, p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid, placement, part_local);
+        } else {
+            if (int rc = allow_large_lds(affinity_partial_kernel<1>, lds, fn)) return rc;
+            hipLaunchKernelGGL(affinity_partial_kernel<1>, dim3(grid), dim3(kTraceThreads), lds, s, trace, L, N, E, p.g, p.Q, p.copies,
+                               p.words, p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid, placement, part_local);
+        }
+    }
+    // rows of all pairs, then the loads of the final layer, the invalid tally and (with a placement) the
+    // locality numerators of all pairs
+    const unsigned fin_grid = static_cast<unsigned>((L - 1) * E + E + 1 + (placement != nullptr ? L - 1 : 0));
+    hipLaunchKernelGGL(affinity_finalize_kernel, dim3(fin_grid), dim3(256), 0, s, part_counts, part_orphan_next, part_orphan_last,
+                       part_invalid, p.C, p.Q, L, E, p.words, counts, loads, cond_prob, n_invalid, part_local, local_per_pair);
+    return check_launch(fn);
+}
+
+}  // namespace exf
+
 extern "C" int affinity_histogram(const int32_t* trace, int L, int64_t N, int E, int64_t* counts, int64_t* loads,
                                   float* cond_prob, int64_t* n_invalid, void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -604,34 +684,28 @@ extern "C" int affinity_histogram(const int32_t* trace, int L, int64_t N, int E,
     if (N > 0) EXF_REQUIRE_PTR(trace);
     if (L > 1) EXF_REQUIRE_PTR(counts);
     EXF_REQUIRE_PTR(workspace);
-    const AffinityPlan p = make_affinity_plan(L, N, E, aligned16(trace));
-    if (workspace_bytes < p.total_bytes)
-        return fail(EXF_ERR_WORKSPACE_TOO_SMALL, "affinity_histogram: workspace %zu < %zu bytes", workspace_bytes, p.total_bytes);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    char* ws = static_cast<char*>(workspace);
-    uint32_t* part_counts = reinterpret_cast<uint32_t*>(ws + p.off_counts);
-    uint32_t* part_orphan_next = reinterpret_cast<uint32_t*>(ws + p.off_orphan_next);
-    uint32_t* part_orphan_last = reinterpret_cast<uint32_t*>(ws + p.off_orphan_last);
-    uint32_t* part_invalid = reinterpret_cast<uint32_t*>(ws + p.off_invalid);
-    if (p.C > 0) {
-        const int c_pad = (p.C + kXcds - 1) / kXcds * kXcds;
-        const unsigned grid = static_cast<unsigned>(c_pad) * p.Q;
-        const size_t lds = (static_cast<size_t>(p.copies) * p.g * p.words + static_cast<size_t>(p.g) * E + E + 1) * sizeof(uint32_t);
-        if (p.vec == 4) {
-            if (int rc = allow_large_lds(affinity_partial_kernel<4>, lds, "affinity_histogram")) return rc;
-            hipLaunchKernelGGL(affinity_partial_kernel<4>, dim3(grid), dim3(kTraceThreads), lds, s, trace, L, N, E, p.g, p.Q, p.copies,
-                               p.words, p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid);
-        } else {
-            if (int rc = allow_large_lds(affinity_partial_kernel<1>, lds, "affinity_histogram")) return rc;
-            hipLaunchKernelGGL(affinity_partial_kernel<1>, dim3(grid), dim3(kTraceThreads), lds, s, trace, L, N, E, p.g, p.Q, p.copies,
-                               p.words, p.chunk, p.C, part_counts, part_orphan_next, part_orphan_last, part_invalid);
-        }
+    return run_affinity("affinity_histogram", trace, nullptr, L, N, E, counts, loads, cond_prob, n_invalid, nullptr, workspace,
+                        workspace_bytes, stream);
+}
+
+extern "C" size_t affinity_statistics_workspace_bytes(int L, int64_t N, int E) { return affinity_histogram_workspace_bytes(L, N, E); }
+
+extern "C" int affinity_statistics(const int32_t* trace, const int32_t* placement, int L, int64_t N, int E, int G, int64_t* counts,
+                                   int64_t* loads, float* cond_prob, int64_t* n_invalid, int64_t* local_per_pair, void* workspace,
+                                   size_t workspace_bytes, void* stream)
+{
+    using namespace exf;
+    if (int rc = validate_trace_args("affinity_statistics", L, N, E)) return rc;
+    if (G < 1) return fail(EXF_ERR_BAD_SHAPE, "affinity_statistics: G = %d < 1", G);
+    if (N > 0) EXF_REQUIRE_PTR(trace);
+    EXF_REQUIRE_PTR(placement);
+    if (L > 1) {
+        EXF_REQUIRE_PTR(counts);
+        EXF_REQUIRE_PTR(local_per_pair);
     }
-    // rows of all pairs, then the loads of the final layer, then the invalid tally
-    const unsigned fin_grid = static_cast<unsigned>((L - 1) * E + E + 1);
-    hipLaunchKernelGGL(affinity_finalize_kernel, dim3(fin_grid), dim3(256), 0, s, part_counts, part_orphan_next, part_orphan_last,
-                       part_invalid, p.C, p.Q, L, E, p.words, counts, loads, cond_prob, n_invalid);
-    return check_launch("affinity_histogram");
+    EXF_REQUIRE_PTR(workspace);
+    return run_affinity("affinity_statistics", trace, placement, L, N, E, counts, loads, cond_prob, n_invalid, local_per_pair,
+                        workspace, workspace_bytes, stream);
 }
 
 namespace exf {
@@ -711,7 +785,7 @@ extern "C" int affinity_multihop(const int32_t* trace, int L, int64_t N, int E, 
     // (the finalize kernel of the one-hop statistic, told that there are pairs+1 "layers" and no loads)
     const unsigned fin_grid = static_cast<unsigned>(p.pairs * E);
     hipLaunchKernelGGL(affinity_finalize_kernel, dim3(fin_grid), dim3(256), 0, s, part_counts, nullptr, nullptr, nullptr, p.C, 1,
-                       p.pairs + 1, E, p.words, counts, nullptr, cond_prob, nullptr);
+                       p.pairs + 1, E, p.words, counts, nullptr, cond_prob, nullptr, nullptr, nullptr);
     return check_launch("affinity_multihop");
 }
 

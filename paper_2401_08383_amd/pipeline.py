@@ -4,8 +4,8 @@
 (gate -> dispatch -> expert FFN -> combine, all enqueued on the current stream with no host
 synchronisation in between; with ``fused=True`` the dispatch is index-only and
 moe_expert_ffn_fused reads and writes the unsorted token rows, so no combine call follows);
-``AffinityRun`` does the same for affinity_histogram and placement_locality over a
-device-resident trace.  Argument marshalling only.
+``AffinityRun`` does the same for the affinity statistic over a device-resident trace
+(affinity_statistics, or affinity_histogram + placement_locality).  Argument marshalling only.
 """
 from __future__ import annotations
 
@@ -89,8 +89,9 @@ class MoELayerRun:
 
 
 class AffinityRun:
-    def __init__(self, trace, placement, E, G):
+    def __init__(self, trace, placement, E, G, one_pass=True):
         self.lib = B.lib()
+        self.one_pass = bool(one_pass)  # step() = affinity_statistics, else affinity_histogram + placement_locality
         self.trace, self.placement = trace, placement
         self.L, self.N = trace.shape
         self.E, self.G = E, G
@@ -118,6 +119,17 @@ class AffinityRun:
                                              self.local_per_pair.data_ptr(), self.ws_loc.data_ptr(), self.ws_loc.numel(),
                                              B._stream()))
 
+    def statistics(self, trace=None):
+        """Both results from one pass over the trace (affinity_statistics)."""
+        t = self.trace if trace is None else trace
+        B._check(self.lib.affinity_statistics(t.data_ptr(), self.placement.data_ptr(), self.L, self.N, self.E, self.G,
+                                              self.counts.data_ptr(), self.loads.data_ptr(), self.cond_prob.data_ptr(),
+                                              self.n_invalid.data_ptr(), self.local_per_pair.data_ptr(), self.ws_hist.data_ptr(),
+                                              self.ws_hist.numel(), B._stream()))
+
     def step(self):
-        self.histogram()
-        self.locality()
+        if self.one_pass:
+            self.statistics()
+        else:
+            self.histogram()
+            self.locality()

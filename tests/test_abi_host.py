@@ -86,6 +86,10 @@ def test_host_validation_rejects_before_launch():
         (lambda: lib.affinity_histogram(one, 3, 8, 65, one, None, None, None, one, 1 << 20, None), B.EXF_ERR_BAD_SHAPE),
         (lambda: lib.affinity_histogram(one, 3, 8, 4, None, None, None, None, one, 1 << 20, None), B.EXF_ERR_NULL_PTR),
         (lambda: lib.affinity_histogram(one, 3, 8, 4, one, None, None, None, one, 8, None), B.EXF_ERR_WORKSPACE_TOO_SMALL),
+        (lambda: lib.affinity_statistics(one, None, 3, 8, 4, 2, one, None, None, None, one, one, 1 << 20, None), B.EXF_ERR_NULL_PTR),
+        (lambda: lib.affinity_statistics(one, one, 3, 8, 4, 2, one, None, None, None, None, one, 1 << 20, None), B.EXF_ERR_NULL_PTR),
+        (lambda: lib.affinity_statistics(one, one, 3, 8, 4, 0, one, None, None, None, one, one, 1 << 20, None), B.EXF_ERR_BAD_SHAPE),
+        (lambda: lib.affinity_statistics(one, one, 3, 8, 4, 2, one, None, None, None, one, one, 8, None), B.EXF_ERR_WORKSPACE_TOO_SMALL),
         (lambda: lib.placement_locality(one, None, 3, 8, 4, 2, one, one, 1 << 20, None), B.EXF_ERR_NULL_PTR),
         (lambda: lib.placement_locality(one, one, 3, 8, 4, 0, one, one, 1 << 20, None), B.EXF_ERR_BAD_SHAPE),
         (lambda: lib.placement_locality(one, one, 3, 8, 4, 2, one, one, 0, None), B.EXF_ERR_WORKSPACE_TOO_SMALL),
@@ -121,6 +125,7 @@ def test_workspace_sizes():
     ws = lib.affinity_histogram_workspace_bytes(24, 1 << 20, 64)
     assert 0 < ws < 64 << 20  # partial histograms stay far below the 100 MB trace
     assert lib.placement_locality_workspace_bytes(24, 1 << 20) > 0
+    assert lib.affinity_statistics_workspace_bytes(24, 1 << 20, 64) == ws
 
 
 def test_check_placement_constraints():

@@ -124,7 +124,14 @@ def _check_fused(oracle, cfg, plain, x, w1, w2, ref, rows_per_expert, seed, expe
 
 
 def _check_affinity(oracle, cfg, trace, placement):
-    aff = AffinityRun(torch.from_numpy(trace).to(DEV), torch.from_numpy(placement).to(DEV), cfg.trace_E, cfg.G)
+    frac = None
+    for one_pass in (True, False):  # affinity_statistics, then affinity_histogram + placement_locality
+        frac = _check_affinity_run(oracle, cfg, trace, placement, one_pass)
+    return frac
+
+
+def _check_affinity_run(oracle, cfg, trace, placement, one_pass):
+    aff = AffinityRun(torch.from_numpy(trace).to(DEV), torch.from_numpy(placement).to(DEV), cfg.trace_E, cfg.G, one_pass=one_pass)
     aff.step()
     counts, loads, n_inv = oracle.affinity_counts(trace, cfg.trace_E)
     np.testing.assert_array_equal(aff.counts.cpu().numpy(), counts)

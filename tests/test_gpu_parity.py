@@ -376,6 +376,18 @@ def _affinity_case(oracle, trace, E, placement=None, G=1):
     if placement is not None and L > 1:
         loc = exf.placement_locality(dev_i32(trace).reshape(L, N), dev_i32(placement), G)
         np.testing.assert_array_equal(loc.cpu().numpy(), oracle.placement_locality(trace, placement))
+        # both results from one pass over the trace; called twice into the same (first garbage-filled)
+        # outputs: the locality numerators are accumulated, so they must start from zero every time
+        both = None
+        for _ in range(2):
+            if both is not None:
+                both["local_per_pair"].fill_(123456789)
+            both = exf.affinity_statistics(dev_i32(trace).reshape(L, N), dev_i32(placement), G, out=both)
+            np.testing.assert_array_equal(both["counts"].cpu().numpy(), counts)
+            np.testing.assert_array_equal(both["loads"].cpu().numpy(), loads)
+            assert int(both["n_invalid"].cpu()) == n_inv
+            assert (np.abs(both["cond_prob"].cpu().numpy() - prob) <= np.spacing(prob)).all()
+            np.testing.assert_array_equal(both["local_per_pair"].cpu().numpy(), oracle.placement_locality(trace, placement))
 
 
 @pytest.mark.parametrize("L,N,E,G", [(2, 512, 8, 4), (12, 8192, 8, 4), (12, 16384, 32, 8), (5, 100001, 64, 8), (3, 70003, 16, 2),
@@ -409,6 +421,8 @@ def test_affinity_invalid_ids_and_degenerate(oracle):
     assert (res["cond_prob"].cpu().numpy() == 0).all() and int(res["n_invalid"].cpu()) == 0
     loc = exf.placement_locality(torch.empty((4, 0), dtype=torch.int32, device=DEV), dev_i32(np.zeros((4, 8))), 1)
     assert (loc.cpu().numpy() == 0).all()
+    both = exf.affinity_statistics(torch.empty((4, 0), dtype=torch.int32, device=DEV), dev_i32(np.zeros((4, 8))), 1)
+    assert (both["local_per_pair"].cpu().numpy() == 0).all() and (both["counts"].cpu().numpy() == 0).all()
     # deterministic routing: one hot column per row, and an aligned placement keeps every token local
     tr, perms = syn.planted_trace(5, 9999, 8, 1.0, seed=714)
     pl = syn.aligned_placement(perms, 8, 4)
@@ -423,6 +437,7 @@ def test_locality_paper_worked_example_on_gpu():
     pl = syn.contiguous_placement(3, 8, 4)
     loc = exf.placement_locality(dev_i32(trace), dev_i32(pl), 4).cpu().numpy()
     assert loc.sum() == 2 and loc.tolist() == [1, 1]
+    assert exf.affinity_statistics(dev_i32(trace), dev_i32(pl), 4)["local_per_pair"].cpu().numpy().tolist() == [1, 1]
     assert exf.check_placement(torch.from_numpy(pl), 4)
 
 
