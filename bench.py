@@ -37,8 +37,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per moe_expert_ffn_fused call at the benchmark configuration, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch summed over the call's three launches), each
 # scaled by what the same counter reads for the 1 GiB copy probe (FETCH x2.000, WRITE x1.000):
-# (73565.0 + 116047.2 + 3875.2) KiB x 2 + (65536 + 23692 + 744) KiB.  See profiles/bench_config2_hbm_traffic.txt.
-FFN_TRAFFIC_BYTES = int((73565.0 + 116047.2 + 3875.2) * 2 * 1024 + (65536 + 23692 + 744) * 1024)
+# (73565.0 + 116043.8 + 3875.2) KiB x 2 + (65536 + 23692 + 744) KiB.  See profiles/bench_config2_hbm_traffic.txt.
+FFN_TRAFFIC_BYTES = int((73565.0 + 116043.8 + 3875.2) * 2 * 1024 + (65536 + 23692 + 744) * 1024)
 
 
 def _events(n):
