@@ -131,8 +131,8 @@ def cpu_baseline(cfg, x, wg, w1, w2, trace, placement, sample_rows_per_expert=No
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
                     help="workload configuration (default 2: the one the headline metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
