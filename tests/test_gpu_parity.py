@@ -452,3 +452,24 @@ def test_repeat_calls_are_deterministic():
     r1 = exf.moe_dispatch(x, idx, 64)
     r2 = exf.moe_dispatch(x, idx, 64)
     assert torch.equal(r1.src_of_sorted, r2.src_of_sorted) and torch.equal(r1.x_sorted, r2.x_sorted)
+    # expert FFN with remainder tiles in K slices (the slices are added in a fixed order), through both
+    # entry points, with the workspace overwritten between the calls
+    g = syn.rng(721)
+    T, d, f, E = 2100, 128, 1024, 6
+    xs = to_dev(g.standard_normal((T, d), dtype=np.float32), "bf16")
+    w1 = to_dev(g.standard_normal((E, f, d), dtype=np.float32) * np.float32(0.05), "bf16")
+    w2 = to_dev(g.standard_normal((E, d, f), dtype=np.float32) * np.float32(0.05), "bf16")
+    idx = dev_i32(g.integers(0, E, size=(T, 1)))
+    gate = torch.rand((T, 1), device=DEV)
+    disp = exf.moe_dispatch(xs, idx, E)
+    nbytes = max(exf.lib().moe_expert_ffn_workspace_bytes(T, d, f, E, exf.EXF_BF16),
+                 exf.lib().moe_expert_ffn_fused_workspace_bytes(T, 1, d, f, E, exf.EXF_BF16))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    outs = []
+    for fill in (0, 255):
+        ws.fill_(fill)
+        y = exf.moe_expert_ffn(disp.x_sorted, disp.expert_offsets, w1, w2, workspace=ws)
+        ws.fill_(255 - fill)
+        o = exf.moe_expert_ffn_fused(xs, disp.src_of_sorted, disp.sorted_of_src, gate, disp.expert_offsets, w1, w2, workspace=ws)
+        outs.append((y.clone(), o.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
