@@ -321,9 +321,31 @@ def main():
         sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
         ms = _time_call(lambda: lib.exf_probe_mfma(wgs, iters, sink.data_ptr(), B._stream()), 5)
         mfma_tflops = wgs * 4 * 4 * iters * 32768.0 / (ms * 1e-3) / 1e12
-        result["box"] = {"copy_GBps": copy_gbs, "mfma_loop_TFLOPs": mfma_tflops}
+        # the bare GEMM K loop on all-zero and on random operands (the chip holds a power limit: what
+        # the matrix cores sustain depends on the values they multiply), the latter also after a longer run
+        loop_bytes = lib.exf_probe_gemm_loop_bytes()
+        loop_sink = torch.empty(256 * 256, dtype=torch.float32, device=dev)
+        loop_flops = 10 * 512 * 2.0 * 256 * 256 * 1024
+
+        def loop_rate(buf, iters):
+            ms = _time_call(lambda: lib.exf_probe_gemm_loop(buf.data_ptr(), loop_bytes, 10, loop_sink.data_ptr(), B._stream()), iters)
+            return loop_flops / (ms * 1e-3) / 1e12
+
+        zeros = torch.zeros(loop_bytes // 2, dtype=torch.bfloat16, device=dev)
+        loop_zero = loop_rate(zeros, 3)
+        del zeros
+        rnd = torch.randn(loop_bytes // 2, dtype=torch.float32, device=dev).to(torch.bfloat16)
+        torch.cuda.synchronize()
+        time.sleep(0.2)
+        loop_rand = loop_rate(rnd, 3)
+        loop_rand_sustained = loop_rate(rnd, 40)
+        del rnd
+        result["box"] = {"copy_GBps": copy_gbs, "mfma_loop_TFLOPs": mfma_tflops, "gemm_k_loop_zero_operands_TFLOPs": loop_zero,
+                         "gemm_k_loop_random_operands_TFLOPs": loop_rand,
+                         "gemm_k_loop_random_operands_sustained_TFLOPs": loop_rand_sustained}
         if roofline["bound"] == "mfma" and bf16:
             result["roofline"]["frac_of_measured_mfma_loop"] = achieved / mfma_tflops
+            result["roofline"]["frac_of_measured_gemm_k_loop_random_operands"] = achieved / max(loop_rand, loop_rand_sustained)
 
     if not args.no_extra and cfg.index == 2:
         # HBM-bound entry points at the shapes of the one-GPU-share configuration (rotating buffers)

@@ -311,9 +311,18 @@ int exf_placement_search(const int64_t* counts_host, int L, int E, int G, int no
  *   exf_probe_mfma: `workgroups` x 256 threads, every wavefront issues 4*iters independent
  *                   32x32x16 bf16 MFMAs (4*iters*32768 flop per wavefront); out receives
  *                   workgroups*256 floats (device) so that the loop cannot be removed.
+ *   exf_probe_gemm_loop: the bare K loop of a 256x256x64-tiled bf16 GEMM (direct-to-LDS operand
+ *                   loads, LDS operand fetches, MFMAs, one barrier per K tile; no epilogue) over
+ *                   caller-supplied operands: `operands` holds exf_probe_gemm_loop_bytes() bytes
+ *                   (8 x [1024,1024] activations followed by 8 x [4096,1024] weights, bf16);
+ *                   256 workgroups walk all 512 output tiles `passes` times, i.e.
+ *                   passes * 512 * 2*256*256*1024 flop; out receives 256*256 floats.  The rate it
+ *                   reaches depends on the operand values (all zeros against random numbers).
  * ------------------------------------------------------------------------------------- */
 int exf_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 int exf_probe_mfma(int workgroups, int iters, float* out, void* stream);
+size_t exf_probe_gemm_loop_bytes(void);
+int exf_probe_gemm_loop(const void* operands, size_t bytes, int passes, float* out, void* stream);
 
 #ifdef __cplusplus
 }

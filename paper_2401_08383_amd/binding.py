@@ -57,6 +57,8 @@ SIGNATURES = {
     "exf_placement_search": (_i, [_vp, _i, _i, _i, _i, _i, ctypes.c_uint64, _vp]),
     "exf_probe_copy": (_i, [_vp, _vp, _sz, _vp]),
     "exf_probe_mfma": (_i, [_i, _i, _vp, _vp]),
+    "exf_probe_gemm_loop_bytes": (_sz, []),
+    "exf_probe_gemm_loop": (_i, [_vp, _sz, _i, _vp, _vp]),
 }
 
 _lib = None

@@ -90,6 +90,9 @@ def test_host_validation_rejects_before_launch():
         (lambda: lib.affinity_statistics(one, one, 3, 8, 4, 2, one, None, None, None, None, one, 1 << 20, None), B.EXF_ERR_NULL_PTR),
         (lambda: lib.affinity_statistics(one, one, 3, 8, 4, 0, one, None, None, None, one, one, 1 << 20, None), B.EXF_ERR_BAD_SHAPE),
         (lambda: lib.affinity_statistics(one, one, 3, 8, 4, 2, one, None, None, None, one, one, 8, None), B.EXF_ERR_WORKSPACE_TOO_SMALL),
+        (lambda: lib.exf_probe_gemm_loop(one, 1 << 20, 1, one, None), B.EXF_ERR_WORKSPACE_TOO_SMALL),
+        (lambda: lib.exf_probe_gemm_loop(None, lib.exf_probe_gemm_loop_bytes(), 1, one, None), B.EXF_ERR_NULL_PTR),
+        (lambda: lib.exf_probe_gemm_loop(one, lib.exf_probe_gemm_loop_bytes(), 0, one, None), B.EXF_ERR_BAD_SHAPE),
         (lambda: lib.placement_locality(one, None, 3, 8, 4, 2, one, one, 1 << 20, None), B.EXF_ERR_NULL_PTR),
         (lambda: lib.placement_locality(one, one, 3, 8, 4, 0, one, one, 1 << 20, None), B.EXF_ERR_BAD_SHAPE),
         (lambda: lib.placement_locality(one, one, 3, 8, 4, 2, one, one, 0, None), B.EXF_ERR_WORKSPACE_TOO_SMALL),
@@ -125,6 +128,7 @@ def test_workspace_sizes():
     ws = lib.affinity_histogram_workspace_bytes(24, 1 << 20, 64)
     assert 0 < ws < 64 << 20  # partial histograms stay far below the 100 MB trace
     assert lib.placement_locality_workspace_bytes(24, 1 << 20) > 0
+    assert lib.exf_probe_gemm_loop_bytes() == 8 * (1024 + 4096) * 1024 * 2
     assert lib.affinity_statistics_workspace_bytes(24, 1 << 20, 64) == ws
 
 
