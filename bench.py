@@ -138,7 +138,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel and large-shape measurements")
     ap.add_argument("--unfused", action="store_true",
-                    help="bf16 configurations: sorted copies of the activations and a separate combine pass "
+                    help="sorted copies of the activations and a separate combine pass "
                          "(moe_expert_ffn + moe_combine) instead of moe_expert_ffn_fused")
     ap.add_argument("--two-pass-affinity", action="store_true",
                     help="affinity_histogram + placement_locality (two passes over the trace) instead of affinity_statistics")
@@ -164,7 +164,7 @@ def main():
 
     cfg = syn.CONFIGS[args.config]
     bf16 = cfg.dtype == "bf16"
-    fused = bf16 and not args.unfused  # the fused entry point is bf16 only
+    fused = not args.unfused
 
     def to_device(a):
         t = torch.from_numpy(a)
@@ -260,7 +260,7 @@ def main():
                     "ms_per_launch": ffn_ms, "bytes_per_launch": ffn_bytes}
     else:
         roofline = {"bound": "mfma", "kernel": f"grouped_gemm_bf16_kernel ({ffn_entry}: both contractions)"
-                    if bf16 else "grouped_gemm_f32_kernel (moe_expert_ffn, fp32 vector ALU: latency-bound tiny case)",
+                    if bf16 else f"grouped_gemm_f32_kernel ({ffn_entry}, fp32 vector ALU: latency-bound tiny case)",
                     "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS if bf16 else 157.3, "unit": "TFLOP/s",
                     "frac": achieved_tf / (PEAK_BF16_TFLOPS if bf16 else 157.3),
                     "traffic": FFN_TRAFFIC_BYTES if (cfg.index == 2 and fused) else None, "ms_per_launch": ffn_ms, "flops_per_launch": ffn_flops}

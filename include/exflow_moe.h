@@ -150,15 +150,16 @@ int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offsets, const vo
  * The first contraction reads row src_of_sorted[s] / k of x for sorted row s, so moe_dispatch
  * can be called with x_sorted = NULL (index-only) and no sorted copy of the activations exists.
  * With k = 1 the second contraction multiplies its fp32 result by the token's gate weight and
- * writes it to the token's own row of `out` (one rounding to bf16); rows of tokens whose
+ * writes it to the token's own row of `out` (one rounding to dt); rows of tokens whose
  * assignment was not kept (sorted_of_src[t] < 0) are set to zero.  With k > 1 the second
  * contraction writes sorted rows into the workspace and the combine kernel follows.
  *
  *   out[t][:] = sum_{j<k, sorted_of_src[t*k+j] >= 0} topk_w[t][j] * FFN_{e(t,j)}( x[t][:] )
  *
- *   x [T,d] bf16;  src_of_sorted [T*k], sorted_of_src [T*k], expert_offsets [E_local+1] as
+ *   x [T,d] dt;  src_of_sorted [T*k], sorted_of_src [T*k], expert_offsets [E_local+1] as
  *   written by moe_dispatch;  topk_w [T,k] fp32;  weights and biases as for moe_expert_ffn;
- *   out [T,d] bf16, must not overlap x.  bf16 only (dt = EXF_BF16), d and f multiples of 64.
+ *   out [T,d] dt, must not overlap x.  Shapes as for moe_expert_ffn (d, f multiples of 64 for
+ *   bf16, of 4 for fp32).
  * workspace: moe_expert_ffn_fused_workspace_bytes(T, k, d, f, E_local, dt) bytes.
  * ------------------------------------------------------------------------------------- */
 size_t moe_expert_ffn_fused_workspace_bytes(int64_t T, int k, int d, int f, int E_local, int dt);

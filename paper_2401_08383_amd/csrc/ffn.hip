@@ -714,18 +714,29 @@ __global__ __launch_bounds__(WM* WN * 64) void tail_reduce_bf16_kernel(const int
 template <int EPI>
 __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __restrict__ act, const int32_t* __restrict__ offsets,
                                                                 const float* __restrict__ weight, const float* __restrict__ bias,
-                                                                int max_rows, int K, int N, int E_local, float* __restrict__ out)
+                                                                int max_rows, int K, int N, int E_local, float* __restrict__ out,
+                                                                const RowMap map)
 {
     constexpr int MT = 64, NT = 64, KT = 16;
     __shared__ float As[KT][MT + 4];
     __shared__ float Bs[KT][NT + 4];
+    if (map.unrouted != nullptr) {  // output rows no sorted row writes: one thread per row clears it
+        const int64_t stride = static_cast<int64_t>(gridDim.x) * gridDim.y * 256;
+        for (int64_t t = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * 256 + threadIdx.x; t < map.n_unrouted; t += stride)
+            if (map.unrouted[t] < 0) {
+                float4* row = reinterpret_cast<float4*>(out + static_cast<size_t>(t) * N);
+                for (int c = 0; c < N / 4; ++c) row[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+    }
     const TileRef tile = locate_row_tile(offsets, E_local, MT, blockIdx.x, max_rows);
     if (tile.expert < 0) return;
     const int n0 = blockIdx.y * NT;
     const float* wexp = weight + static_cast<size_t>(tile.expert) * N * K;
     const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
     const int lrow = threadIdx.x / 4, lk = (threadIdx.x % 4) * 4;
-    const float* arow = act + static_cast<size_t>(min(tile.row_begin + lrow, tile.row_end - 1)) * K;
+    int a_row = min(tile.row_begin + lrow, tile.row_end - 1);
+    if (map.a_row != nullptr) a_row = map.a_row[a_row] / map.a_div;
+    const float* arow = act + static_cast<size_t>(a_row) * K;
     const float* brow = wexp + static_cast<size_t>(min(n0 + lrow, N - 1)) * K;
     float acc[4][4];
 #pragma unroll
@@ -762,6 +773,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
         if (m >= tile.row_end) continue;
         const int n = n0 + tx * 4;
         if (n >= N) continue;  // N % 4 == 0
+        int dst = m;
+        float scale = 1.0f;
+        if (EPI == kEpiNone && map.out_row != nullptr) {
+            dst = map.out_row[m];
+            scale = map.out_scale[dst];
+        }
         float v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -769,9 +786,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
             if (bexp != nullptr) z += bexp[n + j];
             if constexpr (EPI == kEpiGeluErf) z = gelu_erf_exact(z);
             if constexpr (EPI == kEpiGeluTanh) z = gelu_tanh_exact(z);
+            if constexpr (EPI == kEpiNone) z *= scale;
             v[j] = z;
         }
-        *reinterpret_cast<float4*>(out + static_cast<size_t>(m) * N + n) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(out + static_cast<size_t>(dst) * N + n) = make_float4(v[0], v[1], v[2], v[3]);
     }
 }
 
@@ -822,7 +840,7 @@ static int launch_bf16(const void* act, const int32_t* offsets, const void* weig
 }
 
 static int launch_f32(const void* act, const int32_t* offsets, const void* weight, const void* bias, int64_t A, int K, int N,
-                      int E_local, int epi, void* out, hipStream_t stream)
+                      int E_local, int epi, void* out, hipStream_t stream, const RowMap& map = RowMap{})
 {
     const int64_t row_tiles = (A + 63) / 64 + E_local;
     const int64_t n_tiles = (N + 63) / 64;
@@ -833,11 +851,11 @@ static int launch_f32(const void* act, const int32_t* offsets, const void* weigh
     const float* b = static_cast<const float*>(bias);
     float* o = static_cast<float*>(out);
     if (epi == kEpiNone)
-        hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiNone>, grid, dim3(256), 0, stream, a, offsets, w, b, static_cast<int>(A), K, N, E_local, o);
+        hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiNone>, grid, dim3(256), 0, stream, a, offsets, w, b, static_cast<int>(A), K, N, E_local, o, map);
     else if (epi == kEpiGeluErf)
-        hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiGeluErf>, grid, dim3(256), 0, stream, a, offsets, w, b, static_cast<int>(A), K, N, E_local, o);
+        hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiGeluErf>, grid, dim3(256), 0, stream, a, offsets, w, b, static_cast<int>(A), K, N, E_local, o, map);
     else
-        hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiGeluTanh>, grid, dim3(256), 0, stream, a, offsets, w, b, static_cast<int>(A), K, N, E_local, o);
+        hipLaunchKernelGGL(grouped_gemm_f32_kernel<kEpiGeluTanh>, grid, dim3(256), 0, stream, a, offsets, w, b, static_cast<int>(A), K, N, E_local, o, map);
     return EXF_OK;
 }
 
@@ -934,11 +952,12 @@ extern "C" int moe_combine(const void* y_sorted, const int32_t* sorted_of_src, c
 extern "C" size_t moe_expert_ffn_fused_workspace_bytes(int64_t T, int k, int d, int f, int E_local, int dt)
 {
     (void)E_local;
-    if (T < 0 || k < 1 || k > EXF_MAX_TOPK || d < 1 || f < 1 || dt != EXF_BF16) return 0;
+    if (T < 0 || k < 1 || k > EXF_MAX_TOPK || d < 1 || f < 1 || (dt != EXF_BF16 && dt != EXF_F32)) return 0;
+    const size_t elem = dt == EXF_BF16 ? 2 : 4;
     const size_t A = static_cast<size_t>(T > 0 ? T : 1) * static_cast<size_t>(k);
-    size_t bytes = exf::align_up(A * static_cast<size_t>(f) * 2, 256);          // hidden activations [A,f]
-    if (k > 1) bytes += exf::align_up(A * static_cast<size_t>(d) * 2, 256);     // sorted expert outputs [A,d]
-    return bytes + exf::kSplitBytes;                                            // partial sums of K-sliced tail tiles
+    size_t bytes = exf::align_up(A * static_cast<size_t>(f) * elem, 256);        // hidden activations [A,f]
+    if (k > 1) bytes += exf::align_up(A * static_cast<size_t>(d) * elem, 256);   // sorted expert outputs [A,d]
+    return bytes + (dt == EXF_BF16 ? exf::kSplitBytes : 0);                      // bf16: partial sums of K-sliced tail tiles
 }
 
 extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src, const float* topk_w,
@@ -947,17 +966,18 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
                                     size_t workspace_bytes, void* stream)
 {
     using namespace exf;
-    if (dt != EXF_BF16) return fail(EXF_ERR_BAD_DTYPE, "moe_expert_ffn_fused: dt = %d (bf16 only)", dt);
+    if (dt != EXF_F32 && dt != EXF_BF16) return fail(EXF_ERR_BAD_DTYPE, "moe_expert_ffn_fused: dt = %d", dt);
     if (act != EXF_ACT_GELU_ERF && act != EXF_ACT_GELU_TANH) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: act = %d", act);
     if (k < 1 || k > EXF_MAX_TOPK) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: k = %d outside [1,%d]", k, EXF_MAX_TOPK);
     if (T < 0 || T * k >= (1ll << 31))
         return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: T = %lld, T*k outside [0,2^31)", static_cast<long long>(T));
     if (E_local < 1 || E_local > EXF_MAX_EXPERTS)
         return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: E_local = %d outside [1,%d]", E_local, EXF_MAX_EXPERTS);
-    if (d < 64 || d % 64 != 0 || f < 64 || f % 64 != 0)
-        return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: d = %d and f = %d must be positive multiples of 64", d, f);
+    const int gran = dt == EXF_BF16 ? 64 : 4;
+    if (d < gran || d % gran != 0 || f < gran || f % gran != 0)
+        return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: d = %d and f = %d must be positive multiples of %d", d, f, gran);
     const int64_t A = T * k;
-    {  // rows are addressed with 32-bit byte offsets
+    if (dt == EXF_BF16) {  // the bf16 kernel addresses rows with 32-bit byte offsets
         const unsigned long long widest = static_cast<unsigned long long>(d > f ? d : f);
         if (static_cast<unsigned long long>(A) * widest * 2ull >= (1ull << 32) ||
             static_cast<unsigned long long>(d) * static_cast<unsigned long long>(f) * 2ull >= (1ull << 32))
@@ -983,27 +1003,32 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
     if (workspace_bytes < need) return fail(EXF_ERR_WORKSPACE_TOO_SMALL, "moe_expert_ffn_fused: workspace %zu < %zu bytes", workspace_bytes, need);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int epi = act == EXF_ACT_GELU_ERF ? kEpiGeluErf : kEpiGeluTanh;
+    const size_t elem = dt == EXF_BF16 ? 2 : 4;
     unsigned char* hidden = static_cast<unsigned char*>(workspace);
     RowMap gather{};
     gather.a_row = src_of_sorted;
     gather.a_div = k;
-    unsigned char* y_sorted = hidden + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
-    void* partial = y_sorted + (k > 1 ? align_up(static_cast<size_t>(A) * static_cast<size_t>(d) * 2, 256) : 0);
-    int rc = launch_bf16<EXF_GEMM1_CFG>(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather,
-                                        kSplitFirstContraction ? partial : nullptr);
-    if (rc != EXF_OK) return rc;
+    RowMap scatter{};
     if (k == 1) {
-        RowMap scatter{};
         scatter.out_row = src_of_sorted;  // k = 1: the flat assignment index is the token
         scatter.out_scale = topk_w;
         scatter.unrouted = sorted_of_src;
         scatter.n_unrouted = static_cast<int>(T);
-        rc = launch_second_contraction(hidden, expert_offsets, w2, b2, A, f, d, E_local, out, s, scatter, partial);
-        if (rc != EXF_OK) return rc;
-        return check_launch("moe_expert_ffn_fused");
     }
-    rc = launch_second_contraction(hidden, expert_offsets, w2, b2, A, f, d, E_local, y_sorted, s, RowMap{}, partial);
+    unsigned char* y_sorted = hidden + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * elem, 256);
+    void* second_out = k == 1 ? out : static_cast<void*>(y_sorted);
+    int rc;
+    if (dt == EXF_F32) {
+        rc = launch_f32(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather);
+        if (rc == EXF_OK) rc = launch_f32(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, second_out, s, scatter);
+    } else {
+        void* partial = y_sorted + (k > 1 ? align_up(static_cast<size_t>(A) * static_cast<size_t>(d) * 2, 256) : 0);
+        rc = launch_bf16<EXF_GEMM1_CFG>(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather,
+                                        kSplitFirstContraction ? partial : nullptr);
+        if (rc == EXF_OK) rc = launch_second_contraction(hidden, expert_offsets, w2, b2, A, f, d, E_local, second_out, s, scatter, partial);
+    }
     if (rc != EXF_OK) return rc;
+    if (k == 1) return check_launch("moe_expert_ffn_fused");
     rc = check_launch("moe_expert_ffn_fused");
     if (rc != EXF_OK) return rc;
     return moe_combine(y_sorted, sorted_of_src, topk_w, T, d, k, dt, out, stream);

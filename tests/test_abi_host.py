@@ -64,7 +64,7 @@ def test_host_validation_rejects_before_launch():
         (lambda: lib.moe_expert_ffn(one, None, one, None, one, None, 4, 64, 256, 8, 0, B.EXF_F32, one, one, 1 << 20, None),
          B.EXF_ERR_NULL_PTR),
         # moe_expert_ffn_fused(x, src_of_sorted, sorted_of_src, topk_w, offsets, w1, b1, w2, b2, T, k, d, f, E_local, act, dt, out, ws, ws_bytes, stream)
-        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 1, 64, 256, 8, 0, B.EXF_F32, two, one, 1 << 20, None),
+        (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 1, 64, 256, 8, 0, 7, two, one, 1 << 20, None),
          B.EXF_ERR_BAD_DTYPE),
         (lambda: lib.moe_expert_ffn_fused(one, one, one, one, one, one, None, one, None, 4, 3, 64, 256, 8, 0, B.EXF_BF16, two, one, 1 << 20, None),
          B.EXF_ERR_BAD_SHAPE),
@@ -124,7 +124,8 @@ def test_workspace_sizes():
     assert lib.moe_expert_ffn_workspace_bytes(512, 64, 256, 8, B.EXF_F32) == 512 * 256 * 4
     assert lib.moe_expert_ffn_fused_workspace_bytes(8192, 1, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2 + split
     assert lib.moe_expert_ffn_fused_workspace_bytes(256, 2, 4096, 16384, 64, B.EXF_BF16) == 512 * (16384 + 4096) * 2 + split
-    assert lib.moe_expert_ffn_fused_workspace_bytes(256, 1, 64, 256, 8, B.EXF_F32) == 0  # bf16 only
+    assert lib.moe_expert_ffn_fused_workspace_bytes(512, 1, 64, 256, 8, B.EXF_F32) == 512 * 256 * 4
+    assert lib.moe_expert_ffn_fused_workspace_bytes(512, 1, 64, 256, 8, 7) == 0
     ws = lib.affinity_histogram_workspace_bytes(24, 1 << 20, 64)
     assert 0 < ws < 64 << 20  # partial histograms stay far below the 100 MB trace
     assert lib.placement_locality_workspace_bytes(24, 1 << 20) > 0

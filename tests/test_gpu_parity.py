@@ -283,17 +283,22 @@ def test_layer_small_end_to_end(oracle, cfg_id, dtype, T, d, f, E, k, renorm):
     assert_close_max(to_host(y)[: ref_d["kept"]], y_ref, OUT_RTOL[dtype], "y_sorted")
     out_ref = oracle.combine(y_ref, ref_d["sorted_of_src"], w_ref)
     assert_close_max(to_host(out), out_ref, OUT_RTOL[dtype], "layer output")
+    # the same layer without sorted copies: index-only dispatch and the fused FFN + combine
+    only = exf.moe_dispatch(xd, idx, E, gather=False)
+    fused = exf.moe_expert_ffn_fused(xd, only.src_of_sorted, only.sorted_of_src, w, only.expert_offsets, to_dev(w1, dtype),
+                                     to_dev(w2, dtype))
+    assert_close_max(to_host(fused), out_ref, OUT_RTOL[dtype], "fused layer output")
 
 
 # ----------------------------------------------------------------------------- fused FFN + combine
-def _fused_case(oracle, T, d, f, E, E_local, k, act, bias, seed, skew=False):
+def _fused_case(oracle, T, d, f, E, E_local, k, act, bias, seed, skew=False, dtype="bf16"):
     """moe_dispatch (index-only) -> moe_expert_ffn_fused against oracle gather -> FFN -> combine."""
     g = syn.rng(seed)
-    x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), "bf16")
-    w1 = syn.quantize(g.standard_normal((E_local, f, d), dtype=np.float32) * np.float32(0.05), "bf16")
-    w2 = syn.quantize(g.standard_normal((E_local, d, f), dtype=np.float32) * np.float32(0.05), "bf16")
-    b1 = syn.quantize(g.standard_normal((E_local, f), dtype=np.float32) * np.float32(0.1), "bf16") if bias else None
-    b2 = syn.quantize(g.standard_normal((E_local, d), dtype=np.float32) * np.float32(0.1), "bf16") if bias else None
+    x = syn.quantize(g.standard_normal((T, d), dtype=np.float32), dtype)
+    w1 = syn.quantize(g.standard_normal((E_local, f, d), dtype=np.float32) * np.float32(0.05), dtype)
+    w2 = syn.quantize(g.standard_normal((E_local, d, f), dtype=np.float32) * np.float32(0.05), dtype)
+    b1 = syn.quantize(g.standard_normal((E_local, f), dtype=np.float32) * np.float32(0.1), dtype) if bias else None
+    b2 = syn.quantize(g.standard_normal((E_local, d), dtype=np.float32) * np.float32(0.1), dtype) if bias else None
     if skew:  # a few heavy experts, several empty ones
         p = 1.0 / np.arange(1, E + 1) ** 1.5
         idx = np.stack([g.choice(E, size=k, replace=False, p=p / p.sum()) for _ in range(T)]).astype(np.int32)
@@ -304,13 +309,13 @@ def _fused_case(oracle, T, d, f, E, E_local, k, act, bias, seed, skew=False):
     if E_local < E:  # the first E_local of a shuffled list of experts live here; the others' tokens are dropped
         expert_map = np.full(E, -1, dtype=np.int32)
         expert_map[g.permutation(E)[:E_local]] = np.arange(E_local, dtype=np.int32)
-    xd = to_dev(x, "bf16")
+    xd = to_dev(x, dtype)
     disp = exf.moe_dispatch(xd, torch.from_numpy(idx).to(DEV), E, E_local=E_local,
                             expert_map=None if expert_map is None else torch.from_numpy(expert_map).to(DEV), gather=False)
-    out = torch.full((T, d), 7.0, dtype=torch.bfloat16, device=DEV)
+    out = torch.full((T, d), 7.0, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device=DEV)
     exf.moe_expert_ffn_fused(xd, disp.src_of_sorted, disp.sorted_of_src, torch.from_numpy(gate).to(DEV), disp.expert_offsets,
-                             to_dev(w1, "bf16"), to_dev(w2, "bf16"), None if b1 is None else to_dev(b1, "bf16"),
-                             None if b2 is None else to_dev(b2, "bf16"), act, out=out)
+                             to_dev(w1, dtype), to_dev(w2, dtype), None if b1 is None else to_dev(b1, dtype),
+                             None if b2 is None else to_dev(b2, dtype), act, out=out)
     ref_d = oracle.dispatch(idx, expert_map, E, E_local)
     expected_dispatch_compare(disp, ref_d, T * k)
     xs_ref = oracle.gather_rows(x, ref_d["src_of_sorted"], k)
@@ -319,7 +324,7 @@ def _fused_case(oracle, T, d, f, E, E_local, k, act, bias, seed, skew=False):
     got = to_host(out)
     unrouted = (ref_d["sorted_of_src"].reshape(T, k) < 0).all(axis=1)
     assert (got[unrouted] == 0).all(), "rows of tokens without a kept assignment must be zero"
-    assert_close_max(got, out_ref, OUT_RTOL["bf16"], "fused layer output")
+    assert_close_max(got, out_ref, OUT_RTOL[dtype], "fused layer output")
     return int(unrouted.sum())
 
 
@@ -337,6 +342,13 @@ def test_ffn_fused_top1_skewed_and_tiny(oracle):
     _fused_case(oracle, 3000, 256, 512, 32, 32, 1, 0, False, seed=710, skew=True)
     _fused_case(oracle, 1, 64, 64, 4, 4, 1, 0, False, seed=711)
     _fused_case(oracle, 67, 64, 64, 8, 1, 1, 0, True, seed=712)  # one resident expert, seven of eight tokens unrouted
+
+
+@pytest.mark.parametrize("k,E_local,bias", [(1, 6, True), (1, 2, False), (2, 6, False)])
+def test_ffn_fused_f32_parity(oracle, k, E_local, bias):
+    _say(f"ffn fused f32 k={k} E_local={E_local} bias={bias}")
+    _fused_case(oracle, 333, 36, 20, 6, E_local, k, 0, bias, seed=740 + k, dtype="f32")
+    _fused_case(oracle, 700, 64, 256, 6, E_local, k, 1, bias, seed=742 + k, dtype="f32")
 
 
 @pytest.mark.parametrize("E_local", [8, 3])
