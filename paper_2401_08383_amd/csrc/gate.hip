@@ -323,9 +323,9 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
 
     // The wavefront walks the batches (PF steps of 32 reduction elements) of its tiles as ONE
     // stream: the PF 16-byte loads of the next batch - of the next tile, if this one is finished -
-    // are issued before the MFMAs of the current batch.  The loads are unconditional (indices past
-    // the end are clamped; the operand is zeroed when it is used) and a scheduling barrier keeps
-    // them in front of the MFMAs, so PF loads per lane are in flight while the matrix cores work;
+    // are issued before the MFMAs of the current batch.  Inside a tile the loads are unconditional
+    // (indices past the end are clamped; the operand is zeroed when it is used) and a scheduling barrier
+    // keeps them in front of the MFMAs, so PF loads per lane are in flight while the matrix cores work;
     // left to itself the compiler sinks every load down to its MFMA.
     constexpr int PF = 4;
     typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_v;
@@ -338,25 +338,50 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
             b[u] = __builtin_nontemporal_load(reinterpret_cast<const i32x4_v*>(xrow + c * 8));  // x is streamed once
         }
     };
-    i32x4_v cur[PF], nxt[PF];
-    issue(tile, 0, cur);  // the first x loads travel while W_gate is copied
-
-    // W_gate -> LDS, eight 16-byte loads in flight per thread (a plain loop runs one at a time)
-    {
-        const uint4* wg16 = reinterpret_cast<const uint4*>(wg);
-        const int total = EP * chunks, valid = E * chunks;
-        constexpr int FB = 8;
-        for (int base = threadIdx.x; base < total; base += WAVES * 64 * FB) {
-            uint4 v[FB];
-#pragma unroll
-            for (int u = 0; u < FB; ++u) v[u] = wg16[min(base + u * WAVES * 64, valid - 1)];
-#pragma unroll
-            for (int u = 0; u < FB; ++u) {
-                const int i = base + u * WAVES * 64;
-                const int e = i / chunks, c = i - e * chunks;
-                if (i < total) wlds[e * chunks + (c ^ (e & swz))] = i < valid ? v[u] : uint4{0u, 0u, 0u, 0u};
-            }
+    // DEPTH batches per wavefront are in flight.  Two are enough: with one token tile per wavefront
+    // (the launch shape up to 256 * 16 tiles) the batch loop ends when the last x bytes arrive from
+    // HBM, however early they were asked for, and more batches in flight only delayed the weight copy.
+    constexpr int DEPTH = 2;
+    i32x4_v ring[DEPTH][PF];
+    int64_t issue_tile = tile;  // issue cursor: the batch the next loads belong to
+    int issue_s0 = 0;
+    auto issue_next = [&](i32x4_v(&b)[PF]) {
+        if (issue_tile >= n_tiles) return;  // past this wavefront's last tile: nothing will read the batch
+        issue(issue_tile, issue_s0, b);
+        issue_s0 += PF;
+        if (issue_s0 >= steps) {
+            issue_s0 = 0;
+            issue_tile += stride;
         }
+    };
+    // W_gate -> LDS, FB 16-byte loads in flight per thread (a plain loop runs one at a time).  The
+    // loads of the first round are issued first and the first x batches right behind them, so both
+    // travel at once and the weights, which every wavefront waits for, arrive first.
+    const uint4* wg16 = reinterpret_cast<const uint4*>(wg);
+    const int total = EP * chunks, valid = E * chunks;
+    constexpr int FB = 8;
+    auto fill_store = [&](int i, const uint4& v) {
+        if (i >= total) return;
+        const int e = i / chunks, c = i - e * chunks;
+        wlds[e * chunks + (c ^ (e & swz))] = i < valid ? v : uint4{0u, 0u, 0u, 0u};
+    };
+    {
+        uint4 v[FB];
+#pragma unroll
+        for (int u = 0; u < FB; ++u) v[u] = wg16[min(static_cast<int>(threadIdx.x) + u * WAVES * 64, valid - 1)];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < DEPTH - 1; ++q) issue_next(ring[q]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < FB; ++u) fill_store(threadIdx.x + u * WAVES * 64, v[u]);
+    }
+    for (int base = threadIdx.x + WAVES * 64 * FB; base < total; base += WAVES * 64 * FB) {
+        uint4 v[FB];
+#pragma unroll
+        for (int u = 0; u < FB; ++u) v[u] = wg16[min(base + u * WAVES * 64, valid - 1)];
+#pragma unroll
+        for (int u = 0; u < FB; ++u) fill_store(base + u * WAVES * 64, v[u]);
     }
     __syncthreads();
     if (!has_work) return;
@@ -364,11 +389,16 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
     f32x4_t acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    while (true) {
+    bool done = false;
+    while (!done) {
+#pragma unroll
+      for (int q = 0; q < DEPTH; ++q) {
+        if (done) break;
+        i32x4_v(&cur)[PF] = ring[q];
         const bool last_batch = s0 + PF >= steps;
         const int64_t tile_next = last_batch ? tile + stride : tile;
         const int s0_next = last_batch ? 0 : s0 + PF;
-        issue(tile_next, s0_next, nxt);
+        issue_next(ring[(q + DEPTH - 1) % DEPTH]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
@@ -440,12 +470,11 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_lds_kernel(const bf16_t*
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        if (tile_next >= n_tiles) break;
+        if (tile_next >= n_tiles) done = true;
         }  // last batch of the tile
-#pragma unroll
-        for (int u = 0; u < PF; ++u) cur[u] = nxt[u];
         tile = tile_next;
         s0 = s0_next;
+      }
     }
 }
 
