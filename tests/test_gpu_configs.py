@@ -41,7 +41,7 @@ def _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=None, expert_map=
     if forced_idx is None:
         logits64 = oracle.gate_logits(x, wg)
         n_amb = check_routing_against_fp64(idx, logits64, k, GATE_TOL[dtype])
-        assert n_amb <= max(3, cfg.T // 500)
+        assert n_amb <= max(3, cfg.T * k // 250)
         p = oracle.softmax(logits64)
         w_ref = np.take_along_axis(p, idx.astype(np.int64), axis=1)
         if cfg.renormalize and k > 1:

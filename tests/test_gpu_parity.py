@@ -56,7 +56,7 @@ def test_gate_topk_parity(oracle, dtype, T, d, E, k, renorm):
     assert_gate_close(w, w_k, 1e-6, "weights vs own logits")
     # end to end against fp64 logits
     n_amb = check_routing_against_fp64(idx, logits64, k, GATE_TOL[dtype])
-    assert n_amb <= max(3, T // 500)
+    assert n_amb <= max(3, T * k // 250)  # near-ties are rare: the tolerance above must not carry the comparison
     _, w64 = oracle.topk(logits64, k, renorm)
     clear = (idx == oracle.topk(logits64, k, renorm)[0]).all(axis=1)
     assert_gate_close(w[clear], w64[clear], GATE_TOL[dtype], "weights")
@@ -282,12 +282,13 @@ def test_layer_small_end_to_end(oracle, cfg_id, dtype, T, d, f, E, k, renorm):
     y_ref = oracle.expert_ffn(xs_ref, ref_d["offsets"], w1, None, w2, None, 0)
     assert_close_max(to_host(y)[: ref_d["kept"]], y_ref, OUT_RTOL[dtype], "y_sorted")
     out_ref = oracle.combine(y_ref, ref_d["sorted_of_src"], w_ref)
-    assert_close_max(to_host(out), out_ref, OUT_RTOL[dtype], "layer output")
+    mag = oracle.combine(np.abs(y_ref), ref_d["sorted_of_src"], w_ref)  # what the summands' roundings are relative to
+    assert_close_max(to_host(out), out_ref, OUT_RTOL[dtype], "layer output", mag=mag)
     # the same layer without sorted copies: index-only dispatch and the fused FFN + combine
     only = exf.moe_dispatch(xd, idx, E, gather=False)
     fused = exf.moe_expert_ffn_fused(xd, only.src_of_sorted, only.sorted_of_src, w, only.expert_offsets, to_dev(w1, dtype),
                                      to_dev(w2, dtype))
-    assert_close_max(to_host(fused), out_ref, OUT_RTOL[dtype], "fused layer output")
+    assert_close_max(to_host(fused), out_ref, OUT_RTOL[dtype], "fused layer output", mag=mag)
 
 
 # ----------------------------------------------------------------------------- fused FFN + combine
@@ -324,7 +325,8 @@ def _fused_case(oracle, T, d, f, E, E_local, k, act, bias, seed, skew=False, dty
     got = to_host(out)
     unrouted = (ref_d["sorted_of_src"].reshape(T, k) < 0).all(axis=1)
     assert (got[unrouted] == 0).all(), "rows of tokens without a kept assignment must be zero"
-    assert_close_max(got, out_ref, OUT_RTOL[dtype], "fused layer output")
+    mag = oracle.combine(np.abs(y_ref), ref_d["sorted_of_src"], gate)  # what the summands' roundings are relative to
+    assert_close_max(got, out_ref, OUT_RTOL[dtype], "fused layer output", mag=mag)
     return int(unrouted.sum())
 
 
