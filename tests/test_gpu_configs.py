@@ -7,7 +7,7 @@ import torch
 
 import paper_2401_08383_amd as exf
 import synth_inputs as syn
-from helpers import (DEV, GATE_TOL, OUT_RTOL, assert_close_max, assert_gate_close, check_routing_against_fp64, to_dev, to_host)
+from helpers import (DEV, GATE_TOL, OUT_RTOL, assert_close_max, dev_i32, oracle_routing, to_dev, to_host)
 from paper_2401_08383_amd.pipeline import AffinityRun, MoELayerRun
 
 pytestmark = pytest.mark.gpu
@@ -30,62 +30,73 @@ def _sample_rows(offsets, per_expert, seed):
     return np.array(rows, dtype=np.int64)
 
 
-def _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=None, expert_map=None, rows_per_expert=2, seed=0,
-                 weights_on_host=True):
-    """Compares one executed MoELayerRun with the oracle.  w1/w2: host fp32 arrays, or device
-    tensors from which only the sampled experts are copied back."""
-    dtype = cfg.dtype
+def _ffn_rows_ref(oracle, xs_ref, offsets, w1, w2, rows, d):
+    """Oracle FFN of the sorted rows `rows`.  w1/w2: host fp32 arrays, or device tensors from which only
+    the experts that own a row are copied back (one at a time)."""
+    if isinstance(w1, np.ndarray):
+        return oracle.expert_ffn_rows(xs_ref, offsets, w1, None, w2, None, 0, rows)
+    y_ref = np.zeros((len(rows), d))
+    owner = np.searchsorted(offsets, rows, side="right") - 1
+    for e in np.unique(owner):
+        sel = np.nonzero(owner == e)[0]
+        w1e = w1[e].float().cpu().numpy()[None]
+        w2e = w2[e].float().cpu().numpy()[None]
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        y_ref[sel] = oracle.expert_ffn_rows(xs_ref[lo:hi], np.array([0, hi - lo], dtype=np.int32), w1e, None, w2e, None, 0, rows[sel] - lo)
+    return y_ref
+
+
+def _check_chain(oracle, cfg, layer, x, w1, w2, ref, w_ref, rows, seed):
+    """Expert FFN and layer output of one executed MoELayerRun against the oracle chain gather -> FFN ->
+    combine, which is fed by the seeded inputs and the oracle's own routing, dispatch and gate weights:
+    sampled sorted rows, then every sorted row of the tokens that own them, then those tokens' outputs."""
+    dtype, k, T = cfg.dtype, cfg.k, cfg.T
+    kept = ref["kept"]
+    xs_ref = x[ref["src_of_sorted"] // k]
+    np.testing.assert_array_equal(to_host(layer.x_sorted)[:kept], xs_ref)  # a pure copy: bit-exact
+    inv = ref["sorted_of_src"].reshape(T, k)
+    toks = np.unique(ref["src_of_sorted"][rows] // k)
+    pos = inv[toks]
+    rows_all = np.unique(np.concatenate([rows, pos[pos >= 0]]))
+    y_ref = _ffn_rows_ref(oracle, xs_ref, ref["offsets"], w1, w2, rows_all, cfg.d)
+    y = to_host(layer.y_sorted)
+    assert np.abs(y[rows_all] - y_ref).max() <= OUT_RTOL[dtype] * np.abs(y_ref).max(), "expert FFN rows"
+    # the sampled tokens as a layer of their own: their sorted rows renumbered into y_ref
+    inv_small = np.where(pos >= 0, np.searchsorted(rows_all, np.maximum(pos, 0)), -1).astype(np.int32)
+    w_small = np.ascontiguousarray(w_ref[toks], dtype=np.float64)
+    out_ref = oracle.combine(y_ref, inv_small, w_small)
+    mag = oracle.combine(np.abs(y_ref), inv_small, np.abs(w_small))
+    assert_close_max(to_host(layer.out)[toks], out_ref, OUT_RTOL[dtype], "layer output of sampled tokens", mag=mag)
+    # the combine alone at the full size, on seeded expert outputs: one rounding to storage after an
+    # fp32 sum of k terms, relative to the summands
+    g = syn.rng(seed + 1000)
+    y_syn = syn.quantize(g.standard_normal((T * k, cfg.d), dtype=np.float32), dtype)
+    w32 = np.ascontiguousarray(w_ref, dtype=np.float32)
+    got = to_host(exf.moe_combine(to_dev(y_syn, dtype), dev_i32(ref["sorted_of_src"]), torch.from_numpy(w32).to(DEV)))
+    full_ref = oracle.combine(y_syn, ref["sorted_of_src"], w32)
+    full_mag = oracle.combine(np.abs(y_syn), ref["sorted_of_src"], np.abs(w32))
+    eps = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -22
+    assert (np.abs(got - full_ref) <= eps * full_mag + 1e-30).all(), "combine"
+
+
+def _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=None, combine_w=None, expert_map=None, rows_per_expert=2, seed=0):
+    """Compares one executed MoELayerRun with the oracle.  Routing: the oracle's own (checked to be what
+    the GPU decided), or `forced_idx` with the combine weights `combine_w` the caller gave the run.
+    w1/w2: host fp32 arrays or device tensors."""
     k, E, E_local = cfg.k, cfg.E, cfg.E_local
-    idx = layer.topk_idx.cpu().numpy() if forced_idx is None else forced_idx
-    w = layer.topk_w.cpu().numpy()
     if forced_idx is None:
-        logits64 = oracle.gate_logits(x, wg)
-        n_amb = check_routing_against_fp64(idx, logits64, k, GATE_TOL[dtype])
-        assert n_amb <= max(3, cfg.T * k // 250)
-        p = oracle.softmax(logits64)
-        w_ref = np.take_along_axis(p, idx.astype(np.int64), axis=1)
-        if cfg.renormalize and k > 1:
-            w_ref = w_ref / w_ref.sum(axis=1, keepdims=True)
-        assert_gate_close(w, w_ref, GATE_TOL[dtype], "gate weights")
+        idx, w_ref, _ = oracle_routing(oracle, x, wg, k, cfg.renormalize, layer.topk_idx.cpu().numpy(), layer.topk_w.cpu().numpy(),
+                                       GATE_TOL[cfg.dtype])
+    else:
+        idx, w_ref = forced_idx, combine_w
     ref = oracle.dispatch(idx, expert_map, E, E_local)
     kept = ref["kept"]
     np.testing.assert_array_equal(layer.expert_counts.cpu().numpy(), ref["counts"])
     np.testing.assert_array_equal(layer.expert_offsets.cpu().numpy(), ref["offsets"])
     np.testing.assert_array_equal(layer.src_of_sorted.cpu().numpy()[:kept], ref["src_of_sorted"])
     np.testing.assert_array_equal(layer.sorted_of_src.cpu().numpy(), ref["sorted_of_src"])
-    xs = to_host(layer.x_sorted)[:kept]
-    np.testing.assert_array_equal(xs, x[ref["src_of_sorted"] // k])
-    # expert FFN on sampled sorted rows
-    rows = _sample_rows(ref["offsets"], rows_per_expert, seed)
-    y = to_host(layer.y_sorted)
-    if weights_on_host:
-        y_ref = oracle.expert_ffn_rows(xs, ref["offsets"], w1, None, w2, None, 0, rows)
-    else:  # copy back only the experts that own sampled rows (one at a time)
-        y_ref = np.zeros((len(rows), cfg.d))
-        owner = np.searchsorted(ref["offsets"], rows, side="right") - 1
-        for e in np.unique(owner):
-            sel = np.nonzero(owner == e)[0]
-            w1e = w1[e].float().cpu().numpy()[None]
-            w2e = w2[e].float().cpu().numpy()[None]
-            lo = int(ref["offsets"][e])
-            off1 = np.array([0, int(ref["offsets"][e + 1]) - lo], dtype=np.int32)
-            y_ref[sel] = oracle.expert_ffn_rows(xs[lo:int(ref["offsets"][e + 1])], off1, w1e, None, w2e, None, 0, rows[sel] - lo)
-    scale = np.abs(y_ref).max()
-    assert np.abs(y[rows] - y_ref).max() <= OUT_RTOL[dtype] * scale, "expert FFN rows"
-    # combine on the tokens that own the sampled rows (from the GPU's own y_sorted, widened)
-    toks = np.unique(ref["src_of_sorted"][rows] // k)
-    out = to_host(layer.out)
-    inv = ref["sorted_of_src"].reshape(cfg.T, k)
-    out_ref = np.zeros((len(toks), cfg.d))
-    mag = np.zeros((len(toks), cfg.d))
-    for j in range(k):
-        pos = inv[toks, j]
-        ok = pos >= 0
-        term = w[toks[ok], j][:, None].astype(np.float64) * y[pos[ok]].astype(np.float64)
-        out_ref[ok] += term
-        mag[ok] += np.abs(term)
-    eps = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -22  # one rounding to storage after an fp32 sum of k terms
-    assert (np.abs(out[toks] - out_ref) <= eps * mag + 1e-30).all(), "combine"
+    _check_chain(oracle, cfg, layer, x, w1, w2, ref, w_ref, _sample_rows(ref["offsets"], rows_per_expert, seed), seed)
+    ref["w_ref"] = w_ref
     return ref
 
 
@@ -116,7 +127,7 @@ def _check_fused(oracle, cfg, plain, x, w1, w2, ref, rows_per_expert, seed, expe
         return
     rows = _sample_rows(ref["offsets"], rows_per_expert, seed)
     toks = ref["src_of_sorted"][rows]
-    w = fused.topk_w.cpu().numpy()
+    w = ref["w_ref"]
     xs = x[ref["src_of_sorted"]]
     y_ref = oracle.expert_ffn_rows(xs, ref["offsets"], w1, None, w2, None, 0, rows)
     out_ref = w[toks, 0][:, None].astype(np.float64) * y_ref
@@ -171,14 +182,10 @@ def test_config3_xl_skewed(oracle):
     trace, _ = syn.config_trace(cfg)
     forced = trace[0].reshape(-1, 1).copy()
     xd = to_dev(x, "bf16")
-    # the gate is checked on x as it stands; its probabilities at the forced experts weight the combine
-    idx_g, w_g, logits = exf.moe_gate_topk(xd, to_dev(wg, "bf16"), 1, False, want_logits=True)
-    logits64 = oracle.gate_logits(x, wg)
-    check_routing_against_fp64(idx_g.cpu().numpy(), logits64, 1, GATE_TOL["bf16"])
-    lg = logits.cpu().numpy().astype(np.float64)
-    pg = np.exp(lg - lg.max(axis=1, keepdims=True))
-    pg /= pg.sum(axis=1, keepdims=True)
-    forced_w = np.take_along_axis(pg, forced.astype(np.int64), axis=1).astype(np.float32)
+    # the gate is checked on x as it stands; the oracle's probabilities of the forced experts weight the combine
+    idx_g, w_g, _ = exf.moe_gate_topk(xd, to_dev(wg, "bf16"), 1, False)
+    _, _, logits64 = oracle_routing(oracle, x, wg, 1, False, idx_g.cpu().numpy(), w_g.cpu().numpy(), GATE_TOL["bf16"])
+    forced_w = np.take_along_axis(oracle.softmax(logits64), forced.astype(np.int64), axis=1).astype(np.float32)
     layer = MoELayerRun(xd, to_dev(wg, "bf16"), to_dev(w1, "bf16"), to_dev(w2, "bf16"), 1, False,
                         topk_idx=torch.from_numpy(forced).to(DEV))
     layer.topk_w.copy_(torch.from_numpy(forced_w))
@@ -186,7 +193,7 @@ def test_config3_xl_skewed(oracle):
     layer.ffn()
     layer.combine()
     _say("  oracle on sampled rows")
-    ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=forced, rows_per_expert=1, seed=31)
+    ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=forced, combine_w=forced_w, rows_per_expert=1, seed=31)
     assert ref["counts"].max() > 10 * max(1, ref["counts"].min())  # skewed loads
     _check_fused(oracle, cfg, layer, x, w1, w2, ref, rows_per_expert=1, seed=32)
     _check_affinity(oracle, cfg, trace, syn.balanced_random_placement(cfg.trace_L, cfg.trace_E, cfg.G, syn.seed_for(3, 5)))
@@ -202,15 +209,12 @@ def test_config4_one_gpu_share(oracle):
     layer = MoELayerRun(xd, wgd, to_dev(w1, "bf16"), to_dev(w2, "bf16"), 1, False, expert_map=torch.from_numpy(expert_map).to(DEV),
                         topk_idx=torch.from_numpy(idx).to(DEV))
     layer.gate()  # the shared gate over all 64 experts on the tokens this GPU holds
-    logits64 = oracle.gate_logits(x, wg)
-    idx_gate = layer.topk_idx.cpu().numpy()
-    check_routing_against_fp64(idx_gate, logits64, 1, GATE_TOL["bf16"])
-    w_ref = np.take_along_axis(oracle.softmax(logits64), idx_gate.astype(np.int64), axis=1)
-    assert_gate_close(layer.topk_w.cpu().numpy(), w_ref, GATE_TOL["bf16"], "gate weights")
+    _, w_gate, _ = oracle_routing(oracle, x, wg, 1, False, layer.topk_idx.cpu().numpy(), layer.topk_w.cpu().numpy(), GATE_TOL["bf16"])
     layer.dispatch()  # post-exchange share: every token is routed to one of the 8 resident experts
     layer.ffn()
     layer.combine()
-    ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=idx, expert_map=expert_map, rows_per_expert=3, seed=41)
+    ref = _check_layer(oracle, cfg, layer, x, wg, w1, w2, forced_idx=idx, combine_w=w_gate, expert_map=expert_map, rows_per_expert=3,
+                       seed=41)
     assert ref["kept"] == cfg.T
     _check_fused(oracle, cfg, layer, x, w1, w2, ref, rows_per_expert=3, seed=43)
     # the same layer fed with the gate's own routing: 7 of 8 tokens belong to other GPUs and are dropped here
@@ -241,50 +245,20 @@ def test_config5_decode_top2(oracle):
         r[4].step()
     torch.cuda.synchronize()
     for l, (x, wg, w1, w2, layer) in enumerate(runs):
-        _say(f"  layer {l}: oracle on sampled rows")
+        _say(f"  layer {l}: oracle on sampled tokens")
         w = layer.topk_w.cpu().numpy()
         np.testing.assert_allclose(w.sum(axis=1), 1.0, rtol=1e-6)  # renormalised top-2 gates
-        g = syn.rng(50 + l)
-        ref = oracle.dispatch(layer.topk_idx.cpu().numpy(), None, cfg.E, cfg.E_local)
-        # sampled rows from two random non-empty experts only (each needs 2 x 256 MB of weights on the host)
-        nonempty = np.nonzero(ref["counts"] > 0)[0]
-        keep = set(g.choice(nonempty, size=2, replace=False).tolist())
-        offs = ref["offsets"]
-        rows = np.array([int(offs[e]) for e in sorted(keep)] + [int(offs[e + 1]) - 1 for e in sorted(keep)], dtype=np.int64)
-        _check_layer_rows(oracle, cfg, layer, x, wg, w1, w2, rows)
+        idx, w_ref, _ = oracle_routing(oracle, x, wg, cfg.k, cfg.renormalize, layer.topk_idx.cpu().numpy(), w, GATE_TOL["bf16"])
+        ref = oracle.dispatch(idx, None, cfg.E, cfg.E_local)
+        assert ref["kept"] == cfg.T * cfg.k
+        np.testing.assert_array_equal(layer.expert_offsets.cpu().numpy(), ref["offsets"])
+        np.testing.assert_array_equal(layer.src_of_sorted.cpu().numpy(), ref["src_of_sorted"])
+        np.testing.assert_array_equal(layer.sorted_of_src.cpu().numpy(), ref["sorted_of_src"])
+        # two random tokens: their four sorted rows lie in at most four experts (each needs 2 x 256 MB of
+        # weights on the host)
+        toks = syn.rng(50 + l).choice(cfg.T, size=2, replace=False)
+        rows = np.sort(ref["sorted_of_src"].reshape(cfg.T, cfg.k)[toks].ravel()).astype(np.int64)
+        _check_chain(oracle, cfg, layer, x, w1, w2, ref, w_ref, rows, 50 + l)
         if l == 0:
+            ref["w_ref"] = w_ref
             _check_fused(oracle, cfg, layer, x, w1, w2, ref, rows_per_expert=0, seed=0)
-
-
-def _check_layer_rows(oracle, cfg, layer, x, wg, w1_dev, w2_dev, rows):
-    """Like _check_layer, for device-resident weights and an explicit list of sorted rows."""
-    k, E = cfg.k, cfg.E
-    idx = layer.topk_idx.cpu().numpy()
-    w = layer.topk_w.cpu().numpy()
-    logits64 = oracle.gate_logits(x, wg)
-    check_routing_against_fp64(idx, logits64, k, GATE_TOL["bf16"])
-    p = oracle.softmax(logits64)
-    w_ref = np.take_along_axis(p, idx.astype(np.int64), axis=1)
-    w_ref = w_ref / w_ref.sum(axis=1, keepdims=True)
-    assert_gate_close(w, w_ref, GATE_TOL["bf16"], "gate weights")
-    ref = oracle.dispatch(idx, None, E, cfg.E_local)
-    kept = ref["kept"]
-    assert kept == cfg.T * k
-    np.testing.assert_array_equal(layer.expert_offsets.cpu().numpy(), ref["offsets"])
-    np.testing.assert_array_equal(layer.src_of_sorted.cpu().numpy(), ref["src_of_sorted"])
-    np.testing.assert_array_equal(layer.sorted_of_src.cpu().numpy(), ref["sorted_of_src"])
-    xs = to_host(layer.x_sorted)
-    np.testing.assert_array_equal(xs, x[ref["src_of_sorted"] // k])
-    y = to_host(layer.y_sorted)
-    owner = np.searchsorted(ref["offsets"], rows, side="right") - 1
-    for e in np.unique(owner):
-        sel = rows[owner == e]
-        lo, hi = int(ref["offsets"][e]), int(ref["offsets"][e + 1])
-        w1e = w1_dev[e].float().cpu().numpy()[None]
-        w2e = w2_dev[e].float().cpu().numpy()[None]
-        y_ref = oracle.expert_ffn_rows(xs[lo:hi], np.array([0, hi - lo], dtype=np.int32), w1e, None, w2e, None, 0, sel - lo)
-        assert np.abs(y[sel] - y_ref).max() <= OUT_RTOL["bf16"] * np.abs(y_ref).max(), f"expert {e} FFN rows"
-    # combine: every token, from the GPU's own y_sorted
-    out_ref = oracle.combine(y, ref["sorted_of_src"], w)
-    mag = oracle.combine(np.abs(y), ref["sorted_of_src"], np.abs(w))
-    assert (np.abs(to_host(layer.out) - out_ref) <= 2.0 ** -8 * mag + 1e-30).all(), "combine"
