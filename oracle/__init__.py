@@ -31,10 +31,17 @@ def build(force: bool = False) -> str:
 
 
 def _load():
+    """The compiled oracle.  MOE_ORACLE_LIBRARY names another build of it to load instead: the
+    mutation test compiles copies of moe_oracle.c with one planted mistake each and runs the pins
+    against them."""
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        other = os.environ.get("MOE_ORACLE_LIBRARY")
+        if other:
+            _lib = ctypes.CDLL(other)
+        else:
+            build()
+            _lib = ctypes.CDLL(_LIB)
     return _lib
 
 
