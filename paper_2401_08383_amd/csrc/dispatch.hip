@@ -52,6 +52,18 @@ __device__ __forceinline__ void load_local_experts(const int32_t* __restrict__ t
     }
 }
 
+// Lanes of the wavefront that hold the same local expert as this lane (meaningful where e >= 0): the
+// ids are compared bit by bit, log2(E_local) ballots instead of one ballot per expert.
+__device__ __forceinline__ unsigned long long same_expert_lanes(int e, int E_local)
+{
+    unsigned long long m = __ballot(e >= 0);
+    for (int bit = 1; bit < E_local; bit <<= 1) {
+        const unsigned long long b = __ballot((e & bit) != 0);
+        m &= (e & bit) != 0 ? b : ~b;
+    }
+    return m;
+}
+
 __global__ __launch_bounds__(kDispThreads) void dispatch_count_kernel(const int32_t* __restrict__ topk_idx,
                                                                        const int32_t* __restrict__ expert_map, int64_t A,
                                                                        int E, int E_local,
@@ -108,6 +120,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     int e_mine[kDispRounds];
     const int64_t base = static_cast<int64_t>(blockIdx.x) * kDispChunk;
     load_local_experts(topk_idx, expert_map, base, A, E, E_local, e_mine);  // in flight during the scan
+    for (int i = threadIdx.x; i < kDispRounds * kDispWaves * EXF_MAX_EXPERTS; i += kDispThreads) (&wave_cnt[0][0][0])[i] = 0;
     if constexpr (FUSED_SCAN) {
         // column sums of the count matrix [chunks][E_local]: over all chunks (expert totals) and over
         // the chunks before this one; all threads load side by side, four entries each per pass
@@ -162,12 +175,9 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
 #pragma unroll
     for (int round = 0; round < kDispRounds; ++round) {
         const int e = e_mine[round];
-        rank[round] = 0;
-        for (int q = 0; q < E_local; ++q) {
-            const unsigned long long m = __ballot(e == q);
-            if (e == q) rank[round] = __popcll(m & below);
-            if (lane == q) wave_cnt[round][wave][q] = __popcll(m);
-        }
+        const unsigned long long m = same_expert_lanes(e, E_local);
+        rank[round] = __popcll(m & below);
+        if (e >= 0 && (m & below) == 0ull) wave_cnt[round][wave][e] = __popcll(m);  // the lowest lane of every expert present
     }
     __syncthreads();  // counts of all rounds and wavefronts, and the cursors, are in LDS
 #pragma unroll
@@ -278,11 +288,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_place_kernel(
         const bool in_slice = lane >= lane_s && lane < lane_s + MOVE;
         if (!in_slice) e = -1;
         const unsigned long long below = (1ull << lane) - 1ull;
-        int rank = 0;
-        for (int q = 0; q < E_local; ++q) {
-            const unsigned long long m = __ballot(e == q);
-            if (e == q) rank = __popcll(m & below);
-        }
+        const int rank = __popcll(same_expert_lanes(e, E_local) & below);
         if (in_slice) {
             const int64_t a = base + first + (lane - lane_s);
             int pos = -1;
