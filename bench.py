@@ -38,7 +38,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch summed over the call's three launches), each
 # scaled by what the same counter reads for the 1 GiB copy probe (FETCH x2.000, WRITE x1.000):
 # (73565.0 + 116043.8 + 3875.2) KiB x 2 + (65536 + 23692 + 744) KiB.  See profiles/bench_config2_hbm_traffic.txt.
-FFN_TRAFFIC_BYTES = int((73565.9 + 116043.0 + 3877.2) * 2 * 1024 + (65536 + 23692 + 744) * 1024)
+FFN_TRAFFIC_BYTES = int((73565.9 + 116043.3 + 3877.2) * 2 * 1024 + (65536 + 23692 + 744) * 1024)
 
 
 def _events(n):
