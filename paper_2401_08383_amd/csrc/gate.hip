@@ -220,6 +220,7 @@ __global__ __launch_bounds__(NW * 64) void gate_bf16_kernel(const bf16_t* __rest
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     const bf16x8_t zero8 = {};
+#pragma unroll 4  // the loads of four steps go out together: a short batch is a chain of memory round trips otherwise
     for (int s = s_begin; s < s_end; ++s) {
         const int c = s * 32 + kq;
         const bool ok = c < d;  // d % 8 == 0: a group of 8 is entirely inside or outside
@@ -272,6 +273,16 @@ __global__ __launch_bounds__(NW * 64) void gate_bf16_kernel(const bf16_t* __rest
         const int n = static_cast<int>(tokens_here) * E;
         float* dst = logits_out + t0 * E;
         for (int i = threadIdx.x; i < n; i += NW * 64) dst[i] = part[0][i % E][i / E];
+    }
+    if (E > 16) {  // many experts: a wavefront per token, lane e holds expert e
+        for (int tt = wave; tt < TB; tt += NW) {
+            const int64_t t = t0 + tt;
+            if (t < T) {  // (the same for every lane of the wavefront)
+                const Route r = route_wave(part[0][min(lane, E - 1)][tt], E, k, renormalize);
+                if (lane == 0) store_route(r, t, k, topk_idx, topk_w);
+            }
+        }
+        return;
     }
     for (int tt = threadIdx.x; tt < TB; tt += NW * 64) {
         const int64_t t = t0 + tt;
