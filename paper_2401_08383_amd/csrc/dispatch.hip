@@ -8,7 +8,8 @@
 //                separate one-workgroup scan kernel serves longer inputs.
 //   3. place   : every workgroup takes a slice of 32 or 64 assignments of one chunk, ranks it —
 //                assignments of the chunk in front of the slice recounted from the ids, rank
-//                inside the slice from a ballot per expert (lanes with a lower id and the same
+//                inside the slice from the lanes that hold the same expert (found with one ballot per
+//                bit of the id), of which those with a lower lane id count (lanes with a lower id and the same
 //                expert) — which keeps equal experts in ascending assignment order (stable, hence
 //                a unique permutation), writes both index maps and copies the slice's rows
 //                x_sorted[position] = x[assignment / k] as 16-byte vector copies.
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
 // consecutive assignments - a slice of one 1024-assignment chunk of the count matrix.  It
 //   - derives the chunk's start positions like dispatch_scatter_kernel (column sums, or the scanned
 //     matrix), adds the assignments of its chunk that precede its slice (recounted from the ids,
-//     LDS atomics), and ranks its own slice with per-expert ballots: stable, same permutation;
+//     LDS atomics), and ranks its own slice by the lanes below that hold the same expert: stable, same permutation;
 //   - writes both index maps for its slice;
 //   - copies its rows x[a / k] -> x_sorted[position]: every wavefront takes MOVE/4 rows and streams
 //     them as a flat sequence of 16-byte chunks (`vec_per_row` = row bytes / 16) with non-temporal
