@@ -8,9 +8,9 @@
 //                separate one-workgroup scan kernel serves longer inputs.
 //   3. place   : every workgroup takes a slice of 32 or 64 assignments of one chunk, ranks it —
 //                assignments of the chunk in front of the slice recounted from the ids, rank
-//                inside the slice from the lanes that hold the same expert (found with one ballot per
-//                bit of the id), of which those with a lower lane id count (lanes with a lower id and the same
-//                expert) — which keeps equal experts in ascending assignment order (stable, hence
+//                inside the slice = number of lower lanes that hold the same expert (those lanes
+//                are found with one ballot per bit of the id) — which keeps equal experts in
+//                ascending assignment order (stable, hence
 //                a unique permutation), writes both index maps and copies the slice's rows
 //                x_sorted[position] = x[assignment / k] as 16-byte vector copies.
 //                (Without rows to move, dispatch_scatter_kernel ranks whole chunks instead.)
