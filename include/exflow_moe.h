@@ -268,6 +268,33 @@ int routing_transfers(const int32_t* trace, const int32_t* placement, const int3
                       int64_t N, int E, int G, int64_t* local_per_pair, int64_t* away_per_layer,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * exf_comm_volume — the forward communication volume model of the table "Comparison with
+ * state-of-the-art GPT MoE optimization methods" (host helper, pure arithmetic).
+ *   G   GPUs of the expert-parallel group          N  tokens per GPU
+ *   L   MoE layers                                 p  ratio of tokens that take part in an Alltoall
+ *   p_star  the same ratio under context-coherent expert parallelism with an affinity placement
+ * volumes_host (HOST, out, 4 doubles, in tokens):
+ *   [0] vanilla expert parallelism, top-1 gating   2 * G * N * L * p       (out and back per layer)
+ *   [1] vanilla, top-2 gating                      4 * G * N * L * p
+ *   [2] context-coherent, top-1                    G * N * (L * p_star + G)  (one Alltoall per layer
+ *                                                   plus the AllGather of the contexts: the + G term)
+ *   [3] context-coherent, top-2                    G * N * (2 * L * p_star + G)
+ * Requires G >= 1, N >= 0, L >= 1, 0 <= p, p_star <= 1; EXF_ERR_BAD_SHAPE otherwise.
+ *
+ * exf_transfer_ratios — p and p_star of a trace from the counters routing_transfers returns (HOST
+ * copies), for a trace of `tokens` tokens without invalid ids (Design, "Token Context Coherence in
+ * Expert Parallelism": vanilla moves a token out and back whenever its expert is not at home, a
+ * coherent context moves from home to its first expert and then only between GPUs that differ):
+ *   p      = sum_l away_per_layer[l] / (tokens * L)
+ *   p_star = (away_per_layer[0] + sum_l (tokens - local_per_pair[l])) / (tokens * L)
+ * so that 2*G*N*L*p and G*N*L*p_star with G*N = tokens are exactly the two transfer counts.
+ * local_per_pair_host may be NULL when L == 1.  tokens >= 1, L >= 1.
+ * ------------------------------------------------------------------------------------- */
+int exf_comm_volume(int G, int64_t N, int L, double p, double p_star, double* volumes_host);
+int exf_transfer_ratios(const int64_t* away_per_layer_host, const int64_t* local_per_pair_host, int L,
+                        int64_t tokens, double* p_host, double* p_star_host);
+
 /* Host helper: placement is a HOST array [L,E].  Returns EXF_OK iff every entry is in [0,G)
  * and every device holds exactly E/G experts of every layer (the load-balance and
  * exclusivity constraints of the integer program); EXF_ERR_BAD_SHAPE otherwise. */
@@ -303,27 +330,6 @@ int placement_locality_from_counts(const int64_t* counts, const int32_t* placeme
                                    int E, int64_t* local, void* stream);
 int exf_placement_search(const int64_t* counts_host, int L, int E, int G, int nodes, int restarts,
                          uint64_t seed, int32_t* placement_host);
-
-/* ---------------------------------------------------------------------------------------
- * Measurement probes (no counterpart in the paper; used by the benchmark to report achieved
- * rates next to the data-sheet peaks and to calibrate the profiler's HBM byte counters).
- *   exf_probe_copy: dst[0..bytes) = src[0..bytes), a plain streaming copy; bytes % 16 == 0,
- *                   both device pointers 16-byte aligned.
- *   exf_probe_mfma: `workgroups` x 256 threads, every wavefront issues 4*iters independent
- *                   32x32x16 bf16 MFMAs (4*iters*32768 flop per wavefront); out receives
- *                   workgroups*256 floats (device) so that the loop cannot be removed.
- *   exf_probe_gemm_loop: the bare K loop of a 256x256x64-tiled bf16 GEMM (direct-to-LDS operand
- *                   loads, LDS operand fetches, MFMAs, one barrier per K tile; no epilogue) over
- *                   caller-supplied operands: `operands` holds exf_probe_gemm_loop_bytes() bytes
- *                   (8 x [1024,1024] activations followed by 8 x [4096,1024] weights, bf16);
- *                   256 workgroups walk all 512 output tiles `passes` times, i.e.
- *                   passes * 512 * 2*256*256*1024 flop; out receives 256*256 floats.  The rate it
- *                   reaches depends on the operand values (all zeros against random numbers).
- * ------------------------------------------------------------------------------------- */
-int exf_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
-int exf_probe_mfma(int workgroups, int iters, float* out, void* stream);
-size_t exf_probe_gemm_loop_bytes(void);
-int exf_probe_gemm_loop(const void* operands, size_t bytes, int passes, float* out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,40 @@
+/* exflow_probe.h — measurement probes of libexflow_moe.so.
+ *
+ * Not part of the method's boundary (exflow_moe.h): these calls have no counterpart in the paper.
+ * The benchmark uses them to report the rates this GPU sustains next to the data-sheet peaks and
+ * to calibrate the profiler's HBM byte counters.  Same conventions as exflow_moe.h: device
+ * pointers, caller-owned buffers, host-side validation before any launch, asynchronous on `stream`.
+ */
+#ifndef EXFLOW_PROBE_H
+#define EXFLOW_PROBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---------------------------------------------------------------------------------------
+ *   exf_probe_copy: dst[0..bytes) = src[0..bytes), a plain streaming copy; bytes % 16 == 0,
+ *                   both device pointers 16-byte aligned.
+ *   exf_probe_mfma: `workgroups` x 256 threads, every wavefront issues 4*iters independent
+ *                   32x32x16 bf16 MFMAs (4*iters*32768 flop per wavefront); out receives
+ *                   workgroups*256 floats (device) so that the loop cannot be removed.
+ *   exf_probe_gemm_loop: the bare K loop of a 256x256x64-tiled bf16 GEMM (direct-to-LDS operand
+ *                   loads, LDS operand fetches, MFMAs, one barrier per K tile; no epilogue) over
+ *                   caller-supplied operands: `operands` holds exf_probe_gemm_loop_bytes() bytes
+ *                   (8 x [1024,1024] activations followed by 8 x [4096,1024] weights, bf16);
+ *                   256 workgroups walk all 512 output tiles `passes` times, i.e.
+ *                   passes * 512 * 2*256*256*1024 flop; out receives 256*256 floats.  The rate it
+ *                   reaches depends on the operand values (all zeros against random numbers).
+ * ------------------------------------------------------------------------------------- */
+int exf_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+int exf_probe_mfma(int workgroups, int iters, float* out, void* stream);
+size_t exf_probe_gemm_loop_bytes(void);
+int exf_probe_gemm_loop(const void* operands, size_t bytes, int passes, float* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EXFLOW_PROBE_H */

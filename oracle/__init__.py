@@ -240,6 +240,29 @@ def routing_away(trace, placement, home):
     return out
 
 
+def comm_volume(G, N, L, p, p_star):
+    """Forward communication volumes of the paper's comparison table, in tokens:
+    (vanilla top-1, vanilla top-2, coherent top-1, coherent top-2)."""
+    vol = np.zeros(4, dtype=np.float64)
+    _load().ref_comm_volume(int(G), c_i64(int(N)), int(L), c_d(p), c_d(p_star), _p(vol, c_d))
+    return vol
+
+
+def transfer_ratios(trace, placement, home):
+    """(p, p_star) of a clean trace: the share of (token, layer) visits that leave home (vanilla) and
+    the share at which a coherent context moves."""
+    trace = _i32(trace)
+    placement = _i32(placement)
+    home = _i32(home)
+    L, N = trace.shape
+    E = placement.shape[1]
+    assert placement.shape[0] == L and home.shape == (N,)
+    assert trace.min() >= 0 and trace.max() < E
+    r = np.zeros(2, dtype=np.float64)
+    _load().ref_transfer_ratios(_p(trace, c_i32), _p(placement, c_i32), _p(home, c_i32), L, c_i64(N), E, _p(r, c_d))
+    return float(r[0]), float(r[1])
+
+
 # --------------------------------------------------------------------------- placement search
 # Design, "Solving Affinity's duality by Integer Programming": minimise the number of crossing
 # transitions sum_k sum_j R_{k,j} subject to load balance (every part holds E/P experts of every

@@ -344,6 +344,45 @@ void ref_routing_away(const int32_t* trace, const int32_t* placement, const int3
 }
 
 /* -------------------------------------------------------------------------------------
+ * Forward communication volume (Table "Comparison with state-of-the-art GPT MoE optimization
+ * methods"), in tokens.  G GPUs, N tokens per GPU, L MoE layers; p = ratio of tokens involved in
+ * an Alltoall, p* = the same ratio with coherent contexts and an affinity placement.
+ *   row "Deepspeed-MoE": top-1  2 G N L p        top-2  4 G N L p
+ *   row "ExFlow":        top-1  G N (L p* + G)   top-2  G N (2 L p* + G)
+ * The table's entries written out as they stand: vol[0..3] in that order.
+ * ---------------------------------------------------------------------------------- */
+void ref_comm_volume(int G, int64_t N, int L, double p, double p_star, double* vol)
+{
+    double g = (double)G, n = (double)N, l = (double)L;
+    vol[0] = 2.0 * g * n * l * p;
+    vol[1] = 4.0 * g * n * l * p;
+    vol[2] = g * n * (l * p_star + g);
+    vol[3] = g * n * (2.0 * l * p_star + g);
+}
+
+/* The two ratios of a trace (Design, "Token Context Coherence in Expert Parallelism"), by walking
+ * every token as the walk-through does: a vanilla token leaves home (and returns) at every layer
+ * whose expert is elsewhere; a coherent context moves when the GPU of its next expert differs from
+ * where it is.  ratios[0] = p = away visits / (N L), ratios[1] = p* = moves / (N L).  Expert ids
+ * must be valid. */
+void ref_transfer_ratios(const int32_t* trace, const int32_t* placement, const int32_t* home, int L,
+                         int64_t N, int E, double* ratios)
+{
+    int64_t away = 0, moves = 0;
+    for (int64_t n = 0; n < N; ++n) {
+        int32_t at = home[n];
+        for (int l = 0; l < L; ++l) {
+            int32_t gpu = placement[(int64_t)l * E + trace[(int64_t)l * N + n]];
+            if (gpu != home[n]) away += 1;
+            if (gpu != at) moves += 1;
+            at = gpu;
+        }
+    }
+    ratios[0] = (double)away / ((double)N * (double)L);
+    ratios[1] = (double)moves / ((double)N * (double)L);
+}
+
+/* -------------------------------------------------------------------------------------
  * Affinity across several layers (appendix "Extend Expert Affinity to Cross Multiple Layers":
  * the affinity of layer l's experts to the experts of ALL following layers).  The same count
  * as ref_affinity_counts for every ordered pair of layers l < l':

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     affinity_multihop,
     affinity_statistics,
     check_placement,
+    comm_volume,
     last_error,
     lib,
     moe_combine,
@@ -29,4 +30,5 @@ from .binding import (  # noqa: F401
     placement_locality_from_counts,
     placement_search,
     routing_transfers,
+    transfer_ratios,
 )

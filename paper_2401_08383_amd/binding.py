@@ -34,6 +34,8 @@ SIGNATURES = {
     "exf_version": (_i, []),
     "exf_last_error": (ctypes.c_char_p, []),
     "exf_check_placement": (_i, [_vp, _i, _i, _i]),
+    "exf_comm_volume": (_i, [_i, _i64, _i, ctypes.c_double, ctypes.c_double, _vp]),
+    "exf_transfer_ratios": (_i, [_vp, _vp, _i, _i64, _vp, _vp]),
     "moe_gate_topk": (_i, [_vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "moe_topk_from_logits": (_i, [_vp, _i64, _i, _i, _i, _vp, _vp, _vp]),
     "moe_dispatch_workspace_bytes": (_sz, [_i64, _i, _i]),
@@ -345,3 +347,24 @@ def check_placement(placement_host, G) -> bool:
     assert placement_host.device.type == "cpu" and placement_host.dtype == torch.int32 and placement_host.is_contiguous()
     L, E = placement_host.shape
     return lib().exf_check_placement(placement_host.data_ptr(), L, E, G) == EXF_OK
+
+
+def comm_volume(G, N, L, p, p_star):
+    """Forward communication of the paper's comparison table, in tokens:
+    dict(vanilla_top1, vanilla_top2, coherent_top1, coherent_top2)."""
+    out = (ctypes.c_double * 4)()
+    _check(lib().exf_comm_volume(int(G), int(N), int(L), float(p), float(p_star), ctypes.addressof(out)))
+    return dict(vanilla_top1=out[0], vanilla_top2=out[1], coherent_top1=out[2], coherent_top2=out[3])
+
+
+def transfer_ratios(away_per_layer_host, local_per_pair_host, tokens):
+    """(p, p_star) from HOST copies (torch CPU int64) of the counters routing_transfers returns."""
+    assert away_per_layer_host.device.type == "cpu" and away_per_layer_host.dtype == torch.int64 and away_per_layer_host.is_contiguous()
+    L = away_per_layer_host.numel()
+    if L > 1:
+        assert local_per_pair_host.device.type == "cpu" and local_per_pair_host.dtype == torch.int64
+        assert local_per_pair_host.is_contiguous() and local_per_pair_host.numel() == L - 1
+    p, p_star = ctypes.c_double(), ctypes.c_double()
+    _check(lib().exf_transfer_ratios(away_per_layer_host.data_ptr(), local_per_pair_host.data_ptr() if L > 1 else None, L, int(tokens),
+                                     ctypes.addressof(p), ctypes.addressof(p_star)))
+    return p.value, p_star.value

@@ -39,15 +39,15 @@ __global__ __launch_bounds__(kScoreThreads) void placement_score_kernel(const in
                                                                          int64_t* __restrict__ local)
 {
     extern __shared__ long long cnt_lds[];  // [E][E] counts of this layer pair
-    const int l = blockIdx.x;
+    const int l = blockIdx.y;  // layer pair on y (at most 255), candidate slices on x (up to 2^18)
     const int64_t* src = counts + static_cast<size_t>(l) * E * E;
     for (int i = threadIdx.x; i < E * E; i += kScoreThreads) cnt_lds[i] = src[i];
     __syncthreads();
 
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
-    const int b_end = min(B, (static_cast<int>(blockIdx.y) + 1) * kScoreSlice);
-    int b = static_cast<int>(blockIdx.y) * kScoreSlice + wave;
+    const int b_end = min(B, (static_cast<int>(blockIdx.x) + 1) * kScoreSlice);
+    int b = static_cast<int>(blockIdx.x) * kScoreSlice + wave;
     // parts of the candidate's experts at layers l (lane = source expert) and l+1 (lane = target expert);
     // the next candidate's two rows are requested before the current one is scored
     auto load_rows = [&](int cand, int& cur_row, int& nxt_row) {
@@ -301,7 +301,7 @@ extern "C" int placement_locality_from_counts(const int64_t* counts, const int32
     EXF_REQUIRE_PTR(counts);
     EXF_REQUIRE_PTR(placements);
     EXF_REQUIRE_PTR(local);
-    const dim3 grid(static_cast<unsigned>(L - 1), static_cast<unsigned>((B + kScoreSlice - 1) / kScoreSlice));
+    const dim3 grid(static_cast<unsigned>((B + kScoreSlice - 1) / kScoreSlice), static_cast<unsigned>(L - 1));
     const size_t lds = static_cast<size_t>(E) * E * sizeof(long long);
     hipLaunchKernelGGL(placement_score_kernel, grid, dim3(kScoreThreads), lds, static_cast<hipStream_t>(stream), counts, placements, B, L,
                        E, local);

@@ -3,6 +3,7 @@
 // K loop over caller-supplied operands (what the matrix cores sustain while operands stream through
 // LDS - which depends on the operand VALUES: the chip holds a power limit, not a clock).
 #include "common.hpp"
+#include "exflow_probe.h"
 
 namespace exf {
 

@@ -121,3 +121,41 @@ def expected_dispatch_compare(res_gpu, ref, A):
     np.testing.assert_array_equal(res_gpu.expert_offsets.cpu().numpy(), ref["offsets"])
     np.testing.assert_array_equal(res_gpu.src_of_sorted.cpu().numpy()[:kept], ref["src_of_sorted"])
     np.testing.assert_array_equal(res_gpu.sorted_of_src.cpu().numpy(), ref["sorted_of_src"])
+
+
+STRATUM_ROWS = 64  # finer than any row tile a kernel may cut an expert's rows into (a power of two <= 64 rows divides it)
+
+
+def sample_rows(offsets, per_stratum, seed, min_rows=0):
+    """Stratified sample of sorted rows: every expert's rows are cut into consecutive blocks of
+    STRATUM_ROWS rows (counted from the expert's first row, the last block ragged) and every block
+    gives `per_stratum` random rows; the first and the last row of every expert are added.  Whatever
+    row tiling the GPU path uses - full tiles, remainder tiles, a masked last tile - each of its row
+    tiles then holds at least one row that the oracle evaluates.  `per_stratum` is raised until the
+    sample has `min_rows` rows."""
+    offsets = np.asarray(offsets, dtype=np.int64)
+    total = int(offsets[-1] - offsets[0])
+    while True:
+        g = syn.rng(seed)
+        rows = []
+        for e in range(len(offsets) - 1):
+            lo, hi = int(offsets[e]), int(offsets[e + 1])
+            if hi <= lo:
+                continue
+            pick = {lo, hi - 1}
+            for b in range(lo, hi, STRATUM_ROWS):
+                top = min(b + STRATUM_ROWS, hi)
+                pick.update(b + int(v) for v in g.permutation(top - b)[:per_stratum])
+            rows.extend(sorted(pick))
+        if len(rows) >= min(min_rows, total) or per_stratum >= STRATUM_ROWS:
+            return np.array(rows, dtype=np.int64)
+        per_stratum += 1
+
+
+def strata_covered(offsets, rows):
+    """Number of (expert, STRATUM_ROWS-row block) strata and how many of them hold a sampled row."""
+    offsets = np.asarray(offsets, dtype=np.int64)
+    owner = np.searchsorted(offsets, rows, side="right") - 1
+    hit = {(int(e), int((r - offsets[e]) // STRATUM_ROWS)) for e, r in zip(owner, rows)}
+    n = sum(int(-(-(offsets[e + 1] - offsets[e]) // STRATUM_ROWS)) for e in range(len(offsets) - 1))
+    return n, len(hit)

@@ -12,13 +12,15 @@ import paper_2401_08383_amd as exf
 from paper_2401_08383_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "exflow_moe.h")
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("exflow_moe.h", "exflow_probe.h")]
 
 
-def _declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(?:int|size_t|const char\*)\s+(\w+)\s*\(", text)))
+def _declared_functions(headers=HEADERS):
+    names = set()
+    for h in headers:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names.update(re.findall(r"\b(?:int|size_t|const char\*)\s+(\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -30,6 +32,9 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
     assert sorted(B.SIGNATURES) == names  # the binding covers exactly the header
     assert lib.exf_version() >= 100
+    # the method's boundary holds no measurement probe; those live in a header of their own
+    assert not [n for n in _declared_functions(HEADERS[:1]) if "probe" in n]
+    assert all("probe" in n for n in _declared_functions(HEADERS[1:]))
 
 
 def test_host_validation_rejects_before_launch():
@@ -145,3 +150,58 @@ def test_check_placement_constraints():
     bad[0, 0] = 7
     assert not exf.check_placement(bad, 4)
     assert "device" in exf.last_error()
+
+
+def test_comm_volume_helper_matches_the_oracle(oracle):
+    """Host arithmetic of the library against the oracle's transcription of the paper's table."""
+    import synth_inputs as syn
+
+    g = syn.rng(77)
+    for _ in range(200):
+        G, N, L = int(g.integers(1, 129)), int(g.integers(0, 1 << 22)), int(g.integers(1, 97))
+        p, ps = float(g.random()), float(g.random())
+        got = exf.comm_volume(G, N, L, p, ps)
+        ref = oracle.comm_volume(G, N, L, p, ps)
+        np.testing.assert_allclose([got["vanilla_top1"], got["vanilla_top2"], got["coherent_top1"], got["coherent_top2"]], ref,
+                                   rtol=1e-14, atol=0)
+    lib = exf.lib()
+    out = (ctypes.c_double * 4)()
+    for bad in [(0, 10, 3, 0.5, 0.5), (4, -1, 3, 0.5, 0.5), (4, 10, 0, 0.5, 0.5), (4, 10, 3, 1.5, 0.5), (4, 10, 3, 0.5, -0.1),
+                (4, 10, 3, float("nan"), 0.5)]:
+        assert lib.exf_comm_volume(*bad[:3], ctypes.c_double(bad[3]), ctypes.c_double(bad[4]), ctypes.addressof(out)) == B.EXF_ERR_BAD_SHAPE
+    assert lib.exf_comm_volume(4, 10, 3, ctypes.c_double(0.5), ctypes.c_double(0.5), None) == B.EXF_ERR_NULL_PTR
+
+
+def test_transfer_ratios_helper_matches_the_oracle(oracle):
+    """p and p* from the two counter arrays (here the oracle's own counters stand in for the device's)
+    against the oracle's token-by-token walk."""
+    import synth_inputs as syn
+
+    for seed, (L, N, E, G) in enumerate([(6, 3000, 16, 4), (1, 50, 4, 2), (24, 700, 64, 8), (2, 1, 2, 2)]):
+        g = syn.rng(80 + seed)
+        trace = g.integers(0, E, size=(L, N)).astype(np.int32)
+        pl = syn.balanced_random_placement(L, E, G, 90 + seed)
+        home = g.integers(0, G, size=N).astype(np.int32)
+        away = torch.from_numpy(oracle.routing_away(trace, pl, home))
+        local = torch.from_numpy(oracle.placement_locality(trace, pl))
+        p, ps = exf.transfer_ratios(away, local, N)
+        p_ref, ps_ref = oracle.transfer_ratios(trace, pl, home)
+        assert abs(p - p_ref) <= 1e-15 and abs(ps - ps_ref) <= 1e-15
+    lib = exf.lib()
+    a = torch.tensor([5, 7], dtype=torch.int64)
+    loc = torch.tensor([3], dtype=torch.int64)
+    p, q = ctypes.c_double(), ctypes.c_double()
+    assert lib.exf_transfer_ratios(a.data_ptr(), loc.data_ptr(), 2, 6, ctypes.addressof(p), ctypes.addressof(q)) == B.EXF_ERR_BAD_SHAPE  # 7 > tokens
+    assert lib.exf_transfer_ratios(a.data_ptr(), None, 2, 10, ctypes.addressof(p), ctypes.addressof(q)) == B.EXF_ERR_NULL_PTR
+    assert lib.exf_transfer_ratios(a.data_ptr(), loc.data_ptr(), 2, 0, ctypes.addressof(p), ctypes.addressof(q)) == B.EXF_ERR_BAD_SHAPE
+
+
+def test_candidate_batch_bound_of_the_scoring_call():
+    """placement_locality_from_counts accepts up to 2^24 candidate maps (its launch puts the candidate
+    slices on the x axis of the grid); one more is refused on the host."""
+    lib = exf.lib()
+    one = ctypes.c_void_p(4096)
+    assert lib.placement_locality_from_counts(one, one, (1 << 24) + 1, 4, 8, one, None) == B.EXF_ERR_BAD_SHAPE
+    assert lib.placement_locality_from_counts(one, one, -1, 4, 8, one, None) == B.EXF_ERR_BAD_SHAPE
+    assert lib.placement_locality_from_counts(one, one, 0, 4, 8, one, None) == B.EXF_OK
+    assert lib.placement_locality_from_counts(None, one, 1 << 24, 4, 8, one, None) == B.EXF_ERR_NULL_PTR

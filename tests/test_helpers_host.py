@@ -55,3 +55,29 @@ def test_routing_check_separates_clear_and_near_tied_tokens():
         check_routing_against_fp64(np.array([[2], [2], [0]]), logits, 1, 1e-4)  # a near-tie resolved to a far expert
     with pytest.raises(AssertionError):
         assert_gate_close(np.array([1.0002]), np.array([1.0]), 1e-4)
+
+
+def test_stratified_sample_reaches_every_row_tile():
+    """Every aligned block of 64 rows of every expert holds a sampled row, so does every coarser
+    row tile (256-row tiles, 64-row remainder tiles, a masked last tile), however ragged the loads."""
+    from helpers import STRATUM_ROWS, sample_rows, strata_covered
+
+    g = syn.rng(902)
+    counts = np.concatenate([[0, 1, 63, 64, 65, 255, 256, 257, 4649], g.integers(0, 700, size=23)])
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    rows = sample_rows(offsets, 1, 7)
+    n, hit = strata_covered(offsets, rows)
+    assert hit == n == sum(-(-int(c) // STRATUM_ROWS) for c in counts)
+    assert (np.diff(rows) > 0).all() and rows.min() >= 0 and rows.max() < offsets[-1]
+    for e, c in enumerate(counts):  # first and last row of every non-empty expert
+        if c:
+            assert offsets[e] in rows and offsets[e + 1] - 1 in rows
+    for tile in (64, 128, 256):  # coarser tiles counted from the expert's first row
+        for e, c in enumerate(counts):
+            mine = rows[(rows >= offsets[e]) & (rows < offsets[e + 1])] - offsets[e]
+            assert len(np.unique(mine // tile)) == -(-int(c) // tile)
+    big = sample_rows(offsets, 1, 7, min_rows=1024)
+    assert len(big) >= 1024 and strata_covered(offsets, big) == (n, n)
+    assert len(sample_rows(np.array([0, 5, 5, 9]), 1, 3, min_rows=1024)) == 9  # never more rows than there are
+    # a sample that misses a block is reported as such
+    assert strata_covered(offsets, rows[rows >= 64])[1] < n

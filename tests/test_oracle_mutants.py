@@ -45,6 +45,11 @@ MUTANTS = [
      "if (placement[(int64_t)l * E + i] == placement[(int64_t)(l + 1) * E + p])\n                    c += counts",
      "if (placement[(int64_t)l * E + i] == placement[(int64_t)l * E + p])\n                    c += counts"),
     ("transfers: tokens at home counted instead of tokens away", "!= home[n]) c += 1;", "== home[n]) c += 1;"),
+    ("volume model: vanilla counted one way only", "vol[0] = 2.0 * g * n * l * p;", "vol[0] = g * n * l * p;"),
+    ("volume model: AllGather term of one GPU instead of G", "vol[2] = g * n * (l * p_star + g);", "vol[2] = g * n * (l * p_star + 1.0);"),
+    ("volume model: top-2 doubles the AllGather as well", "vol[3] = g * n * (2.0 * l * p_star + g);", "vol[3] = 2.0 * g * n * (l * p_star + g);"),
+    ("transfer ratios: a coherent context is always compared with home", "if (gpu != at) moves += 1;", "if (gpu != home[n]) moves += 1;"),
+    ("transfer ratios: the context does not stay where its expert was", "            at = gpu;\n", ""),
     ("multi-hop: counts transposed", "c[(int64_t)a * E + b] += 1;", "c[(int64_t)b * E + a] += 1;"),
     ("multi-hop: target layer is always the next one", "int32_t b = trace[(int64_t)m * N + n];", "int32_t b = trace[(int64_t)(l + 1) * N + n];"),
 ]

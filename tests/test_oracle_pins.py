@@ -536,3 +536,71 @@ def test_multihop_counts_pins(oracle):
             np.testing.assert_array_equal(c.sum(axis=1), loads1[l])
             np.testing.assert_array_equal(c.sum(axis=0), loads1[m])
     assert [oracle.multihop_pair_index(4, l, m) for l in range(4) for m in range(l + 1, 4)] == list(range(6))
+
+
+# --------------------------------------------------------------------------- communication volume model
+def test_comm_volume_hand_computed_and_structure(oracle):
+    """Table "Comparison with state-of-the-art GPT MoE optimization methods", evaluated by hand:
+    G = 8 GPUs, N = 1000 tokens per GPU, L = 12 layers, p = 0.875, p* = 0.25."""
+    v = oracle.comm_volume(8, 1000, 12, 0.875, 0.25)
+    assert v.tolist() == [168000.0, 336000.0, 88000.0, 112000.0]  # 2*96000*.875, 4*..., 8000*(3+8), 8000*(6+8)
+    # uniform routing over G GPUs leaves (G-1)/G of the tokens away from home: p = 7/8 above, and the
+    # vanilla top-1 volume is then 2 (G-1) N L
+    assert v[0] == 2 * 7 * 1000 * 12
+    g = syn.rng(950)
+    for _ in range(50):
+        G, N, L = int(g.integers(1, 65)), int(g.integers(0, 100000)), int(g.integers(1, 49))
+        p, ps = float(g.random()), float(g.random())
+        a = oracle.comm_volume(G, N, L, p, ps)
+        assert a[1] == 2 * a[0]                                   # top-2 doubles the vanilla volume
+        gather = G * N * G
+        assert math.isclose(a[3] - gather, 2 * (a[2] - gather), rel_tol=1e-12, abs_tol=1e-9)  # ... and only the Alltoall part of the coherent one
+        assert math.isclose(a[2], oracle.comm_volume(G, N, L, p, 0.0)[2] + G * N * L * ps, rel_tol=1e-12, abs_tol=1e-9)
+        assert oracle.comm_volume(G, N, L, p, 0.0)[2] == gather   # nothing moves: the AllGather term alone
+        b = oracle.comm_volume(G, 3 * N, L, p, ps)
+        np.testing.assert_allclose(b, 3 * a, rtol=1e-12)          # linear in the tokens per GPU
+        # the coherent scheme wins exactly when L p* + G < 2 L p
+        if not math.isclose(L * ps + G, 2 * L * p, rel_tol=1e-9):
+            assert (a[2] < a[0]) == (L * ps + G < 2 * L * p)
+    # an argument swap (p for p*, G for L) changes the result
+    assert oracle.comm_volume(8, 1000, 12, 0.25, 0.875).tolist() != v.tolist()
+    assert oracle.comm_volume(12, 1000, 8, 0.875, 0.25).tolist() != v.tolist()
+
+
+def test_comm_volume_on_the_printed_walk_through(oracle):
+    """Design, "Token Context Coherence in Expert Parallelism": the two tokens of the walk-through need
+    4 + 6 transfers with vanilla expert parallelism and 3 + 1 with coherent contexts.  With G*N = 2
+    resident tokens the table's Alltoall terms 2*G*N*L*p and G*N*L*p* must be those totals."""
+    with open(os.path.join(GOLDEN, "fig_compare_example.json")) as fh:
+        ex = json.load(fh)
+    L, E, G = ex["layers"], ex["experts"], ex["gpus"]
+    default = syn.contiguous_placement(L, E, G)
+    trace = np.array([t["experts"] for t in ex["tokens"]], dtype=np.int32).T.copy()
+    home = np.array([t["home_gpu"] for t in ex["tokens"]], dtype=np.int32)
+    p, ps = oracle.transfer_ratios(trace, default, home)
+    assert math.isclose(p, (4 + 6) / 2 / (2 * L)) and math.isclose(ps, (3 + 1) / (2 * L))
+    vol = oracle.comm_volume(2, 1, L, p, ps)   # two GPUs' worth of one token each: G*N = 2 tokens
+    assert math.isclose(vol[0], sum(ex["vanilla_transfers"]))
+    assert math.isclose(vol[2] - 2 * 1 * 2, sum(ex["coherent_transfers"]))
+    for n in range(2):  # token by token
+        pn, psn = oracle.transfer_ratios(trace[:, n:n + 1].copy(), default, home[n:n + 1])
+        assert math.isclose(2 * L * pn, ex["vanilla_transfers"][n]) and math.isclose(L * psn, ex["coherent_transfers"][n])
+
+
+def test_transfer_ratios_against_the_counters(oracle):
+    """The token walk agrees with the two counter formulas (2*sum away; away[0] + crossings), which
+    are computed by separately written routines, and with closed forms."""
+    L, N, E, G = 6, 5000, 16, 4
+    g = syn.rng(951)
+    trace = g.integers(0, E, size=(L, N)).astype(np.int32)
+    pl = syn.balanced_random_placement(L, E, G, 952)
+    home = g.integers(0, G, size=N).astype(np.int32)
+    p, ps = oracle.transfer_ratios(trace, pl, home)
+    away = oracle.routing_away(trace, pl, home)
+    local = oracle.placement_locality(trace, pl)
+    assert math.isclose(p, away.sum() / (N * L))
+    assert math.isclose(ps, (away[0] + (N * (L - 1) - local.sum())) / (N * L))
+    assert abs(p - (G - 1) / G) < 0.02 and abs(ps - (G - 1) / G) < 0.02   # uniform routing: any GPU equally likely
+    one = np.zeros((L, E), dtype=np.int32)
+    assert oracle.transfer_ratios(trace, one, np.zeros(N, np.int32)) == (0.0, 0.0)      # everything at home
+    assert oracle.transfer_ratios(trace, one, np.ones(N, np.int32)) == (1.0, 1.0 / L)   # one move, then stays
