@@ -57,6 +57,7 @@ extern "C" {
 
 #define EXF_MAX_EXPERTS 64   /* gate width E, local experts E_local and trace alphabet E */
 #define EXF_MAX_TOPK 2
+#define EXF_DISPATCH_STATIC_MAX_ASSIGNMENTS (1ll << 20)  /* largest T*k of moe_dispatch_static */
 #define EXF_MAX_TRACE_LAYERS 256
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -120,6 +121,21 @@ int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* expert_m
                  int k, int E, int E_local, int dt, void* x_sorted, int32_t* src_of_sorted,
                  int32_t* sorted_of_src, int32_t* expert_counts, int32_t* expert_offsets,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_dispatch_static — moe_dispatch for callers that cannot allocate or supply scratch memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs and validation as moe_dispatch without the workspace pair; the per-chunk
+ * expert counts live in a device array built into the library (256 KiB per GPU, held until the
+ * process ends).  Limit: T*k <= EXF_DISPATCH_STATIC_MAX_ASSIGNMENTS, EXF_ERR_BAD_SHAPE beyond it.
+ * The call allocates and frees nothing.  All calls on one GPU share that array: calls that overlap
+ * on one GPU (different streams, different threads) race and must be serialised by the caller;
+ * successive calls on one stream are safe, nothing has to be cleared in between.
+ * ------------------------------------------------------------------------------------- */
+int moe_dispatch_static(const void* x, const int32_t* topk_idx, const int32_t* expert_map, int64_t T,
+                        int d, int k, int E, int E_local, int dt, void* x_sorted,
+                        int32_t* src_of_sorted, int32_t* sorted_of_src, int32_t* expert_counts,
+                        int32_t* expert_offsets, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * moe_expert_ffn — every local expert applies its feed-forward network to the rows routed

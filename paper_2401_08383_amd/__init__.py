@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     lib,
     moe_combine,
     moe_dispatch,
+    moe_dispatch_static,
     moe_expert_ffn,
     moe_expert_ffn_fused,
     moe_gate_topk,

@@ -40,6 +40,7 @@ SIGNATURES = {
     "moe_topk_from_logits": (_i, [_vp, _i64, _i, _i, _i, _vp, _vp, _vp]),
     "moe_dispatch_workspace_bytes": (_sz, [_i64, _i, _i]),
     "moe_dispatch": (_i, [_vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_dispatch_static": (_i, [_vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_expert_ffn_workspace_bytes": (_sz, [_i64, _i, _i, _i, _i]),
     "moe_expert_ffn": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]),
     "moe_expert_ffn_fused_workspace_bytes": (_sz, [_i64, _i, _i, _i, _i, _i]),
@@ -177,6 +178,19 @@ def moe_dispatch(x, topk_idx, E, E_local=None, expert_map=None, out=None, worksp
     _check(lib().moe_dispatch(_ptr(x), _ptr(topk_idx), _ptr(expert_map), T, d, k, E, E_local, dtype_code(x),
                               _ptr(out.x_sorted), _ptr(out.src_of_sorted), _ptr(out.sorted_of_src),
                               _ptr(out.expert_counts), _ptr(out.expert_offsets), _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def moe_dispatch_static(x, topk_idx, E, out, E_local=None, expert_map=None):
+    """moe_dispatch without a workspace and without any allocation: every output tensor comes from the
+    caller (``out``: a DispatchResult; ``x_sorted`` None skips the row gather)."""
+    T, k = topk_idx.shape
+    d = x.shape[1]
+    E_local = E if E_local is None else E_local
+    assert topk_idx.dtype == torch.int32 and topk_idx.is_contiguous() and x.is_contiguous()
+    _check(lib().moe_dispatch_static(_ptr(x), _ptr(topk_idx), _ptr(expert_map), T, d, k, E, E_local, dtype_code(x),
+                                     _ptr(out.x_sorted), _ptr(out.src_of_sorted), _ptr(out.sorted_of_src),
+                                     _ptr(out.expert_counts), _ptr(out.expert_offsets), _stream()))
     return out
 
 

@@ -15,6 +15,8 @@
 //                x_sorted[position] = x[assignment / k] as 16-byte vector copies.
 //                (Without rows to move, dispatch_scatter_kernel ranks whole chunks instead.)
 // No step needs the host to know a data-dependent size.
+#include <mutex>
+
 #include "common.hpp"
 
 namespace exf {
@@ -378,12 +380,14 @@ extern "C" size_t moe_dispatch_workspace_bytes(int64_t T, int k, int E_local)
     return exf::align_up(static_cast<size_t>(blocks > 0 ? blocks : 1) * static_cast<size_t>(E_local) * sizeof(int32_t), 256);
 }
 
-extern "C" int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* expert_map, int64_t T, int d, int k, int E,
-                            int E_local, int dt, void* x_sorted, int32_t* src_of_sorted, int32_t* sorted_of_src,
-                            int32_t* expert_counts, int32_t* expert_offsets, void* workspace, size_t workspace_bytes,
-                            void* stream)
+namespace exf {
+
+// Validation and launches shared by moe_dispatch (chunk counts in the caller's workspace) and
+// moe_dispatch_static (chunk counts in this library's own device array).
+static int dispatch_run(const void* x, const int32_t* topk_idx, const int32_t* expert_map, int64_t T, int d, int k, int E, int E_local,
+                        int dt, void* x_sorted, int32_t* src_of_sorted, int32_t* sorted_of_src, int32_t* expert_counts,
+                        int32_t* expert_offsets, void* workspace, size_t workspace_bytes, void* stream)
 {
-    using namespace exf;
     if (dt != EXF_F32 && dt != EXF_BF16) return fail(EXF_ERR_BAD_DTYPE, "moe_dispatch: dt = %d", dt);
     if (T < 0) return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch: T = %lld < 0", static_cast<long long>(T));
     if (k < 1 || k > EXF_MAX_TOPK) return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch: k = %d outside [1,%d]", k, EXF_MAX_TOPK);
@@ -449,4 +453,65 @@ extern "C" int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_
         }
     }
     return check_launch("moe_dispatch");
+}
+
+// ---- the entry point that allocates nothing --------------------------------------------------
+// Chunk counts of moe_dispatch_static: EXF_DISPATCH_STATIC_MAX_ASSIGNMENTS / 1024 chunks x 64 experts
+// of int32 = 256 KiB, held by every GPU the library runs on until the process ends.  Host code must
+// never pass the array's name to a kernel or a copy: the name is a host-side stand-in, the device
+// address comes from hipGetSymbolAddress, once per device.
+constexpr int64_t kStaticChunks = EXF_DISPATCH_STATIC_MAX_ASSIGNMENTS / kDispChunk;
+static __device__ __align__(256) int32_t scratch[kStaticChunks * EXF_MAX_EXPERTS];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static int32_t* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+static int scratch_of_current_device(int32_t** out)
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return fail(EXF_ERR_HIP, "moe_dispatch_static: hipGetDevice: %s", hipGetErrorString(err));
+    if (dev < 0 || dev >= kMaxDevices) return fail(EXF_ERR_HIP, "moe_dispatch_static: device %d outside [0,%d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || p == nullptr)
+            return fail(EXF_ERR_HIP, "moe_dispatch_static: hipGetSymbolAddress: %s", hipGetErrorString(err));
+        g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return EXF_OK;
+}
+
+}  // namespace exf
+
+extern "C" int moe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* expert_map, int64_t T, int d, int k, int E,
+                            int E_local, int dt, void* x_sorted, int32_t* src_of_sorted, int32_t* sorted_of_src,
+                            int32_t* expert_counts, int32_t* expert_offsets, void* workspace, size_t workspace_bytes,
+                            void* stream)
+{
+    return exf::dispatch_run(x, topk_idx, expert_map, T, d, k, E, E_local, dt, x_sorted, src_of_sorted, sorted_of_src, expert_counts,
+                             expert_offsets, workspace, workspace_bytes, stream);
+}
+
+extern "C" int moe_dispatch_static(const void* x, const int32_t* topk_idx, const int32_t* expert_map, int64_t T, int d, int k, int E,
+                                   int E_local, int dt, void* x_sorted, int32_t* src_of_sorted, int32_t* sorted_of_src,
+                                   int32_t* expert_counts, int32_t* expert_offsets, void* stream)
+{
+    using namespace exf;
+    if (T < 0 || k < 1 || k > EXF_MAX_TOPK || T > EXF_DISPATCH_STATIC_MAX_ASSIGNMENTS || T * k > EXF_DISPATCH_STATIC_MAX_ASSIGNMENTS)
+        return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch_static: T*k = %lld*%d exceeds the %lld assignments the built-in scratch holds",
+                    static_cast<long long>(T), k, static_cast<long long>(EXF_DISPATCH_STATIC_MAX_ASSIGNMENTS));
+    if (E_local < 1 || E_local > EXF_MAX_EXPERTS)
+        return fail(EXF_ERR_BAD_SHAPE, "moe_dispatch_static: E_local = %d outside [1,%d]", E_local, EXF_MAX_EXPERTS);
+    int32_t* ptr = nullptr;
+    const int rc = scratch_of_current_device(&ptr);
+    if (rc != EXF_OK) return rc;
+    // every entry of the count matrix that a launch reads is written by the count launch in front of
+    // it, so nothing has to be cleared between calls
+    return dispatch_run(x, topk_idx, expert_map, T, d, k, E, E_local, dt, x_sorted, src_of_sorted, sorted_of_src, expert_counts,
+                        expert_offsets, ptr, sizeof(int32_t) * kStaticChunks * EXF_MAX_EXPERTS, stream);
 }
