@@ -34,11 +34,27 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM-side bytes per moe_expert_ffn_fused call at the benchmark configuration, from two rocprofv3 --pmc
-# runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch summed over the call's three launches), each
-# scaled by what the same counter reads for the 1 GiB copy probe (FETCH x2.000, WRITE x1.000):
-# (73565.0 + 116043.8 + 3875.2) KiB x 2 + (65536 + 23692 + 744) KiB.  See profiles/bench_config2_hbm_traffic.txt.
-FFN_TRAFFIC_BYTES = int((73565.9 + 116043.3 + 3877.2) * 2 * 1024 + (65536 + 23692 + 744) * 1024)
+WARM_SECONDS = 0.3          # steps run before the caller's --warmup, so that the clocks are up whatever W is
+
+# HBM-side bytes per moe_expert_ffn_fused call at the benchmark configuration come from a tracked
+# rocprofv3 summary (two --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for
+# the 1 GiB copy probe); the file records the commit it was taken at.  Missing or unreadable: null.
+FFN_TRAFFIC_FILE = os.path.join(ROOT, "profiles", "ffn_config2_hbm_traffic.txt")
+
+
+def ffn_traffic_from_profile():
+    """(bytes per call, commit the profile was taken at) from the tracked summary, or (None, None)."""
+    try:
+        text = open(FFN_TRAFFIC_FILE).read()
+    except OSError:
+        return None, None
+    val = head = None
+    for line in text.splitlines():
+        if line.startswith("traffic_bytes_per_call:"):
+            val = int(float(line.split(":", 1)[1].split()[0]))
+        if line.startswith("head:"):
+            head = line.split(":", 1)[1].strip()
+    return val, head
 
 
 def _events(n):
@@ -61,21 +77,47 @@ def _time_call(fn, iters, warmup=3):
     return a.elapsed_time(b) / iters
 
 
-def _time_rotating(make_fn, n_sets, iters):
-    """Like _time_call, but cycles over `n_sets` distinct buffer sets so that neither L2 nor the
-    256 MB Infinity Cache can serve the reads."""
+def _time_groups(fns, groups=12, inner=5, warmup=10):
+    """Milliseconds per call of the calls in `fns`, cycled through in order (one buffer set per entry:
+    several entries whose buffers together exceed the 256 MB Infinity Cache give the rotated figure, one
+    entry the un-rotated one).  `groups` event pairs bracket `inner` calls each; returns mean, median
+    and min over the groups."""
     import torch
-    fns = [make_fn(i) for i in range(n_sets)]
-    for f in fns:
-        f()
-    a, b = _events(2)
+    n = len(fns)
+    for i in range(max(warmup, n)):
+        fns[i % n]()
+    ev = [_events(2) for _ in range(groups)]
     torch.cuda.synchronize()
-    a.record()
-    for i in range(iters):
-        fns[i % n_sets]()
-    b.record()
+    c = 0
+    for g in range(groups):
+        ev[g][0].record()
+        for _ in range(inner):
+            fns[c % n]()
+            c += 1
+        ev[g][1].record()
     torch.cuda.synchronize()
-    return a.elapsed_time(b) / iters
+    t = np.array([a.elapsed_time(b) / inner for a, b in ev])
+    return {"ms": float(t.mean()), "ms_median": float(np.median(t)), "ms_min": float(t.min())}
+
+
+def _hbm_entry(make_fn, n_sets, nbytes, extra=None):
+    """One HBM-bound call: rotated over `n_sets` buffer sets and un-rotated (set 0 only)."""
+    rot = _time_groups([make_fn(i) for i in range(n_sets)])
+    same = _time_groups([make_fn(0)])
+    gbs = nbytes / (rot["ms_median"] * 1e-3) / 1e9
+    out = {"ms": rot["ms_median"], "ms_mean": rot["ms"], "ms_min": rot["ms_min"], "GBps": gbs, "frac": gbs / PEAK_HBM_GBS, "bytes": nbytes,
+           "unrotated_ms": same["ms_median"], "unrotated_ms_min": same["ms_min"],
+           "unrotated_GBps": nbytes / (same["ms_median"] * 1e-3) / 1e9,
+           "unrotated_frac": nbytes / (same["ms_median"] * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    if extra:
+        out.update(extra(rot["ms_median"]))
+    return out
+
+
+def _set_oracle_threads(n):
+    """Thread count of the oracle's OpenMP loops (the GNU OpenMP runtime the oracle is linked with)."""
+    import ctypes
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
 
 
 def cpu_baseline(cfg, x, wg, w1, w2, trace, placement, sample_rows_per_expert=None):
@@ -126,6 +168,78 @@ def cpu_baseline(cfg, x, wg, w1, w2, trace, placement, sample_rows_per_expert=No
         "seconds_per_step_extrapolated": total,
         "seconds": {k: round(v, 4) for k, v in t.items()},
     }
+
+
+def cpu_baseline_single_thread(cfg, x, wg, w1, w2, rows_per_expert=4):
+    """The same oracle on ONE thread, on a bounded sample: the gate in full, the expert FFN (which is
+    all but a fraction of a percent of the step) on `rows_per_expert` rows of every expert,
+    extrapolated linearly; the other steps are taken from the full run (they are single-threaded
+    loops or negligible)."""
+    import oracle
+    _set_oracle_threads(1)
+    try:
+        t0 = time.perf_counter()
+        logits = oracle.gate_logits(x, wg)
+        idx, _ = oracle.topk(logits, cfg.k, cfg.renormalize)
+        t_gate = time.perf_counter() - t0
+        disp = oracle.dispatch(idx, None, cfg.E, cfg.E_local)
+        xs = oracle.gather_rows(x, disp["src_of_sorted"], cfg.k)
+        rows = []
+        for e in range(cfg.E_local):
+            lo, hi = int(disp["offsets"][e]), int(disp["offsets"][e + 1])
+            rows.extend(range(lo, min(hi, lo + rows_per_expert)))
+        rows = np.array(rows, dtype=np.int64)
+        t0 = time.perf_counter()
+        oracle.expert_ffn_rows(xs, disp["offsets"], w1, None, w2, None, 0, rows)
+        t_ffn = time.perf_counter() - t0
+    finally:
+        _set_oracle_threads(oracle.threads())
+    total = t_gate + t_ffn * disp["kept"] / max(len(rows), 1)
+    return {"value": cfg.T / total, "unit": "tokens/s", "cores": 1,
+            "sample": f"gate in full ({t_gate:.2f} s), expert FFN on {len(rows)} of {disp['kept']} rows ({t_ffn:.2f} s, extrapolated linearly)"}
+
+
+def other_configs(syn, torch, MoELayerRun, dev):
+    """Expert FFN (moe_expert_ffn_fused) and whole-layer time of the three larger configurations, each
+    against the roofline that bounds it.  Expert weights are drawn on the device (same distribution as
+    the host recipe, torch's generator); the decode-shaped configuration runs ONE layer's distinct
+    weights repeatedly - 17 GB per pass, far beyond any cache, so the timing is that of distinct layers."""
+    out = {}
+    for index in (3, 4, 5):
+        c = syn.CONFIGS[index]
+        x = torch.from_numpy(syn.tokens(c)).to(torch.bfloat16).to(dev)
+        wg = torch.from_numpy(syn.gate_weight(c)).to(torch.bfloat16).to(dev)
+        w1, w2 = syn.device_expert_weights(c, 0, dev)
+        kw = {}
+        if index == 3:
+            tr3, _ = syn.config_trace(c)
+            kw["topk_idx"] = torch.from_numpy(tr3[0].reshape(-1, 1).copy()).to(dev)
+        if index == 4:
+            idx4_h, map4_h = syn.local_routing(c, syn.seed_for(4, 4, 1))
+            kw["topk_idx"] = torch.from_numpy(idx4_h).to(dev)
+            kw["expert_map"] = torch.from_numpy(map4_h).to(dev)
+        run = MoELayerRun(x, wg, w1, w2, c.k, c.renormalize, fused=True, **kw)
+        run.step()
+        ffn = _time_groups([run.ffn], groups=6, inner=3, warmup=3)
+        layer = _time_groups([run.step], groups=6, inner=3, warmup=2)
+        A = c.T * c.k
+        flops = 4.0 * A * c.d * c.f
+        entry = {"workload": c.name, "tokens": c.T, "d_model": c.d, "d_ff": c.f, "local_experts": c.E_local, "top_k": c.k,
+                 "ffn_ms": ffn["ms_median"], "ffn_ms_min": ffn["ms_min"], "layer_ms": layer["ms_median"],
+                 "layer_tokens_per_s": c.T / (layer["ms_median"] * 1e-3), "weights": "drawn on the device, N(0, 0.02)"}
+        if index == 5:
+            nbytes = 2.0 * c.E_local * c.d * c.f * 2 + 2.0 * A * c.d * 2
+            gbs = nbytes / (ffn["ms_median"] * 1e-3) / 1e9
+            entry.update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                          "bytes_per_call": nbytes, "layers": "one layer's weights, repeated (the 8 layers of a step alias it here)"})
+        else:
+            tf = flops / (ffn["ms_median"] * 1e-3) / 1e12
+            entry.update({"bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS,
+                          "flops_per_call": flops})
+        out[f"config{index}"] = entry
+        del run, x, wg, w1, w2
+        torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -226,12 +340,24 @@ def main():
             lay.step()
         affinity_join()
 
+    # fixed internal warm-up (clocks, caches, lazy module loads), then the caller's W steps
+    step()
+    torch.cuda.synchronize()
+    t_w = time.perf_counter()
+    n_internal = 1
+    while time.perf_counter() - t_w < WARM_SECONDS:
+        for _ in range(8):
+            step()
+        n_internal += 8
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     ffn_ev = [[_events(2) for _ in layers] for _ in range(args.steps)]
+    step_ev = _events(args.steps + 1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
+        step_ev[i].record()
         affinity_fork()
         for j, lay in enumerate(layers):
             lay.gate()
@@ -241,10 +367,13 @@ def main():
             ffn_ev[i][j][1].record()
             lay.combine()
         affinity_join()
+    step_ev[args.steps].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
-    ffn_ms = float(np.mean([a.elapsed_time(b) for step_ev in ffn_ev for a, b in step_ev]))
+    per_step = np.array([step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(args.steps)])
+    ffn_all = np.array([a.elapsed_time(b) for step_ev_ in ffn_ev for a, b in step_ev_])
+    ffn_ms = float(ffn_all.mean())
 
     A = cfg.T * cfg.k
     ffn_flops = 4.0 * A * cfg.d * cfg.f
@@ -263,7 +392,11 @@ def main():
                     if bf16 else f"grouped_gemm_f32_kernel ({ffn_entry}, fp32 vector ALU: latency-bound tiny case)",
                     "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS if bf16 else 157.3, "unit": "TFLOP/s",
                     "frac": achieved_tf / (PEAK_BF16_TFLOPS if bf16 else 157.3),
-                    "traffic": FFN_TRAFFIC_BYTES if (cfg.index == 2 and fused) else None, "ms_per_launch": ffn_ms, "flops_per_launch": ffn_flops}
+                    "traffic": None, "ms_per_launch": ffn_ms, "flops_per_launch": ffn_flops}
+        if cfg.index == 2 and fused:
+            roofline["traffic"], roofline["traffic_profile_head"] = ffn_traffic_from_profile()
+    roofline["ms_per_launch_median"] = float(np.median(ffn_all))
+    roofline["ms_per_launch_min"] = float(ffn_all.min())
     workloads = {
         1: "configs[0] tiny fp32: d_model=64 d_ff=256 E=8 top-1 T=512; 2-layer x 512-token trace",
         2: "configs[1] GPT-MoE-350M-shaped: d_model=1024 d_ff=4096 E=8 top-1 T=8192 bf16; affinity on a 12-layer x 8192-token "
@@ -282,6 +415,9 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_median": float(np.median(per_step)),
+        "ms_per_step_min": float(per_step.min()),
+        "internal_warmup_steps": n_internal,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -298,15 +434,17 @@ def main():
     if not args.no_extra:
         # per-entry-point averages at the benchmark configuration
         per = {}
-        per["gate_ms"] = _time_call(layer.gate, 50)
-        per["dispatch_ms"] = _time_call(layer.dispatch, 50)
-        per["ffn_ms"] = _time_call(layer.ffn, 30)
-        per["combine_ms"] = _time_call(layer.combine, 50)
+        calls = [("gate", layer.gate), ("dispatch", layer.dispatch), ("ffn", layer.ffn)]
+        if not fused:
+            calls.append(("combine", layer.combine))
         if aff is not None:
-            per["affinity_statistics_ms"] = _time_call(aff.statistics, 50)
-            per["affinity_histogram_ms"] = _time_call(aff.histogram, 50)
-            per["placement_locality_ms"] = _time_call(aff.locality, 50)
-        layer_ms = per["gate_ms"] + per["dispatch_ms"] + per["ffn_ms"] + per["combine_ms"]
+            calls += [("affinity_statistics", aff.statistics), ("affinity_histogram", aff.histogram), ("placement_locality", aff.locality)]
+        for name, fn in calls:
+            st = _time_groups([fn], groups=10, inner=5 if name == "ffn" else 10)
+            per[name + "_ms"] = st["ms_median"]
+            per[name + "_ms_mean"] = st["ms"]
+            per[name + "_ms_min"] = st["ms_min"]
+        layer_ms = per["gate_ms"] + per["dispatch_ms"] + per["ffn_ms"] + per.get("combine_ms", 0.0)
         per["layer_tokens_per_s"] = cfg.T / (layer_ms * 1e-3)
         result["per_call"] = per
 
@@ -340,7 +478,19 @@ def main():
         loop_rand = loop_rate(rnd, 3)
         loop_rand_sustained = loop_rate(rnd, 40)
         del rnd
-        result["box"] = {"copy_GBps": copy_gbs, "mfma_loop_TFLOPs": mfma_tflops, "gemm_k_loop_zero_operands_TFLOPs": loop_zero,
+        # what the vendor GEMM library (through torch.matmul) sustains on this machine on random bf16 operands at
+        # the two contraction shapes of the benchmark configuration, as dense GEMMs of the same flop count:
+        # [8192,1024] x [4096,1024]^T (first contraction) and [8192,4096] x [1024,4096]^T (second)
+        ref_gemm = {}
+        if bf16:
+            for name, (m_, n_, k_) in (("gemm1_8192x4096x1024", (8192, 4096, 1024)), ("gemm2_8192x1024x4096", (8192, 1024, 4096))):
+                a_ = torch.randn((m_, k_), device=dev).to(torch.bfloat16)
+                b_ = (torch.randn((n_, k_), device=dev) * 0.02).to(torch.bfloat16)
+                c_ = torch.empty((m_, n_), dtype=torch.bfloat16, device=dev)
+                st = _time_groups([lambda: torch.matmul(a_, b_.t(), out=c_)], groups=10, inner=10)
+                ref_gemm[name + "_TFLOPs"] = 2.0 * m_ * n_ * k_ / (st["ms_median"] * 1e-3) / 1e12
+                del a_, b_, c_
+        result["box"] = {"torch_matmul_random_bf16": ref_gemm, "copy_GBps": copy_gbs, "mfma_loop_TFLOPs": mfma_tflops, "gemm_k_loop_zero_operands_TFLOPs": loop_zero,
                          "gemm_k_loop_random_operands_TFLOPs": loop_rand,
                          "gemm_k_loop_random_operands_sustained_TFLOPs": loop_rand_sustained}
         if roofline["bound"] == "mfma" and bf16:
@@ -359,25 +509,37 @@ def main():
         map4 = torch.from_numpy(map4_h).to(dev)
         outs = [B.moe_dispatch(xs4[i], idx4, c4.E, c4.E_local, map4) for i in range(sets)]
         ws = torch.empty(max(lib.moe_dispatch_workspace_bytes(T4, 1, c4.E_local), 256), dtype=torch.uint8, device=dev)
-        ms = _time_rotating(lambda i: (lambda: B.moe_dispatch(xs4[i], idx4, c4.E, c4.E_local, map4, out=outs[i], workspace=ws)),
-                            sets, 40)
+        stream = B._stream()
+        # (the library is called directly with plain addresses: a call is ~20-30 us on the GPU, the
+        # binding's argument checks would be a visible share of that on the host)
+
+        def disp_fn(i):
+            a = (xs4[i].data_ptr(), idx4.data_ptr(), map4.data_ptr(), T4, d4, 1, c4.E, c4.E_local, B.EXF_BF16, outs[i].x_sorted.data_ptr(),
+                 outs[i].src_of_sorted.data_ptr(), outs[i].sorted_of_src.data_ptr(), outs[i].expert_counts.data_ptr(),
+                 outs[i].expert_offsets.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+            return lambda: lib.moe_dispatch(*a)
+
         bytes_disp = T4 * d4 * 2 * 2 + T4 * 16
-        hbm["dispatch"] = {"ms": ms, "GBps": bytes_disp / (ms * 1e-3) / 1e9, "frac": bytes_disp / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                           "bytes": bytes_disp}
+        hbm["dispatch"] = _hbm_entry(disp_fn, sets, bytes_disp)
         w4 = torch.rand((T4, 1), device=dev)
         couts = [torch.empty((T4, d4), dtype=torch.bfloat16, device=dev) for _ in range(sets)]
-        ms = _time_rotating(lambda i: (lambda: B.moe_combine(outs[i].x_sorted, outs[i].sorted_of_src, w4, out=couts[i])), sets, 40)
+
+        def comb_fn(i):
+            a = (outs[i].x_sorted.data_ptr(), outs[i].sorted_of_src.data_ptr(), w4.data_ptr(), T4, d4, 1, B.EXF_BF16, couts[i].data_ptr(), stream)
+            return lambda: lib.moe_combine(*a)
+
         bytes_comb = T4 * d4 * 2 * 2 + T4 * 12
-        hbm["combine"] = {"ms": ms, "GBps": bytes_comb / (ms * 1e-3) / 1e9, "frac": bytes_comb / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                          "bytes": bytes_comb}
+        hbm["combine"] = _hbm_entry(comb_fn, sets, bytes_comb)
         gw4 = torch.randn((c4.E, d4), device=dev).to(torch.bfloat16)
         gi = torch.empty((T4, 1), dtype=torch.int32, device=dev)
         gwt = torch.empty((T4, 1), dtype=torch.float32, device=dev)
-        ms = _time_rotating(lambda i: (lambda: lib.moe_gate_topk(xs4[i].data_ptr(), gw4.data_ptr(), T4, d4, c4.E, 1, 0, B.EXF_BF16,
-                                                                 None, gi.data_ptr(), gwt.data_ptr(), B._stream())), sets, 40)
+
+        def gate_fn(i):
+            a = (xs4[i].data_ptr(), gw4.data_ptr(), T4, d4, c4.E, 1, 0, B.EXF_BF16, None, gi.data_ptr(), gwt.data_ptr(), stream)
+            return lambda: lib.moe_gate_topk(*a)
+
         bytes_gate = T4 * d4 * 2 + c4.E * d4 * 2 + T4 * 8
-        hbm["gate"] = {"ms": ms, "GBps": bytes_gate / (ms * 1e-3) / 1e9, "frac": bytes_gate / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                       "bytes": bytes_gate}
+        hbm["gate"] = _hbm_entry(gate_fn, sets, bytes_gate)
         del xs4, outs, couts
         tr4_h, _ = syn.config_trace(c4)
         pl4 = torch.from_numpy(syn.balanced_random_placement(c4.trace_L, c4.trace_E, c4.G, syn.seed_for(4, 5))).to(dev)
@@ -386,15 +548,10 @@ def main():
         traces = [base] + [base.roll(shifts=7 * (i + 1), dims=1).contiguous() for i in range(tr_sets - 1)]
         aff4 = AffinityRun(base, pl4, c4.trace_E, c4.G)
         bytes_tr = 4 * c4.trace_L * c4.trace_N
-        ms = _time_rotating(lambda i: (lambda: aff4.histogram(traces[i])), tr_sets, 30)
-        hbm["affinity_histogram"] = {"ms": ms, "GBps": bytes_tr / (ms * 1e-3) / 1e9, "frac": bytes_tr / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                     "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
-        ms = _time_rotating(lambda i: (lambda: aff4.locality(traces[i])), tr_sets, 30)
-        hbm["placement_locality"] = {"ms": ms, "GBps": bytes_tr / (ms * 1e-3) / 1e9, "frac": bytes_tr / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                     "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
-        ms = _time_rotating(lambda i: (lambda: aff4.statistics(traces[i])), tr_sets, 30)
-        hbm["affinity_statistics"] = {"ms": ms, "GBps": bytes_tr / (ms * 1e-3) / 1e9, "frac": bytes_tr / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                      "bytes": bytes_tr, "trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
+        tok = lambda ms: {"trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
+        hbm["affinity_histogram"] = _hbm_entry(lambda i: (lambda: aff4.histogram(traces[i])), tr_sets, bytes_tr, tok)
+        hbm["placement_locality"] = _hbm_entry(lambda i: (lambda: aff4.locality(traces[i])), tr_sets, bytes_tr, tok)
+        hbm["affinity_statistics"] = _hbm_entry(lambda i: (lambda: aff4.statistics(traces[i])), tr_sets, bytes_tr, tok)
         result["hbm_bound_calls_config4_shapes"] = hbm
 
         # placement search on the one-GPU-share trace (24 layers x 1M tokens, E=64, 8 GPUs on 2 nodes):
@@ -418,22 +575,24 @@ def main():
         gh.manual_seed(syn.seed_for(4, 7))
         home4 = torch.randint(0, c4.G, (c4.trace_N,), generator=gh, dtype=torch.int32).to(dev)
         ws_rt = torch.empty(max(lib.routing_transfers_workspace_bytes(c4.trace_L, c4.trace_N), 256), dtype=torch.uint8, device=dev)
-        visits = float(c4.trace_N) * c4.trace_L
         ratios = {}
+        # p and p* of the trace and the forward communication volumes of the paper's comparison table for it
+        # (G GPUs holding trace_N / G tokens each, L MoE layers; the top-2 columns use the same ratios)
         for name, pl_t in (("found", cands[0]), ("contiguous", cands[1])):
             loc_t, away_t = B.routing_transfers(base, pl_t.contiguous(), home4, c4.G, workspace=ws_rt)
-            away_sum, loc_sum, away0 = float(away_t.sum()), float(loc_t.sum()), float(away_t[0])
-            ratios[name] = {"vanilla_p": away_sum / visits, "coherent_p_star": (away0 + total - loc_sum) / visits,
-                            "transfers_vanilla": 2.0 * away_sum, "transfers_coherent": away0 + total - loc_sum}
-        ms_rt = _time_rotating(lambda i: (lambda: B.routing_transfers(traces[i], cands[0], home4, c4.G, workspace=ws_rt)), tr_sets, 30)
-        bytes_rt = bytes_tr + 4 * c4.trace_N
-        result["routing_transfers"] = {"ms": ms_rt, "GBps": bytes_rt / (ms_rt * 1e-3) / 1e9,
-                                       "frac": bytes_rt / (ms_rt * 1e-3) / 1e9 / PEAK_HBM_GBS, "bytes": bytes_rt,
-                                       "alltoall_token_ratio": ratios}
+            p_van, p_star = B.transfer_ratios(away_t.cpu(), loc_t.cpu(), c4.trace_N)
+            vol = B.comm_volume(c4.G, c4.trace_N // c4.G, c4.trace_L, p_van, p_star)
+            ratios[name] = {"vanilla_p": p_van, "coherent_p_star": p_star, "volume_tokens": vol,
+                            "coherent_over_vanilla_top1": vol["coherent_top1"] / vol["vanilla_top1"]}
+        rt = _hbm_entry(lambda i: (lambda: B.routing_transfers(traces[i], cands[0], home4, c4.G, workspace=ws_rt)), tr_sets,
+                        bytes_tr + 4 * c4.trace_N)
+        rt["alltoall_token_ratio"] = ratios
+        result["routing_transfers"] = rt
         # affinity across several layers: all 276 ordered layer pairs of the same trace
         ws_mh = torch.empty(max(lib.affinity_multihop_workspace_bytes(c4.trace_L, c4.trace_N, c4.trace_E), 256), dtype=torch.uint8,
                             device=dev)
-        ms_mh = _time_rotating(lambda i: (lambda: B.affinity_multihop(traces[i], c4.trace_E, want_prob=True, workspace=ws_mh)), tr_sets, 5)
+        ms_mh = _time_groups([(lambda i: (lambda: B.affinity_multihop(traces[i], c4.trace_E, want_prob=True, workspace=ws_mh)))(i)
+                              for i in range(tr_sets)], groups=4, inner=3, warmup=3)["ms_median"]
         n_pairs = c4.trace_L * (c4.trace_L - 1) // 2
         result["affinity_multihop"] = {"ms": ms_mh, "layer_pairs": n_pairs, "pair_transitions_per_s": n_pairs * c4.trace_N / (ms_mh * 1e-3),
                                        "trace_bytes": bytes_tr, "workspace_bytes": ws_mh.numel()}
@@ -444,8 +603,12 @@ def main():
             "gpu_locality": {"found": sc[0] / total, "contiguous": sc[1] / total, "random": sc[2] / total},
             "node_locality": {"found": node_sc[0] / total, "contiguous": node_sc[1] / total, "random": node_sc[2] / total}}
 
+    if not args.no_extra and cfg.index == 2 and fused:
+        result["other_configs"] = other_configs(syn, torch, MoELayerRun, dev)
+
     if not args.no_cpu_baseline and host is not None:
         result["cpu_baseline"] = cpu_baseline(cfg, host[0], host[1], host[2], host[3], trace_h, pl_h)
+        result["cpu_baseline"]["single_thread"] = cpu_baseline_single_thread(cfg, host[0], host[1], host[2], host[3])
     else:
         result["cpu_baseline"] = None
 

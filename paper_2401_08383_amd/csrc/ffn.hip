@@ -77,12 +77,21 @@ enum Epilogue { kEpiNone = 0, kEpiGeluErf = 1, kEpiGeluTanh = 2 };
 constexpr int kTailRows = 64;
 __host__ __device__ constexpr int max_tail_tiles(int mt) { return mt / 2 >= kTailRows ? (mt / 2 + kTailRows - 1) / kTailRows : 1; }
 constexpr int kXcdChunk = 32;  // consecutive tiles handed to one XCD at a time: one per compute unit of the XCD
+constexpr int kLdsBytes = 160 * 1024;  // LDS of a compute unit
+// A tile configuration can run tall tiles (MT + kTailRows rows) if its wavefront rows still split into
+// 32-row MFMA tiles and the taller stages still fit the LDS.
+__host__ __device__ constexpr bool tall_tiles_supported(int mt, int nt, int kt, int stages, int wm)
+{
+    return mt > kTailRows && ((mt + kTailRows) / wm) % 32 == 0 && (mt + kTailRows) % wm == 0 &&
+           stages * (mt + kTailRows + nt) * kt * 2 <= kLdsBytes;
+}
 
 struct Tile2D {
     int expert;
     int row_begin, row_end;
     int n_tile;
     bool tail;
+    bool tall;             // a full tile extended by kTailRows rows (see TileSchedule)
     int kt_begin, kt_end;  // K tiles [kt_begin, kt_end) of the reduction this workgroup sums
     int slot;              // >= 0: the sum goes to partial-sum slot `slot` (a K slice of a tail tile)
 };
@@ -114,16 +123,26 @@ __device__ __forceinline__ int tile_index_of_workgroup(int wg)
 }
 
 // Per-expert tile counts (lane e = expert e) and their running sums; the same in every workgroup.
+//
+// "Tall" tiles.  A remainder of r <= MT/2 rows costs far more as tail tiles than its share of the work:
+// a tail tile does a quarter of the MFMA work of a full tile but loads the same weight panel, pays
+// the same tile start-up, and takes half as long as a full tile.  When the launch runs at least
+// kTallMinRounds rounds of full tiles (every compute unit gets several tiles, so one longer tile
+// does not decide the end of the launch), the remainder is instead folded into the expert's last full
+// tiles: ceil(r/64) of them become MT + 64 rows tall (same weight panel, same start-up, same K loop
+// with one more 32-row MFMA tile per wavefront).  Tall tiles are numbered first: longest work first.
+constexpr int kTallMinRounds = 2;
 struct TileSchedule {
     int lo, hi;              // this lane's expert: clamped row range
     int full_rt, tail_rt;    //   its full and tail row tiles
-    int full_incl, tail_incl;
-    int total_full, total_tail;
+    int tall_rt;             //   its tall row tiles (they follow the full ones in the row order)
+    int full_incl, tail_incl, tall_incl;
+    int total_full, total_tail, total_tall;
     int split;               // K slices per tail tile
 };
 
 __device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles,
-                                                     int max_rows, int nk, bool may_split)
+                                                     int max_rows, int nk, bool may_split, bool allow_tall)
 {
     TileSchedule sc;
     const int lane = lane_id();
@@ -134,8 +153,14 @@ __device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__
         sc.hi = min(max(offsets[lane + 1], sc.lo), max_rows);
     }
     const int cnt = sc.hi - sc.lo;
-    sc.full_rt = cnt / mt;
-    sc.tail_rt = (cnt - sc.full_rt * mt + kTailRows - 1) / kTailRows;
+    const int q = cnt / mt;
+    const int need = (cnt - q * mt + kTailRows - 1) / kTailRows;  // 64-row blocks of the remainder
+    bool use_tall = false;
+    if (allow_tall)  // rounds of the launch, counted in row tiles of mt rows (a ragged last one included)
+        use_tall = __shfl(wave_inclusive_scan((cnt + mt - 1) / mt * n_tiles), kWave - 1, kWave) >= kTallMinRounds * kSplitUnits;
+    sc.tall_rt = (use_tall && need > 0 && need <= max_tail_tiles(mt) && need <= q) ? need : 0;
+    sc.full_rt = q - sc.tall_rt;
+    sc.tail_rt = sc.tall_rt > 0 ? 0 : need;
     if (sc.tail_rt > max_tail_tiles(mt)) {
         sc.full_rt += 1;
         sc.tail_rt = 0;
@@ -144,18 +169,26 @@ __device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__
     sc.tail_incl = wave_inclusive_scan(sc.tail_rt * n_tiles);
     sc.total_full = __shfl(sc.full_incl, kWave - 1, kWave);
     sc.total_tail = __shfl(sc.tail_incl, kWave - 1, kWave);
+    sc.tall_incl = 0;
+    sc.total_tall = 0;
+    if (use_tall) {
+        sc.tall_incl = wave_inclusive_scan(sc.tall_rt * n_tiles);
+        sc.total_tall = __shfl(sc.tall_incl, kWave - 1, kWave);
+    }
     int split = 1;
     if (may_split && sc.total_tail > 0) split = max(1, min(min(kSplitUnits / sc.total_tail, nk / kSplitMinKTiles), kSplitMax));
     sc.split = __builtin_amdgcn_readfirstlane(split);
     return sc;
 }
 
-// Tile j of the full (tail = false) or tail tiles -> expert, rows, column tile.
-__device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local, int mt, int n_tiles, bool tail, int j, Tile2D& out)
+// Tile j of one kind (kTileFull, kTileTail, kTileTall) -> expert, rows, column tile.
+enum TileKind { kTileFull = 0, kTileTail = 1, kTileTall = 2 };
+__device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local, int mt, int n_tiles, int kind, int j, Tile2D& out)
 {
     const int lane = lane_id();
-    const int incl = tail ? sc.tail_incl : sc.full_incl;
-    const int rt = tail ? sc.tail_rt : sc.full_rt;
+    const bool tail = kind == kTileTail, tall = kind == kTileTall;
+    const int incl = tail ? sc.tail_incl : (tall ? sc.tall_incl : sc.full_incl);
+    const int rt = tail ? sc.tail_rt : (tall ? sc.tall_rt : sc.full_rt);
     const int excl = incl - rt * n_tiles;
     const unsigned long long m = __ballot(lane < E_local && j >= excl && j < incl);
     if (m == 0ull) return false;
@@ -171,7 +204,7 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
     // follow each other.  Remaining row tiles (and small experts) run row tile fastest.
     constexpr int kBlockRows = 4, kBlockCols = kXcdChunk / kBlockRows;
     int row_tile, col_tile;
-    const int blocked_rows = (!tail && n_tiles % kBlockCols == 0) ? e_rt / kBlockRows * kBlockRows : 0;
+    const int blocked_rows = (kind == kTileFull && n_tiles % kBlockCols == 0) ? e_rt / kBlockRows * kBlockRows : 0;
     if (r < blocked_rows * n_tiles) {
         const int per_row_block = kBlockRows * n_tiles;
         const int rbk = r / per_row_block, in_rb = r - rbk * per_row_block;
@@ -183,13 +216,17 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
         col_tile = rr / rows_left;
         row_tile = blocked_rows + rr % rows_left;
     }
-    const int begin = tail ? e_lo + e_full * mt + row_tile * kTailRows : e_lo + row_tile * mt;
+    // rows of an expert: its full tiles, then its tall tiles (or its tail tiles)
+    const int begin = tail ? e_lo + e_full * mt + row_tile * kTailRows
+                           : (tall ? e_lo + e_full * mt + row_tile * (mt + kTailRows) : e_lo + row_tile * mt);
+    const int height = tail ? kTailRows : (tall ? mt + kTailRows : mt);
     // every lane holds the same values; readfirstlane tells the compiler so (scalar registers)
     out.expert = __builtin_amdgcn_readfirstlane(src);
     out.n_tile = __builtin_amdgcn_readfirstlane(col_tile);
     out.row_begin = __builtin_amdgcn_readfirstlane(begin);
-    out.row_end = __builtin_amdgcn_readfirstlane(min(begin + (tail ? kTailRows : mt), e_hi));
+    out.row_end = __builtin_amdgcn_readfirstlane(min(begin + height, e_hi));
     out.tail = tail;
+    out.tall = tall;
     return true;
 }
 
@@ -198,19 +235,21 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
 // tiles the few compute units that get a tail tile at the very end would decide when the launch is
 // over.  Many tail items: they go last and fill the ragged end of the last round of full tiles.
 __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles, int max_rows,
-                                            int nk, bool may_split, int idx, Tile2D& out)
+                                            int nk, bool may_split, bool allow_tall, int idx, Tile2D& out)
 {
-    const TileSchedule sc = scan_experts(offsets, E_local, mt, n_tiles, max_rows, nk, may_split);
+    const TileSchedule sc = scan_experts(offsets, E_local, mt, n_tiles, max_rows, nk, may_split, allow_tall);
+    out.kt_begin = 0;
+    out.kt_end = nk;
+    out.slot = -1;
+    if (idx < sc.total_tall) return decode_tile(sc, E_local, mt, n_tiles, kTileTall, idx, out);  // longest work first
+    idx -= sc.total_tall;
     const int tail_units = sc.total_tail * sc.split;
     if (idx >= sc.total_full + tail_units) return false;
     const bool tails_first = tail_units <= kSplitUnits;
     const bool tail = tails_first ? idx < tail_units : idx >= sc.total_full;
     const int u = tails_first ? idx : idx - sc.total_full;
     const int full_idx = tails_first ? idx - tail_units : idx;
-    if (!decode_tile(sc, E_local, mt, n_tiles, tail, tail ? u / sc.split : full_idx, out)) return false;
-    out.kt_begin = 0;
-    out.kt_end = nk;
-    out.slot = -1;
+    if (!decode_tile(sc, E_local, mt, n_tiles, tail ? kTileTail : kTileFull, tail ? u / sc.split : full_idx, out)) return false;
     if (tail && sc.split > 1) {
         const int slice = u % sc.split;
         out.kt_begin = __builtin_amdgcn_readfirstlane(slice * nk / sc.split);
@@ -508,7 +547,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     // Writing that straight to memory would touch 32 rows per store instruction, so every
     // wavefront transposes its tile through its own slice of the (now idle) LDS ring, 64 rows at a
     // time, and stores whole 16-byte chunks of contiguous row segments.
-    constexpr int BP = TM >= 2 ? 2 : 1;            // 32-row MFMA tiles per pass
+    constexpr int BP = (TM >= 2 && TM % 2 == 0) ? 2 : 1;  // 32-row MFMA tiles per pass
     constexpr int ROW_BYTES = WTN * 2;
     constexpr int S = ROW_BYTES + 8;               // padded LDS row stride: conflict-free 8-byte writes
     constexpr int REGION = BP * 32 * S;
@@ -622,12 +661,18 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
     }
     Tile2D tile;
     const int n_tiles = (N + NT - 1) / NT;
-    if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, K / KT, partial != nullptr && MT > kTailRows,
+    constexpr bool TALL = tall_tiles_supported(MT, NT, KT, STAGES, WM);
+    if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, K / KT, partial != nullptr && MT > kTailRows, TALL,
                      tile_index_of_workgroup(blockIdx.x), tile))
         return;
     const bf16_t* wexp = weight + static_cast<size_t>(tile.expert) * N * K;
     const bf16_t* bias_e = BIAS ? bias + static_cast<size_t>(tile.expert) * N : nullptr;
-    if (!tile.tail || MT <= kTailRows) {
+    if (tile.tall) {
+        if constexpr (TALL)
+            gemm_tile<MT + kTailRows, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS, false>(act, wexp, bias_e, tile.row_begin, tile.row_end,
+                                                                                     tile.n_tile * NT, K, N, out, smem, map, 0, K / KT,
+                                                                                     nullptr);
+    } else if (!tile.tail || MT <= kTailRows) {
         gemm_tile<MT, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS, false>(act, wexp, bias_e, tile.row_begin, tile.row_end,
                                                                      tile.n_tile * NT, K, N, out, smem, map, 0, K / KT, nullptr);
     } else if constexpr (MT > kTailRows) {
@@ -652,7 +697,7 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
 // were written (1 KiB per wavefront and load), all slices requested at once, and summed in slice
 // order.  Does nothing when the launch before it did not split (the same schedule is derived from
 // expert_offsets).
-template <int MT, int NT, int KT, int WM, int WN, int EPI, bool BIAS>
+template <int MT, int NT, int KT, int WM, int WN, bool TALL, int EPI, bool BIAS>
 __global__ __launch_bounds__(WM* WN * 64) void tail_reduce_bf16_kernel(const int32_t* __restrict__ offsets,
                                                                         const bf16_t* __restrict__ bias,  // [E_local,N] or null
                                                                         int max_rows, int K, int N, int E_local,
@@ -665,11 +710,11 @@ __global__ __launch_bounds__(WM* WN * 64) void tail_reduce_bf16_kernel(const int
     constexpr int GROUPS = TN * TM * 4;
     constexpr int SLOT = kTailRows * NT / 4;  // float4 per slice
     const int n_tiles = (N + NT - 1) / NT;
-    const TileSchedule sc = scan_experts(offsets, E_local, MT, n_tiles, max_rows, K / KT, true);
+    const TileSchedule sc = scan_experts(offsets, E_local, MT, n_tiles, max_rows, K / KT, true, TALL);
     const int j = blockIdx.x / GROUPS, q = blockIdx.x % GROUPS;
     if (sc.split <= 1 || j >= sc.total_tail) return;
     Tile2D tile;
-    if (!decode_tile(sc, E_local, MT, n_tiles, true, j, tile)) return;
+    if (!decode_tile(sc, E_local, MT, n_tiles, kTileTail, j, tile)) return;
     const int a = q / (TM * 4), b = (q / 4) % TM, g = q % 4;
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -798,7 +843,7 @@ template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int OCC>
 static int launch_bf16(const void* act, const int32_t* offsets, const void* weight, const void* bias, int64_t A, int K, int N,
                        int E_local, int epi, void* out, hipStream_t stream, const RowMap& map = RowMap{}, void* partial = nullptr)
 {
-    constexpr size_t lds = static_cast<size_t>(STAGES) * (MT + NT) * KT * 2;
+    constexpr size_t lds = static_cast<size_t>(STAGES) * (MT + (tall_tiles_supported(MT, NT, KT, STAGES, WM) ? kTailRows : 0) + NT) * KT * 2;
     static_assert(NT <= kSplitMaxCols, "a partial-sum slot holds kTailRows x kSplitMaxCols values");
     // worst case: A/MT unmasked row tiles plus, for every expert, its tail tiles or one masked tile;
     // cutting tail tiles into K slices adds fewer than kSplitUnits work items
@@ -821,7 +866,7 @@ static int launch_bf16(const void* act, const int32_t* offsets, const void* weig
                            static_cast<const bf16_t*>(bias), static_cast<int>(A), K, N, E_local, static_cast<bf16_t*>(out),     \
                            map, static_cast<float4*>(partial));                                                                 \
         if (partial != nullptr && MT > kTailRows && K / KT >= 2 * kSplitMinKTiles)                                              \
-            hipLaunchKernelGGL((tail_reduce_bf16_kernel<MT, NT, KT, WM, WN, EPI, BIAS>),                                        \
+            hipLaunchKernelGGL((tail_reduce_bf16_kernel<MT, NT, KT, WM, WN, tall_tiles_supported(MT, NT, KT, STAGES, WM), EPI, BIAS>),                                        \
                                dim3(kSplitUnits / 2 * (kTailRows * NT / (WM * WN * 64 * 4))),                                   \
                                dim3(WM* WN * 64), 0, stream, offsets, static_cast<const bf16_t*>(bias), static_cast<int>(A), K, \
                                N, E_local, static_cast<const float4*>(partial), static_cast<bf16_t*>(out), map);                \

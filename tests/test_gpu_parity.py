@@ -208,6 +208,20 @@ def test_ffn_bf16_wide_second_contraction(oracle):
     _ffn_case(oracle, "bf16", counts, 1088, 128, 1, False, seed=452, rows=rows)
 
 
+@pytest.mark.parametrize("bias", [False, True])
+def test_ffn_bf16_tall_tiles(oracle, bias):
+    """Launches with two or more rounds of 256-row tiles fold small remainders into taller last tiles
+    of the expert (320 rows): remainders of 1, 64, 65 and 128 rows (one and two tall tiles), 129 rows (a
+    masked full tile instead), a remainder larger than the expert's full tiles can take (tail tiles),
+    experts without a full tile.  Every element against the oracle; first contraction (wide hidden
+    layer), then second contraction (wide output)."""
+    counts = [6 * 256 + 1, 3 * 256 + 65, 2 * 256 + 128, 5 * 256 + 129, 256 + 44, 256 + 100, 200, 100, 0, 2 * 256 + 64]
+    _say(f"ffn bf16 tall tiles bias={bias}: first contraction")
+    _ffn_case(oracle, "bf16", counts, 64, 8192, 0, bias, seed=460)
+    _say(f"ffn bf16 tall tiles bias={bias}: second contraction")
+    _ffn_case(oracle, "bf16", counts, 8192, 64, 1, bias, seed=461)
+
+
 def test_ffn_bf16_many_experts_skewed(oracle):
     _say("ffn bf16 skewed 32 experts")
     tr, _ = syn.planted_trace(1, 3000, 32, 0.0, seed=420, marginal="zipf")
