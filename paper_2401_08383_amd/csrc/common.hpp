@@ -102,16 +102,63 @@ __device__ __forceinline__ T wave_sum(T v)
     return v;
 }
 
-// Inclusive prefix sum across the 64 lanes of a wavefront.
+// Inclusive prefix sum across the 64 lanes of a wavefront, on the cross-lane data path of the vector
+// ALU (a shuffle goes through the LDS pipeline and costs a round trip of its own per step; a tile
+// lookup runs several scans in a row before a workgroup can request its first operand).  Steps 1-4 add
+// the lanes 1, 2, 4 and 8 to the right inside every row of 16 lanes (zero shifted in at a row's
+// start), step 5 adds lane 15 of rows 0 and 2 to rows 1 and 3, step 6 lane 31 to rows 2 and 3.
 __device__ __forceinline__ int wave_inclusive_scan(int v)
 {
-    const int lane = lane_id();
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        int n = __shfl_up(v, off, kWave);
-        if (lane >= off) v += n;
-    }
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
     return v;
+}
+
+// Value of `v` in lane `src`, where src is the same in every lane (read on the scalar path).
+__device__ __forceinline__ int wave_read_lane(int v, int src)
+{
+    return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(src));
+}
+
+// ---- "the workgroup that finishes last adds up" ------------------------------------------------
+// A reduction kernel whose workgroups each leave a partial result can do without a second launch
+// (a dependent launch costs about 5 us here, a quarter of a 100 MB streaming pass): every workgroup
+// publishes its partials, takes a ticket, and the one that draws the last ticket reads all partials
+// back and writes the result.  The ticket is a 64-bit word in the caller's workspace that holds
+// (epoch << 24 | arrivals); the host hands every call a fresh epoch (next_epoch(), unique within the
+// process and started from a random value), so the word needs no clearing: a workgroup that finds
+// another epoch in it - a previous call's, or whatever the buffer held - restarts the count at one.
+// Compare-and-swap until it sticks; every failure means another workgroup got through, so the loop
+// ends after at most n_wg rounds and waits for nobody.
+constexpr int kTicketCountBits = 24;  // workgroups per launch stay below 2^24
+unsigned long long next_epoch();      // host: the epoch of one call (40 bits, never 0)
+
+// Call with ALL threads of the workgroup, after the partial results were stored.  Returns true in
+// every thread of exactly one workgroup of the launch, after all workgroups' partials are visible.
+__device__ __forceinline__ bool last_workgroup_of_launch(unsigned long long* ticket, unsigned long long epoch, unsigned n_wg)
+{
+    __shared__ int exf_is_last;
+    __threadfence();  // release: this thread's partial results are visible to the whole device
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long cur = __hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long want;
+        for (;;) {
+            want = (cur >> kTicketCountBits) == epoch ? cur + 1ull : ((epoch << kTicketCountBits) | 1ull);
+            const unsigned long long old = atomicCAS(ticket, cur, want);
+            if (old == cur) break;
+            cur = old;
+        }
+        exf_is_last = (want & ((1ull << kTicketCountBits) - 1ull)) == n_wg ? 1 : 0;
+    }
+    __syncthreads();
+    const bool last = exf_is_last != 0;
+    if (last) __threadfence();  // acquire: no stale copy of the others' partials is read below
+    return last;
 }
 
 // Which expert owns row-tile `tile` when every expert's rows [off[e], off[e+1]) are cut into
@@ -141,7 +188,7 @@ __device__ __forceinline__ TileRef locate_row_tile(const int32_t* __restrict__ o
     const bool mine = (lane < E_local) && (tile >= excl) && (tile < incl);
     const unsigned long long m = __ballot(mine);
     TileRef r;
-    r.total = __shfl(incl, kWave - 1, kWave);
+    r.total = wave_read_lane(incl, kWave - 1);
     if (m == 0ull) {
         r.expert = -1;
         r.row_begin = 0;
@@ -149,9 +196,9 @@ __device__ __forceinline__ TileRef locate_row_tile(const int32_t* __restrict__ o
         return r;
     }
     const int src = __ffsll(static_cast<long long>(m)) - 1;
-    const int e_lo = __shfl(lo, src, kWave);
-    const int e_hi = __shfl(hi, src, kWave);
-    const int e_excl = __shfl(excl, src, kWave);
+    const int e_lo = wave_read_lane(lo, src);
+    const int e_hi = wave_read_lane(hi, src);
+    const int e_excl = wave_read_lane(excl, src);
     r.expert = src;
     r.row_begin = e_lo + (tile - e_excl) * mt;
     r.row_end = min(r.row_begin + mt, e_hi);

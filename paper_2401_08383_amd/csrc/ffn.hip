@@ -157,7 +157,7 @@ __device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__
     const int need = (cnt - q * mt + kTailRows - 1) / kTailRows;  // 64-row blocks of the remainder
     bool use_tall = false;
     if (allow_tall)  // rounds of the launch, counted in row tiles of mt rows (a ragged last one included)
-        use_tall = __shfl(wave_inclusive_scan((cnt + mt - 1) / mt * n_tiles), kWave - 1, kWave) >= kTallMinRounds * kSplitUnits;
+        use_tall = wave_read_lane(wave_inclusive_scan((cnt + mt - 1) / mt * n_tiles), kWave - 1) >= kTallMinRounds * kSplitUnits;
     sc.tall_rt = (use_tall && need > 0 && need <= max_tail_tiles(mt) && need <= q) ? need : 0;
     sc.full_rt = q - sc.tall_rt;
     sc.tail_rt = sc.tall_rt > 0 ? 0 : need;
@@ -167,13 +167,13 @@ __device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__
     }
     sc.full_incl = wave_inclusive_scan(sc.full_rt * n_tiles);
     sc.tail_incl = wave_inclusive_scan(sc.tail_rt * n_tiles);
-    sc.total_full = __shfl(sc.full_incl, kWave - 1, kWave);
-    sc.total_tail = __shfl(sc.tail_incl, kWave - 1, kWave);
+    sc.total_full = wave_read_lane(sc.full_incl, kWave - 1);
+    sc.total_tail = wave_read_lane(sc.tail_incl, kWave - 1);
     sc.tall_incl = 0;
     sc.total_tall = 0;
     if (use_tall) {
         sc.tall_incl = wave_inclusive_scan(sc.tall_rt * n_tiles);
-        sc.total_tall = __shfl(sc.tall_incl, kWave - 1, kWave);
+        sc.total_tall = wave_read_lane(sc.tall_incl, kWave - 1);
     }
     int split = 1;
     if (may_split && sc.total_tail > 0) split = max(1, min(min(kSplitUnits / sc.total_tail, nk / kSplitMinKTiles), kSplitMax));
@@ -193,11 +193,11 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
     const unsigned long long m = __ballot(lane < E_local && j >= excl && j < incl);
     if (m == 0ull) return false;
     const int src = __ffsll(static_cast<long long>(m)) - 1;
-    const int e_lo = __shfl(sc.lo, src, kWave);
-    const int e_hi = __shfl(sc.hi, src, kWave);
-    const int e_rt = __shfl(rt, src, kWave);
-    const int e_full = __shfl(sc.full_rt, src, kWave);
-    const int r = j - __shfl(excl, src, kWave);
+    const int e_lo = wave_read_lane(sc.lo, src);
+    const int e_hi = wave_read_lane(sc.hi, src);
+    const int e_rt = wave_read_lane(rt, src);
+    const int e_full = wave_read_lane(sc.full_rt, src);
+    const int r = j - wave_read_lane(excl, src);
     // Order of the expert's tiles.  With many row tiles, consecutive tiles form blocks of kBlockRows
     // row tiles x kBlockCols column tiles (one XCD chunk): the 32 workgroups of a block share 4
     // activation and 8 weight panels in their L2, against 16 and 2 when the rows of a column simply

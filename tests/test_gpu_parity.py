@@ -495,3 +495,37 @@ def test_repeat_calls_are_deterministic():
         o = exf.moe_expert_ffn_fused(xs, disp.src_of_sorted, disp.sorted_of_src, gate, disp.expert_offsets, w1, w2, workspace=ws)
         outs.append((y.clone(), o.clone()))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+def test_single_launch_reductions_need_no_clean_workspace(oracle):
+    """placement_locality and routing_transfers add their per-chunk counts up in the workgroup that
+    finishes last, found through a ticket word in the workspace that is never cleared: many calls in a
+    row on one workspace, of changing size, with the workspace filled with zeros, ones, and whatever
+    the previous call left, must all give the oracle's counts."""
+    _say("single-launch reductions: ticket robustness")
+    L, E, G = 7, 32, 4
+    g = syn.rng(730)
+    cases = []
+    for N in (300000, 4096, 1, 70001, 300000):
+        trace = g.integers(0, E, size=(L, N)).astype(np.int32)
+        pl = syn.balanced_random_placement(L, E, G, 731 + N % 7)
+        home = g.integers(0, G, size=N).astype(np.int32)
+        cases.append((dev_i32(trace).reshape(L, N), dev_i32(pl).reshape(L, E), dev_i32(home), oracle.placement_locality(trace, pl),
+                      oracle.routing_away(trace, pl, home)))
+    nbytes = max(exf.lib().routing_transfers_workspace_bytes(L, 300000), exf.lib().placement_locality_workspace_bytes(L, 300000))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    for rep in range(12):
+        if rep < 3:
+            ws.fill_((0, 255, 1)[rep])
+        for t, p, h, loc_ref, away_ref in cases:
+            loc = exf.placement_locality(t, p, G, workspace=ws)
+            np.testing.assert_array_equal(loc.cpu().numpy(), loc_ref)
+            loc2, away = exf.routing_transfers(t, p, h, G, workspace=ws)
+            np.testing.assert_array_equal(loc2.cpu().numpy(), loc_ref)
+            np.testing.assert_array_equal(away.cpu().numpy(), away_ref)
+    # back to back without host synchronisation in between: 50 calls queued on the stream, every result kept
+    t, p, h, loc_ref, away_ref = cases[0]
+    outs = [exf.placement_locality(t, p, G, workspace=ws) for _ in range(50)]
+    torch.cuda.synchronize()
+    for o in outs:
+        np.testing.assert_array_equal(o.cpu().numpy(), loc_ref)
