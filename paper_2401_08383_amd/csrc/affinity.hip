@@ -23,7 +23,7 @@
 //   a workgroup owns a chunk of tokens for ALL layers (each trace entry is read exactly once),
 //   maps expert -> device through an LDS copy of the placement, keeps the loads of four layers in
 //   flight, and counts per pair the tokens whose device does not change; per-chunk partial counts
-//   are summed by the workgroup of the same launch that finishes last (no second launch).
+//   are summed by a second kernel.
 #include "common.hpp"
 
 namespace exf {
@@ -482,9 +482,7 @@ template <int VEC, bool HOME>
 __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const int32_t* __restrict__ trace,
                                                                           const int32_t* __restrict__ placement,
                                                                           const int32_t* __restrict__ home, int L, int64_t N, int E,
-                                                                          int64_t chunk, uint32_t* part, unsigned long long* ticket,
-                                                                          unsigned long long epoch, int64_t* __restrict__ local_per_pair,
-                                                                          int64_t* __restrict__ away_per_layer)
+                                                                          int64_t chunk, uint32_t* __restrict__ part)
 {
     extern __shared__ int32_t lds_i[];
     int32_t* pl = lds_i;                                              // [L][E]
@@ -577,23 +575,10 @@ __global__ __launch_bounds__(kTraceThreads) void locality_partial_kernel(const i
     }
     __syncthreads();
     for (int i = threadIdx.x; i < n_out; i += kTraceThreads) part[static_cast<size_t>(blockIdx.x) * n_out + i] = pair_cnt[i];
-    // the workgroup that finishes last sums the per-chunk counts: wavefront w takes the outputs w, w + 16, ...
-    if (!last_workgroup_of_launch(ticket, epoch, gridDim.x)) return;
-    const int C = static_cast<int>(gridDim.x);
-    for (int j = threadIdx.x / kWave; j < n_out; j += kTraceThreads / kWave) {
-        long long s = 0;
-        for (int c = lane; c < C; c += kWave) s += part[static_cast<size_t>(c) * n_out + j];
-        s = wave_sum(s);
-        if (lane == 0) {
-            if (j < L - 1) local_per_pair[j] = s;
-            else away_per_layer[j - (L - 1)] = s;
-        }
-    }
 }
 
-// Empty traces only (no chunk, so no workgroup to add up): one wavefront per output element j writes
-// the sum over C = 0 chunks.  The first `pairs` elements go to local_per_pair, the rest (present
-// with home devices only) to away_per_layer.
+// One wavefront per output element j: the first `pairs` elements go to local_per_pair, the rest
+// (present with home devices only) to away_per_layer.
 __global__ __launch_bounds__(kWave) void locality_finalize_kernel(const uint32_t* __restrict__ part, int C, int pairs, int n_out,
                                                                    int64_t* __restrict__ local_per_pair,
                                                                    int64_t* __restrict__ away_per_layer)
@@ -809,8 +794,7 @@ extern "C" size_t placement_locality_workspace_bytes(int L, int64_t N)
     if (L < 1 || N < 0) return 0;
     const int64_t chunk = exf::locality_chunk(N, 1);  // the scalar plan has the most chunks
     const int64_t C = N > 0 ? (N + chunk - 1) / chunk : 0;
-    // per-chunk partial counts, then the 8-byte ticket of the launch
-    return exf::align_up(static_cast<size_t>(C > 0 ? C : 1) * static_cast<size_t>(L > 1 ? L - 1 : 1) * sizeof(uint32_t), 256) + 256;
+    return exf::align_up(static_cast<size_t>(C > 0 ? C : 1) * static_cast<size_t>(L > 1 ? L - 1 : 1) * sizeof(uint32_t), 256);
 }
 
 extern "C" int placement_locality(const int32_t* trace, const int32_t* placement, int L, int64_t N, int E, int G,
@@ -832,23 +816,19 @@ extern "C" int placement_locality(const int32_t* trace, const int32_t* placement
     const int64_t chunk = locality_chunk(N, vec);
     const int C = static_cast<int>(N > 0 ? (N + chunk - 1) / chunk : 0);
     uint32_t* part = static_cast<uint32_t*>(workspace);
-    unsigned long long* ticket = reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(workspace) +
-                                                                       placement_locality_workspace_bytes(L, N) - 256);
     if (C > 0) {
         const size_t lds = (static_cast<size_t>(L) * E + (L - 1)) * sizeof(int32_t);
-        const unsigned long long epoch = next_epoch();
         if (vec == 4) {
             if (int rc = allow_large_lds(locality_partial_kernel<4, false>, lds, "placement_locality")) return rc;
             hipLaunchKernelGGL((locality_partial_kernel<4, false>), dim3(C), dim3(kTraceThreads), lds, s, trace, placement, nullptr, L, N,
-                               E, chunk, part, ticket, epoch, local_per_pair, nullptr);
+                               E, chunk, part);
         } else {
             if (int rc = allow_large_lds(locality_partial_kernel<1, false>, lds, "placement_locality")) return rc;
             hipLaunchKernelGGL((locality_partial_kernel<1, false>), dim3(C), dim3(kTraceThreads), lds, s, trace, placement, nullptr, L, N,
-                               E, chunk, part, ticket, epoch, local_per_pair, nullptr);
+                               E, chunk, part);
         }
-    } else {
-        hipLaunchKernelGGL(locality_finalize_kernel, dim3(L - 1), dim3(kWave), 0, s, part, C, L - 1, L - 1, local_per_pair, nullptr);
     }
+    hipLaunchKernelGGL(locality_finalize_kernel, dim3(L - 1), dim3(kWave), 0, s, part, C, L - 1, L - 1, local_per_pair, nullptr);
     return check_launch("placement_locality");
 }
 
@@ -857,7 +837,7 @@ extern "C" size_t routing_transfers_workspace_bytes(int L, int64_t N)
     if (L < 1 || N < 0) return 0;
     const int64_t chunk = exf::locality_chunk(N, 1);  // the scalar plan has the most chunks
     const int64_t C = N > 0 ? (N + chunk - 1) / chunk : 0;
-    return exf::align_up(static_cast<size_t>(C > 0 ? C : 1) * static_cast<size_t>(2 * L - 1) * sizeof(uint32_t), 256) + 256;
+    return exf::align_up(static_cast<size_t>(C > 0 ? C : 1) * static_cast<size_t>(2 * L - 1) * sizeof(uint32_t), 256);
 }
 
 extern "C" int routing_transfers(const int32_t* trace, const int32_t* placement, const int32_t* home, int L, int64_t N, int E, int G,
@@ -883,23 +863,19 @@ extern "C" int routing_transfers(const int32_t* trace, const int32_t* placement,
     const int64_t chunk = locality_chunk(N, vec);
     const int C = static_cast<int>(N > 0 ? (N + chunk - 1) / chunk : 0);
     uint32_t* part = static_cast<uint32_t*>(workspace);
-    unsigned long long* ticket = reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(workspace) +
-                                                                       routing_transfers_workspace_bytes(L, N) - 256);
     const int n_out = 2 * L - 1;
     if (C > 0) {
         const size_t lds = (static_cast<size_t>(L) * E + n_out) * sizeof(int32_t);
-        const unsigned long long epoch = next_epoch();
         if (vec == 4) {
             if (int rc = allow_large_lds(locality_partial_kernel<4, true>, lds, "routing_transfers")) return rc;
             hipLaunchKernelGGL((locality_partial_kernel<4, true>), dim3(C), dim3(kTraceThreads), lds, s, trace, placement, home, L, N, E,
-                               chunk, part, ticket, epoch, local_per_pair, away_per_layer);
+                               chunk, part);
         } else {
             if (int rc = allow_large_lds(locality_partial_kernel<1, true>, lds, "routing_transfers")) return rc;
             hipLaunchKernelGGL((locality_partial_kernel<1, true>), dim3(C), dim3(kTraceThreads), lds, s, trace, placement, home, L, N, E,
-                               chunk, part, ticket, epoch, local_per_pair, away_per_layer);
+                               chunk, part);
         }
-    } else {
-        hipLaunchKernelGGL(locality_finalize_kernel, dim3(n_out), dim3(kWave), 0, s, part, C, L - 1, n_out, local_per_pair, away_per_layer);
     }
+    hipLaunchKernelGGL(locality_finalize_kernel, dim3(n_out), dim3(kWave), 0, s, part, C, L - 1, n_out, local_per_pair, away_per_layer);
     return check_launch("routing_transfers");
 }

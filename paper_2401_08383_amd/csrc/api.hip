@@ -1,6 +1,4 @@
 // Host-only part of the C ABI: error text, version, placement constraint check, communication volume model.
-#include <atomic>
-#include <chrono>
 #include <cstdarg>
 #include <cstdio>
 #include <vector>
@@ -18,19 +16,6 @@ int fail(int code, const char* fmt, ...)
     vsnprintf(g_error, sizeof(g_error), fmt, ap);
     va_end(ap);
     return code;
-}
-
-// Epochs of the "last workgroup adds up" tickets: unique within the process, 40 bits, never 0, started
-// from a value no stale buffer content is likely to hold.
-unsigned long long next_epoch()
-{
-    static std::atomic<unsigned long long> counter{
-        static_cast<unsigned long long>(std::chrono::steady_clock::now().time_since_epoch().count()) * 0x9e3779b97f4a7c15ull};
-    unsigned long long e;
-    do {
-        e = counter.fetch_add(1, std::memory_order_relaxed) & ((1ull << 40) - 1ull);
-    } while (e == 0);
-    return e;
 }
 
 int check_launch(const char* what)

@@ -124,43 +124,6 @@ __device__ __forceinline__ int wave_read_lane(int v, int src)
     return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(src));
 }
 
-// ---- "the workgroup that finishes last adds up" ------------------------------------------------
-// A reduction kernel whose workgroups each leave a partial result can do without a second launch
-// (a dependent launch costs about 5 us here, a quarter of a 100 MB streaming pass): every workgroup
-// publishes its partials, takes a ticket, and the one that draws the last ticket reads all partials
-// back and writes the result.  The ticket is a 64-bit word in the caller's workspace that holds
-// (epoch << 24 | arrivals); the host hands every call a fresh epoch (next_epoch(), unique within the
-// process and started from a random value), so the word needs no clearing: a workgroup that finds
-// another epoch in it - a previous call's, or whatever the buffer held - restarts the count at one.
-// Compare-and-swap until it sticks; every failure means another workgroup got through, so the loop
-// ends after at most n_wg rounds and waits for nobody.
-constexpr int kTicketCountBits = 24;  // workgroups per launch stay below 2^24
-unsigned long long next_epoch();      // host: the epoch of one call (40 bits, never 0)
-
-// Call with ALL threads of the workgroup, after the partial results were stored.  Returns true in
-// every thread of exactly one workgroup of the launch, after all workgroups' partials are visible.
-__device__ __forceinline__ bool last_workgroup_of_launch(unsigned long long* ticket, unsigned long long epoch, unsigned n_wg)
-{
-    __shared__ int exf_is_last;
-    __threadfence();  // release: this thread's partial results are visible to the whole device
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long cur = __hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned long long want;
-        for (;;) {
-            want = (cur >> kTicketCountBits) == epoch ? cur + 1ull : ((epoch << kTicketCountBits) | 1ull);
-            const unsigned long long old = atomicCAS(ticket, cur, want);
-            if (old == cur) break;
-            cur = old;
-        }
-        exf_is_last = (want & ((1ull << kTicketCountBits) - 1ull)) == n_wg ? 1 : 0;
-    }
-    __syncthreads();
-    const bool last = exf_is_last != 0;
-    if (last) __threadfence();  // acquire: no stale copy of the others' partials is read below
-    return last;
-}
-
 // Which expert owns row-tile `tile` when every expert's rows [off[e], off[e+1]) are cut into
 // tiles of `mt` rows (tiles never straddle experts)?  Every lane of the calling wavefront
 // returns the same answer.  e = -1 if `tile` is beyond the last tile.  E_local <= 64;

@@ -904,14 +904,19 @@ static int launch_f32(const void* act, const int32_t* offsets, const void* weigh
     return EXF_OK;
 }
 
-// Tile configuration <MT, NT, KT, STAGES, WM, WN, SWZ, OCC> of the two contractions
-// (OCC = wavefronts per SIMD the register allocation must leave room for).
-#ifndef EXF_GEMM1_CFG
-#define EXF_GEMM1_CFG 256, 256, 64, 2, 2, 4, 1, 1
-#endif
-#ifndef EXF_GEMM2_CFG
-#define EXF_GEMM2_CFG 256, 128, 64, 3, 4, 2, 1, 1
-#endif
+// Tile configurations of the two contractions: <MT, NT, KT, STAGES, WM, WN, SWZ, OCC> (OCC = wavefronts
+// per SIMD the register allocation must leave room for).  kWideTile: 256x256x64, two stages, 2x4
+// wavefronts of 128x64; kNarrowTile: 256x128x64, three stages, 4x2 wavefronts of 64x64.
+template <typename... Args>
+static int launch_wide_tile(Args&&... args)
+{
+    return launch_bf16<256, 256, 64, 2, 2, 4, 1, 1>(static_cast<Args&&>(args)...);
+}
+template <typename... Args>
+static int launch_narrow_tile(Args&&... args)
+{
+    return launch_bf16<256, 128, 64, 3, 4, 2, 1, 1>(static_cast<Args&&>(args)...);
+}
 
 // The second contraction has few output columns (N = d).  With 256x128 tiles it offers twice as many
 // tiles, which a short batch needs to fill the chip; the 256x256 tile of the first contraction moves
@@ -923,8 +928,8 @@ static int launch_second_contraction(const void* act, const int32_t* offsets, co
 {
     const int64_t wide_tiles = (A / 256) * ((N + 255) / 256);
     if (wide_tiles >= static_cast<int64_t>(kWideRounds) * kSplitUnits)
-        return launch_bf16<EXF_GEMM1_CFG>(act, offsets, weight, bias, A, K, N, E_local, kEpiNone, out, stream, map, partial);
-    return launch_bf16<EXF_GEMM2_CFG>(act, offsets, weight, bias, A, K, N, E_local, kEpiNone, out, stream, map, partial);
+        return launch_wide_tile(act, offsets, weight, bias, A, K, N, E_local, static_cast<int>(kEpiNone), out, stream, map, partial);
+    return launch_narrow_tile(act, offsets, weight, bias, A, K, N, E_local, static_cast<int>(kEpiNone), out, stream, map, partial);
 }
 
 }  // namespace exf
@@ -982,8 +987,8 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
         if (rc == EXF_OK) rc = launch_f32(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
     } else {
         void* partial = static_cast<unsigned char*>(workspace) + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
-        rc = launch_bf16<EXF_GEMM1_CFG>(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s, RowMap{},
-                                        kSplitFirstContraction ? partial : nullptr);
+        rc = launch_wide_tile(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s, RowMap{},
+                              kSplitFirstContraction ? partial : nullptr);
         if (rc == EXF_OK)
             rc = launch_second_contraction(workspace, expert_offsets, w2, b2, A, f, d, E_local, y_sorted, s, RowMap{}, partial);
     }
@@ -1068,8 +1073,8 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
         if (rc == EXF_OK) rc = launch_f32(hidden, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, second_out, s, scatter);
     } else {
         void* partial = y_sorted + (k > 1 ? align_up(static_cast<size_t>(A) * static_cast<size_t>(d) * 2, 256) : 0);
-        rc = launch_bf16<EXF_GEMM1_CFG>(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather,
-                                        kSplitFirstContraction ? partial : nullptr);
+        rc = launch_wide_tile(x, expert_offsets, w1, b1, A, d, f, E_local, epi, hidden, s, gather,
+                              kSplitFirstContraction ? partial : nullptr);
         if (rc == EXF_OK) rc = launch_second_contraction(hidden, expert_offsets, w2, b2, A, f, d, E_local, second_out, s, scatter, partial);
     }
     if (rc != EXF_OK) return rc;

@@ -497,12 +497,11 @@ def test_repeat_calls_are_deterministic():
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
 
 
-def test_single_launch_reductions_need_no_clean_workspace(oracle):
-    """placement_locality and routing_transfers add their per-chunk counts up in the workgroup that
-    finishes last, found through a ticket word in the workspace that is never cleared: many calls in a
-    row on one workspace, of changing size, with the workspace filled with zeros, ones, and whatever
-    the previous call left, must all give the oracle's counts."""
-    _say("single-launch reductions: ticket robustness")
+def test_trace_reductions_repeat_on_one_workspace(oracle):
+    """placement_locality and routing_transfers keep per-chunk counts in the workspace: many calls in
+    a row on one workspace, of changing size, with the workspace filled with zeros, ones, and whatever
+    the previous call left, must all give the oracle's counts; then 50 calls queued back to back."""
+    _say("trace reductions: repeated calls on one workspace")
     L, E, G = 7, 32, 4
     g = syn.rng(730)
     cases = []
