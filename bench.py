@@ -242,6 +242,76 @@ def other_configs(syn, torch, MoELayerRun, dev):
     return out
 
 
+def timeline_report(syn, torch, B, index, dev):
+    """Where the time of the grouped GEMM's workgroups goes at one configuration (exf_probe_ffn_timeline):
+    per launch the span from the first workgroup's start to the last one's end, per tile kind the phases
+    of a workgroup (tile lookup, arrival of the first K tile, K loop, epilogue), the busy time of the
+    compute units, and the gap between the two launches.  Plain text, one fact per line."""
+    import ctypes
+    c = syn.CONFIGS[index]
+    lib = B.lib()
+    x = torch.from_numpy(syn.tokens(c)).to(torch.bfloat16).to(dev)
+    wg = torch.from_numpy(syn.gate_weight(c)).to(torch.bfloat16).to(dev)
+    w1, w2 = syn.device_expert_weights(c, 0, dev)
+    emap = None
+    if index == 3:
+        tr3, _ = syn.config_trace(c)
+        idx = torch.from_numpy(tr3[0].reshape(-1, 1).copy()).to(dev)
+        w = torch.rand((c.T, 1), device=dev)
+    elif index == 4:
+        i4, m4 = syn.local_routing(c, syn.seed_for(4, 4, 1))
+        idx, emap = torch.from_numpy(i4).to(dev), torch.from_numpy(m4).to(dev)
+        w = torch.rand((c.T, 1), device=dev)
+    else:
+        idx, w, _ = B.moe_gate_topk(x, wg, c.k, c.renormalize)
+    disp = B.moe_dispatch(x, idx, c.E, E_local=c.E_local, expert_map=emap, gather=False)
+    ws = torch.empty(lib.moe_expert_ffn_fused_workspace_bytes(c.T, c.k, c.d, c.f, c.E_local, B.EXF_BF16), dtype=torch.uint8, device=dev)
+    out = torch.empty((c.T, c.d), dtype=torch.bfloat16, device=dev)
+    cap = 16384
+    tl = torch.zeros((2, cap, 8), dtype=torch.int64, device=dev)
+    args = (x.data_ptr(), disp.src_of_sorted.data_ptr(), disp.sorted_of_src.data_ptr(), w.data_ptr(), disp.expert_offsets.data_ptr(),
+            w1.data_ptr(), w2.data_ptr(), c.T, c.k, c.d, c.f, c.E_local, out.data_ptr(), ws.data_ptr(), ws.numel(), tl.data_ptr(), cap,
+            B._stream())
+    ms = _time_groups([lambda: B._check(lib.exf_probe_ffn_timeline(*args))], groups=6, inner=5, warmup=20)
+    t = tl.cpu().numpy()
+    us = 0.01  # the device clock of the records ticks at 100 MHz
+    print(f"timeline of moe_expert_ffn_fused, {c.name}: T={c.T} d={c.d} f={c.f} E_local={c.E_local} k={c.k}; "
+          f"rows per expert {disp.expert_counts.cpu().numpy().tolist()}")
+    print(f"call: {ms['ms_median'] * 1e3:.1f} us median, {ms['ms_min'] * 1e3:.1f} us min (back to back, timeline recording on)")
+    spans = []
+    for which, name in ((0, "first contraction"), (1, "second contraction")):
+        r = t[which]
+        ran = (r[:, 4] > 0) & (r[:, 1] > 0)
+        if not ran.any():
+            print(f"{name}: no record")
+            continue
+        t0, t1 = r[ran, 0].min(), r[ran, 4].max()
+        spans.append((t0, t1))
+        print(f"{name}: {int(ran.sum())} workgroups ran a tile, first start to last end {(t1 - t0) * us:.1f} us")
+        kind = r[:, 6] & 3
+        for kd, kn in ((2, "tall"), (0, "full"), (1, "remainder")):
+            m = ran & (kind == kd)
+            if not m.any():
+                continue
+            nk = np.unique((r[m, 6] >> 48) & 0xffff).tolist()
+            ph = {"lookup": r[m, 1] - r[m, 0], "first K tile": r[m, 2] - r[m, 1], "K loop": r[m, 3] - r[m, 2], "epilogue": r[m, 4] - r[m, 3],
+                  "total": r[m, 4] - r[m, 0]}
+            print(f"  {kn} tiles: {int(m.sum())}, K tiles per work item {nk}, starts {(r[m, 0].min() - t0) * us:.1f}..{(r[m, 0].max() - t0) * us:.1f} us, "
+                  f"ends {(r[m, 4].min() - t0) * us:.1f}..{(r[m, 4].max() - t0) * us:.1f} us")
+            for pn, v in ph.items():
+                v = v * us
+                print(f"    {pn:13s} mean {v.mean():6.2f}  p10 {np.percentile(v, 10):6.2f}  median {np.median(v):6.2f}  p90 {np.percentile(v, 90):6.2f}  max {v.max():6.2f} us")
+        hw = r[:, 5]
+        cu = (hw >> 32) * 4096 + ((hw >> 13) & 7) * 256 + ((hw >> 8) & 15)  # XCD, shader engine, compute unit
+        keys = np.unique(cu[ran])
+        busy = np.array([((r[ran & (cu == k), 4] - r[ran & (cu == k), 0]).sum() * us, (r[ran & (cu == k), 4].max() - t0) * us) for k in keys])
+        print(f"  compute units seen {len(keys)}; busy per unit mean {busy[:, 0].mean():.1f} max {busy[:, 0].max():.1f} us; "
+              f"last end per unit min {busy[:, 1].min():.1f} mean {busy[:, 1].mean():.1f} max {busy[:, 1].max():.1f} us")
+    if len(spans) == 2:
+        print(f"gap between the launches (last end of the first to first start of the second): {(spans[1][0] - spans[0][1]) * us:.2f} us; "
+              f"first start to last end of both: {(spans[1][1] - spans[0][0]) * us:.1f} us")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -250,7 +320,13 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
                     help="workload configuration (default 2: the one the headline metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--timeline", action="store_true",
+                    help="print the per-workgroup phase timeline of the grouped GEMM at --config (text) instead of the benchmark line")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel and large-shape measurements")
+    ap.add_argument("--sections", default="all",
+                    help="comma list of what to run: step (the timed steps), per_call, box, hbm4 (the HBM-bound calls, the placement "
+                         "search and the transfer counters at the shapes of the one-GPU-share configuration), other (the larger "
+                         "configurations), cpu; default all.  Profiling runs pick one so that every kernel appears at one shape only")
     ap.add_argument("--unfused", action="store_true",
                     help="sorted copies of the activations and a separate combine pass "
                          "(moe_expert_ffn + moe_combine) instead of moe_expert_ffn_fused")
@@ -260,6 +336,11 @@ def main():
                     help="run the affinity statistic on a second stream beside the layer (forked and joined every step) "
                          "instead of on the layer's stream")
     args = ap.parse_args()
+    sections = {"step", "per_call", "box", "hbm4", "other", "cpu"} if args.sections == "all" else set(args.sections.split(","))
+    if args.no_extra:
+        sections &= {"step", "cpu"}
+    if args.no_cpu_baseline:
+        sections.discard("cpu")
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives, no sharding)",
               file=sys.stderr)
@@ -275,6 +356,9 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     lib = B.lib()
+    if args.timeline:
+        timeline_report(syn, torch, B, args.config, dev)
+        return
 
     cfg = syn.CONFIGS[args.config]
     bf16 = cfg.dtype == "bf16"
@@ -340,40 +424,42 @@ def main():
             lay.step()
         affinity_join()
 
-    # fixed internal warm-up (clocks, caches, lazy module loads), then the caller's W steps
-    step()
-    torch.cuda.synchronize()
-    t_w = time.perf_counter()
-    n_internal = 1
-    while time.perf_counter() - t_w < WARM_SECONDS:
-        for _ in range(8):
-            step()
-        n_internal += 8
-        torch.cuda.synchronize()
-    for _ in range(args.warmup):
+    ms_per_step, per_step, ffn_all, ffn_ms, n_internal = float("nan"), np.array([float("nan")]), np.array([float("nan")]), float("nan"), 0
+    if "step" in sections:
+        # fixed internal warm-up (clocks, caches, lazy module loads), then the caller's W steps
         step()
-    ffn_ev = [[_events(2) for _ in layers] for _ in range(args.steps)]
-    step_ev = _events(args.steps + 1)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step_ev[i].record()
-        affinity_fork()
-        for j, lay in enumerate(layers):
-            lay.gate()
-            lay.dispatch()
-            ffn_ev[i][j][0].record()
-            lay.ffn()
-            ffn_ev[i][j][1].record()
-            lay.combine()
-        affinity_join()
-    step_ev[args.steps].record()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    per_step = np.array([step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(args.steps)])
-    ffn_all = np.array([a.elapsed_time(b) for step_ev_ in ffn_ev for a, b in step_ev_])
-    ffn_ms = float(ffn_all.mean())
+        torch.cuda.synchronize()
+        t_w = time.perf_counter()
+        n_internal = 1
+        while time.perf_counter() - t_w < WARM_SECONDS:
+            for _ in range(8):
+                step()
+            n_internal += 8
+            torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            step()
+        ffn_ev = [[_events(2) for _ in layers] for _ in range(args.steps)]
+        step_ev = _events(args.steps + 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step_ev[i].record()
+            affinity_fork()
+            for j, lay in enumerate(layers):
+                lay.gate()
+                lay.dispatch()
+                ffn_ev[i][j][0].record()
+                lay.ffn()
+                ffn_ev[i][j][1].record()
+                lay.combine()
+            affinity_join()
+        step_ev[args.steps].record()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        ms_per_step = elapsed * 1e3 / args.steps
+        per_step = np.array([step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(args.steps)])
+        ffn_all = np.array([a.elapsed_time(b) for step_ev_ in ffn_ev for a, b in step_ev_])
+        ffn_ms = float(ffn_all.mean())
 
     A = cfg.T * cfg.k
     ffn_flops = 4.0 * A * cfg.d * cfg.f
@@ -431,7 +517,7 @@ def main():
     }
     achieved = achieved_tf
 
-    if not args.no_extra:
+    if "per_call" in sections:
         # per-entry-point averages at the benchmark configuration
         per = {}
         calls = [("gate", layer.gate), ("dispatch", layer.dispatch), ("ffn", layer.ffn)]
@@ -448,6 +534,7 @@ def main():
         per["layer_tokens_per_s"] = cfg.T / (layer_ms * 1e-3)
         result["per_call"] = per
 
+    if "box" in sections:
         # achieved rates of this machine
         nbytes = 1 << 30
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
@@ -496,8 +583,11 @@ def main():
         if roofline["bound"] == "mfma" and bf16:
             result["roofline"]["frac_of_measured_mfma_loop"] = achieved / mfma_tflops
             result["roofline"]["frac_of_measured_gemm_k_loop_random_operands"] = achieved / max(loop_rand, loop_rand_sustained)
+            if ref_gemm and cfg.index == 2:  # two dense vendor GEMMs of the same flop counts, random operands
+                t_ref = sum(ffn_flops / 2 / (v * 1e12) for v in ref_gemm.values())
+                result["roofline"]["frac_of_vendor_gemm_same_shapes"] = (ffn_flops / t_ref / 1e12) and achieved / (ffn_flops / t_ref / 1e12)
 
-    if not args.no_extra and cfg.index == 2:
+    if "hbm4" in sections and cfg.index == 2:
         # HBM-bound entry points at the shapes of the one-GPU-share configuration (rotating buffers)
         c4 = syn.CONFIGS[4]
         hbm = {}
@@ -603,10 +693,10 @@ def main():
             "gpu_locality": {"found": sc[0] / total, "contiguous": sc[1] / total, "random": sc[2] / total},
             "node_locality": {"found": node_sc[0] / total, "contiguous": node_sc[1] / total, "random": node_sc[2] / total}}
 
-    if not args.no_extra and cfg.index == 2 and fused:
+    if "other" in sections and cfg.index == 2 and fused:
         result["other_configs"] = other_configs(syn, torch, MoELayerRun, dev)
 
-    if not args.no_cpu_baseline and host is not None:
+    if "cpu" in sections and host is not None:
         result["cpu_baseline"] = cpu_baseline(cfg, host[0], host[1], host[2], host[3], trace_h, pl_h)
         result["cpu_baseline"]["single_thread"] = cpu_baseline_single_thread(cfg, host[0], host[1], host[2], host[3])
     else:

@@ -28,11 +28,25 @@ extern "C" {
  *                   256 workgroups walk all 512 output tiles `passes` times, i.e.
  *                   passes * 512 * 2*256*256*1024 flop; out receives 256*256 floats.  The rate it
  *                   reaches depends on the operand values (all zeros against random numbers).
+ *   exf_probe_ffn_timeline: moe_expert_ffn_fused (bf16, erf GELU, no biases; same arguments and
+ *                   validation) that also records where the time of every workgroup of its two
+ *                   grouped-GEMM launches goes.  timeline (device) holds 2 * capacity records of
+ *                   eight uint64: records [0, capacity) belong to the first contraction, [capacity,
+ *                   2 capacity) to the second; record b is written by workgroup b (workgroups b >=
+ *                   capacity write nothing): [0] start, [1] tile located, [2] first K tile landed,
+ *                   [3] K loop done, [4] end or 0 if the workgroup had no tile - all in ticks of the
+ *                   constant 100 MHz device clock -, [5] hardware id, [6] tile kind (0 full, 1 remainder,
+ *                   2 tall) | expert << 8 | column tile << 16 | rows << 32 | K tiles << 48.
  * ------------------------------------------------------------------------------------- */
 int exf_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 int exf_probe_mfma(int workgroups, int iters, float* out, void* stream);
 size_t exf_probe_gemm_loop_bytes(void);
 int exf_probe_gemm_loop(const void* operands, size_t bytes, int passes, float* out, void* stream);
+int exf_probe_ffn_timeline(const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src,
+                           const float* topk_w, const int32_t* expert_offsets, const void* w1,
+                           const void* w2, int64_t T, int k, int d, int f, int E_local, void* out,
+                           void* workspace, size_t workspace_bytes, uint64_t* timeline, int capacity,
+                           void* stream);
 
 #ifdef __cplusplus
 }

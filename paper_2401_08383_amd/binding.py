@@ -62,6 +62,7 @@ SIGNATURES = {
     "exf_probe_mfma": (_i, [_i, _i, _vp, _vp]),
     "exf_probe_gemm_loop_bytes": (_sz, []),
     "exf_probe_gemm_loop": (_i, [_vp, _sz, _i, _vp, _vp]),
+    "exf_probe_ffn_timeline": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i, _vp, _vp, _sz, _vp, _i, _vp]),
 }
 
 _lib = None

@@ -314,7 +314,19 @@ struct RowMap {
                               //   fp32 before the single rounding to bf16              (null: row s, no scale)
     const int32_t* unrouted;  // [n_unrouted]: output row t with unrouted[t] < 0 is set to zero
     int n_unrouted;
+    // Measurement only (exf_probe_ffn_timeline; null in every other call): workgroup b < timeline_cap
+    // writes eight 64-bit words - [0] start, [1] tile located, [2] first K tile landed, [3] K loop done,
+    // [4] end (all on the constant 100 MHz clock), [5] hardware id, [6] tile kind / expert / column tile /
+    // rows / K tiles, [7] unused.
+    unsigned long long* timeline;
+    int timeline_cap;
 };
+
+__device__ __forceinline__ void timeline_stamp(const RowMap& map, int slot)
+{
+    if (map.timeline != nullptr && threadIdx.x == 0 && static_cast<int>(blockIdx.x) < map.timeline_cap)
+        map.timeline[static_cast<size_t>(blockIdx.x) * 8 + slot] = wall_clock64();
+}
 
 // One output tile: rows [row_begin,row_end) (at most MT) x columns [n0, n0+NT) of expert weights wexp,
 // summed over K tiles [kt_begin, kt_end).  With `partial` set (SPLIT instantiations only) the fp32
@@ -444,6 +456,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         else wait_vmcnt<0>();
     }
     __syncthreads();
+    timeline_stamp(map, 2);
     // Operand register ring: FD K steps deep (fetches run FD-1 K steps ahead of the MFMAs).  Two is
     // enough when a K step holds many MFMAs; a wavefront tile of one or two MFMAs per K step (the
     // remainder tiles) takes four, or every K step would expose a full LDS round trip.
@@ -529,6 +542,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
             }
         }
     }
+    timeline_stamp(map, 3);
     if constexpr (SPLIT) {
         if (partial != nullptr) {  // a K slice: hand the raw sums to the kernel that adds the slices
 #pragma unroll
@@ -641,6 +655,9 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
                                                                          float4* __restrict__ partial)       // K-slice sums or null
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    timeline_stamp(map, 0);
+    if (map.timeline != nullptr && threadIdx.x == 0 && static_cast<int>(blockIdx.x) < map.timeline_cap)
+        map.timeline[static_cast<size_t>(blockIdx.x) * 8 + 4] = 0ull;  // stays zero if this workgroup has no tile
     if (map.unrouted != nullptr) {
         // output rows no sorted row writes (dropped or remote assignments): one wavefront looks at 64
         // rows at a time and clears those it finds, all lanes together
@@ -665,6 +682,19 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
     if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, K / KT, partial != nullptr && MT > kTailRows, TALL,
                      tile_index_of_workgroup(blockIdx.x), tile))
         return;
+    timeline_stamp(map, 1);
+    if (map.timeline != nullptr && threadIdx.x == 0 && static_cast<int>(blockIdx.x) < map.timeline_cap) {
+        unsigned hw = 0, xcc = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+#endif
+        unsigned long long* rec = map.timeline + static_cast<size_t>(blockIdx.x) * 8;
+        rec[5] = static_cast<unsigned long long>(hw) | (static_cast<unsigned long long>(xcc & 0xfu) << 32);
+        rec[6] = static_cast<unsigned long long>(tile.tail ? 1 : (tile.tall ? 2 : 0)) | (static_cast<unsigned long long>(tile.expert) << 8) |
+                 (static_cast<unsigned long long>(tile.n_tile) << 16) | (static_cast<unsigned long long>(tile.row_end - tile.row_begin) << 32) |
+                 (static_cast<unsigned long long>(tile.kt_end - tile.kt_begin) << 48);
+    }
     const bf16_t* wexp = weight + static_cast<size_t>(tile.expert) * N * K;
     const bf16_t* bias_e = BIAS ? bias + static_cast<size_t>(tile.expert) * N : nullptr;
     if (tile.tall) {
@@ -689,6 +719,7 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
         gemm_tile<kTailRows, NT, KT, STAGES_T, WM_T, WM * WN / WM_T, SWZ, EPI, BIAS, true>(
             act, wexp, bias_e, tile.row_begin, tile.row_end, tile.n_tile * NT, K, N, out, smem, map, tile.kt_begin, tile.kt_end, slot);
     }
+    timeline_stamp(map, 4);
 }
 
 // Adds the K slices of every tail tile and applies the epilogue the slices skipped.  A workgroup owns
@@ -1010,12 +1041,13 @@ extern "C" size_t moe_expert_ffn_fused_workspace_bytes(int64_t T, int k, int d, 
     return bytes + (dt == EXF_BF16 ? exf::kSplitBytes : 0);                      // bf16: partial sums of K-sliced tail tiles
 }
 
-extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src, const float* topk_w,
-                                    const int32_t* expert_offsets, const void* w1, const void* b1, const void* w2, const void* b2,
-                                    int64_t T, int k, int d, int f, int E_local, int act, int dt, void* out, void* workspace,
-                                    size_t workspace_bytes, void* stream)
+static int ffn_fused_run(const char* fn, const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src, const float* topk_w,
+                         const int32_t* expert_offsets, const void* w1, const void* b1, const void* w2, const void* b2, int64_t T, int k,
+                         int d, int f, int E_local, int act, int dt, void* out, void* workspace, size_t workspace_bytes, void* stream,
+                         unsigned long long* timeline, int timeline_cap)
 {
     using namespace exf;
+    (void)fn;
     if (dt != EXF_F32 && dt != EXF_BF16) return fail(EXF_ERR_BAD_DTYPE, "moe_expert_ffn_fused: dt = %d", dt);
     if (act != EXF_ACT_GELU_ERF && act != EXF_ACT_GELU_TANH) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: act = %d", act);
     if (k < 1 || k > EXF_MAX_TOPK) return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: k = %d outside [1,%d]", k, EXF_MAX_TOPK);
@@ -1058,7 +1090,11 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
     RowMap gather{};
     gather.a_row = src_of_sorted;
     gather.a_div = k;
+    gather.timeline = timeline;  // first contraction: records [0, cap), second: [cap, 2 cap)
+    gather.timeline_cap = timeline_cap;
     RowMap scatter{};
+    scatter.timeline = timeline != nullptr ? timeline + static_cast<size_t>(timeline_cap) * 8 : nullptr;
+    scatter.timeline_cap = timeline_cap;
     if (k == 1) {
         scatter.out_row = src_of_sorted;  // k = 1: the flat assignment index is the token
         scatter.out_scale = topk_w;
@@ -1082,4 +1118,26 @@ extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted,
     rc = check_launch("moe_expert_ffn_fused");
     if (rc != EXF_OK) return rc;
     return moe_combine(y_sorted, sorted_of_src, topk_w, T, d, k, dt, out, stream);
+}
+
+extern "C" int moe_expert_ffn_fused(const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src, const float* topk_w,
+                                    const int32_t* expert_offsets, const void* w1, const void* b1, const void* w2, const void* b2,
+                                    int64_t T, int k, int d, int f, int E_local, int act, int dt, void* out, void* workspace,
+                                    size_t workspace_bytes, void* stream)
+{
+    return ffn_fused_run("moe_expert_ffn_fused", x, src_of_sorted, sorted_of_src, topk_w, expert_offsets, w1, b1, w2, b2, T, k, d, f,
+                         E_local, act, dt, out, workspace, workspace_bytes, stream, nullptr, 0);
+}
+
+// moe_expert_ffn_fused (bf16) with a per-workgroup timeline of both contractions (see RowMap::timeline).
+extern "C" int exf_probe_ffn_timeline(const void* x, const int32_t* src_of_sorted, const int32_t* sorted_of_src, const float* topk_w,
+                                      const int32_t* expert_offsets, const void* w1, const void* w2, int64_t T, int k, int d, int f,
+                                      int E_local, void* out, void* workspace, size_t workspace_bytes, uint64_t* timeline,
+                                      int capacity, void* stream)
+{
+    EXF_REQUIRE_PTR(timeline);
+    if (capacity < 1) return exf::fail(EXF_ERR_BAD_SHAPE, "exf_probe_ffn_timeline: capacity = %d < 1", capacity);
+    return ffn_fused_run("exf_probe_ffn_timeline", x, src_of_sorted, sorted_of_src, topk_w, expert_offsets, w1, nullptr, w2, nullptr, T, k,
+                         d, f, E_local, EXF_ACT_GELU_ERF, EXF_BF16, out, workspace, workspace_bytes, stream,
+                         reinterpret_cast<unsigned long long*>(timeline), capacity);
 }
