@@ -12,10 +12,18 @@ Inputs are resident in HBM before the timed region; no allocation happens inside
 `--config N` times another of the five workload configurations the same way (the decode-shaped
 one runs its 8 consecutive layers per step and reports the weight-streaming HBM roofline).
 
-Prints ONE JSON line: tokens/s of the whole step, the roofline of the dominant kernel (the
-grouped expert GEMM, measured with HIP events on the launch stream), per-entry-point timings,
-HBM-bound entry points at the larger shapes of the one-GPU-share configuration, achieved copy
-and MFMA rates of the box, and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: tokens/s of the whole step (mean of the K timed steps, which follow a fixed
+0.3 s of untimed steps and the caller's W; the median and minimum over per-step event pairs beside
+it), the roofline of the dominant kernel (the grouped expert GEMM, measured with HIP events on the
+launch stream; its HBM-side bytes come from the tracked profile summary), per-entry-point timings
+(median / mean / minimum), the HBM-bound entry points at the larger shapes of the one-GPU-share
+configuration (rotated over buffer sets larger than the 256 MB cache, and un-rotated), the expert
+FFN of the three larger configurations, the copy, MFMA and vendor-GEMM rates of the box, the
+placement search with the communication volumes of the paper's comparison table, and the CPU oracle
+timed on all host threads and on one.
+
+`--sections` runs a part of this (profiling runs use it so that every kernel appears at one shape
+only); `--timeline` prints where the time of the grouped GEMM's workgroups goes instead.
 """
 from __future__ import annotations
 
@@ -326,7 +334,11 @@ def main():
     ap.add_argument("--sections", default="all",
                     help="comma list of what to run: step (the timed steps), per_call, box, hbm4 (the HBM-bound calls, the placement "
                          "search and the transfer counters at the shapes of the one-GPU-share configuration), other (the larger "
-                         "configurations), cpu; default all.  Profiling runs pick one so that every kernel appears at one shape only")
+                         "configurations), search (placement search, transfer ratios, multi-hop statistic), cpu; default all.  "
+                         "Profiling runs pick one so that every kernel appears at one shape only")
+    ap.add_argument("--hbm4-calls", default="all",
+                    help="comma list of the calls the hbm4 section times (dispatch, combine, gate, affinity_histogram, "
+                         "placement_locality, affinity_statistics, routing_transfers); default all")
     ap.add_argument("--unfused", action="store_true",
                     help="sorted copies of the activations and a separate combine pass "
                          "(moe_expert_ffn + moe_combine) instead of moe_expert_ffn_fused")
@@ -336,7 +348,8 @@ def main():
                     help="run the affinity statistic on a second stream beside the layer (forked and joined every step) "
                          "instead of on the layer's stream")
     args = ap.parse_args()
-    sections = {"step", "per_call", "box", "hbm4", "other", "cpu"} if args.sections == "all" else set(args.sections.split(","))
+    sections = {"step", "per_call", "box", "hbm4", "search", "other", "cpu"} if args.sections == "all" else set(args.sections.split(","))
+    want4 = (lambda name: True) if args.hbm4_calls == "all" else (lambda name: name in args.hbm4_calls.split(","))
     if args.no_extra:
         sections &= {"step", "cpu"}
     if args.no_cpu_baseline:
@@ -577,17 +590,28 @@ def main():
                 st = _time_groups([lambda: torch.matmul(a_, b_.t(), out=c_)], groups=10, inner=10)
                 ref_gemm[name + "_TFLOPs"] = 2.0 * m_ * n_ * k_ / (st["ms_median"] * 1e-3) / 1e12
                 del a_, b_, c_
+            # the same two contractions as batched GEMMs over 8 equal experts of 1024 rows (torch.bmm): eight weight
+            # matrices as in the grouped GEMM, but no ragged groups, no GELU, no gather / scatter
+            for name, (m_, n_, k_) in (("bmm1_8x1024x4096x1024", (1024, 4096, 1024)), ("bmm2_8x1024x1024x4096", (1024, 1024, 4096))):
+                a_ = torch.randn((8, m_, k_), device=dev).to(torch.bfloat16)
+                b_ = (torch.randn((8, n_, k_), device=dev) * 0.02).to(torch.bfloat16)
+                c_ = torch.empty((8, m_, n_), dtype=torch.bfloat16, device=dev)
+                st = _time_groups([lambda: torch.bmm(a_, b_.transpose(1, 2), out=c_)], groups=10, inner=10)
+                ref_gemm[name + "_TFLOPs"] = 8 * 2.0 * m_ * n_ * k_ / (st["ms_median"] * 1e-3) / 1e12
+                del a_, b_, c_
         result["box"] = {"torch_matmul_random_bf16": ref_gemm, "copy_GBps": copy_gbs, "mfma_loop_TFLOPs": mfma_tflops, "gemm_k_loop_zero_operands_TFLOPs": loop_zero,
                          "gemm_k_loop_random_operands_TFLOPs": loop_rand,
                          "gemm_k_loop_random_operands_sustained_TFLOPs": loop_rand_sustained}
         if roofline["bound"] == "mfma" and bf16:
             result["roofline"]["frac_of_measured_mfma_loop"] = achieved / mfma_tflops
             result["roofline"]["frac_of_measured_gemm_k_loop_random_operands"] = achieved / max(loop_rand, loop_rand_sustained)
-            if ref_gemm and cfg.index == 2:  # two dense vendor GEMMs of the same flop counts, random operands
-                t_ref = sum(ffn_flops / 2 / (v * 1e12) for v in ref_gemm.values())
-                result["roofline"]["frac_of_vendor_gemm_same_shapes"] = (ffn_flops / t_ref / 1e12) and achieved / (ffn_flops / t_ref / 1e12)
+            if ref_gemm and cfg.index == 2:  # the vendor library's two GEMMs of the same flop counts, random operands
+                for key, names in (("frac_of_vendor_dense_gemms", ("gemm1_8192x4096x1024_TFLOPs", "gemm2_8192x1024x4096_TFLOPs")),
+                                   ("frac_of_vendor_batched_gemms", ("bmm1_8x1024x4096x1024_TFLOPs", "bmm2_8x1024x1024x4096_TFLOPs"))):
+                    t_ref = sum(ffn_flops / 2 / (ref_gemm[n] * 1e12) for n in names)
+                    result["roofline"][key] = achieved / (ffn_flops / t_ref / 1e12)
 
-    if "hbm4" in sections and cfg.index == 2:
+    if ("hbm4" in sections or "search" in sections) and cfg.index == 2:
         # HBM-bound entry points at the shapes of the one-GPU-share configuration (rotating buffers)
         c4 = syn.CONFIGS[4]
         hbm = {}
@@ -610,7 +634,8 @@ def main():
             return lambda: lib.moe_dispatch(*a)
 
         bytes_disp = T4 * d4 * 2 * 2 + T4 * 16
-        hbm["dispatch"] = _hbm_entry(disp_fn, sets, bytes_disp)
+        if "hbm4" in sections and want4("dispatch"):
+            hbm["dispatch"] = _hbm_entry(disp_fn, sets, bytes_disp)
         w4 = torch.rand((T4, 1), device=dev)
         couts = [torch.empty((T4, d4), dtype=torch.bfloat16, device=dev) for _ in range(sets)]
 
@@ -619,7 +644,8 @@ def main():
             return lambda: lib.moe_combine(*a)
 
         bytes_comb = T4 * d4 * 2 * 2 + T4 * 12
-        hbm["combine"] = _hbm_entry(comb_fn, sets, bytes_comb)
+        if "hbm4" in sections and want4("combine"):
+            hbm["combine"] = _hbm_entry(comb_fn, sets, bytes_comb)
         gw4 = torch.randn((c4.E, d4), device=dev).to(torch.bfloat16)
         gi = torch.empty((T4, 1), dtype=torch.int32, device=dev)
         gwt = torch.empty((T4, 1), dtype=torch.float32, device=dev)
@@ -629,7 +655,8 @@ def main():
             return lambda: lib.moe_gate_topk(*a)
 
         bytes_gate = T4 * d4 * 2 + c4.E * d4 * 2 + T4 * 8
-        hbm["gate"] = _hbm_entry(gate_fn, sets, bytes_gate)
+        if "hbm4" in sections and want4("gate"):
+            hbm["gate"] = _hbm_entry(gate_fn, sets, bytes_gate)
         del xs4, outs, couts
         tr4_h, _ = syn.config_trace(c4)
         pl4 = torch.from_numpy(syn.balanced_random_placement(c4.trace_L, c4.trace_E, c4.G, syn.seed_for(4, 5))).to(dev)
@@ -639,11 +666,23 @@ def main():
         aff4 = AffinityRun(base, pl4, c4.trace_E, c4.G)
         bytes_tr = 4 * c4.trace_L * c4.trace_N
         tok = lambda ms: {"trace_tokens_per_s": c4.trace_N / (ms * 1e-3)}
-        hbm["affinity_histogram"] = _hbm_entry(lambda i: (lambda: aff4.histogram(traces[i])), tr_sets, bytes_tr, tok)
-        hbm["placement_locality"] = _hbm_entry(lambda i: (lambda: aff4.locality(traces[i])), tr_sets, bytes_tr, tok)
-        hbm["affinity_statistics"] = _hbm_entry(lambda i: (lambda: aff4.statistics(traces[i])), tr_sets, bytes_tr, tok)
-        result["hbm_bound_calls_config4_shapes"] = hbm
+        gh = torch.Generator(device="cpu")
+        gh.manual_seed(syn.seed_for(4, 7))
+        home4 = torch.randint(0, c4.G, (c4.trace_N,), generator=gh, dtype=torch.int32).to(dev)  # requests owned by uniformly drawn GPUs
+        ws_rt = torch.empty(max(lib.routing_transfers_workspace_bytes(c4.trace_L, c4.trace_N), 256), dtype=torch.uint8, device=dev)
+        if "hbm4" in sections:
+            if want4("affinity_histogram"):
+                hbm["affinity_histogram"] = _hbm_entry(lambda i: (lambda: aff4.histogram(traces[i])), tr_sets, bytes_tr, tok)
+            if want4("placement_locality"):
+                hbm["placement_locality"] = _hbm_entry(lambda i: (lambda: aff4.locality(traces[i])), tr_sets, bytes_tr, tok)
+            if want4("affinity_statistics"):
+                hbm["affinity_statistics"] = _hbm_entry(lambda i: (lambda: aff4.statistics(traces[i])), tr_sets, bytes_tr, tok)
+            if want4("routing_transfers"):
+                hbm["routing_transfers"] = _hbm_entry(lambda i: (lambda: B.routing_transfers(traces[i], pl4, home4, c4.G, workspace=ws_rt)),
+                                                      tr_sets, bytes_tr + 4 * c4.trace_N, tok)
+            result["hbm_bound_calls_config4_shapes"] = hbm
 
+    if "search" in sections and cfg.index == 2:
         # placement search on the one-GPU-share trace (24 layers x 1M tokens, E=64, 8 GPUs on 2 nodes):
         # counts on the GPU, host solver, GPU batch scoring of {found, default, random} from the counts
         res4 = B.affinity_histogram(base, c4.trace_E)
@@ -659,12 +698,8 @@ def main():
         sc = B.placement_locality_from_counts(res4["counts"], cands).sum(dim=1).cpu().numpy()
         total = float(c4.trace_N) * (c4.trace_L - 1)
         node_sc = B.placement_locality_from_counts(res4["counts"], (cands // (c4.G // 2)).to(torch.int32).contiguous()).sum(dim=1).cpu().numpy()
-        # cross-GPU transfers of the trace (requests owned by uniformly drawn GPUs): ratio of token-layer
-        # visits that take part in an Alltoall, vanilla (out and back) against coherent contexts
-        gh = torch.Generator(device="cpu")
-        gh.manual_seed(syn.seed_for(4, 7))
-        home4 = torch.randint(0, c4.G, (c4.trace_N,), generator=gh, dtype=torch.int32).to(dev)
-        ws_rt = torch.empty(max(lib.routing_transfers_workspace_bytes(c4.trace_L, c4.trace_N), 256), dtype=torch.uint8, device=dev)
+        # cross-GPU transfers of the trace: ratio of token-layer visits that take part in an Alltoall, vanilla (out
+        # and back) against coherent contexts
         ratios = {}
         # p and p* of the trace and the forward communication volumes of the paper's comparison table for it
         # (G GPUs holding trace_N / G tokens each, L MoE layers; the top-2 columns use the same ratios)
@@ -674,10 +709,7 @@ def main():
             vol = B.comm_volume(c4.G, c4.trace_N // c4.G, c4.trace_L, p_van, p_star)
             ratios[name] = {"vanilla_p": p_van, "coherent_p_star": p_star, "volume_tokens": vol,
                             "coherent_over_vanilla_top1": vol["coherent_top1"] / vol["vanilla_top1"]}
-        rt = _hbm_entry(lambda i: (lambda: B.routing_transfers(traces[i], cands[0], home4, c4.G, workspace=ws_rt)), tr_sets,
-                        bytes_tr + 4 * c4.trace_N)
-        rt["alltoall_token_ratio"] = ratios
-        result["routing_transfers"] = rt
+        result["alltoall_token_ratio"] = ratios
         # affinity across several layers: all 276 ordered layer pairs of the same trace
         ws_mh = torch.empty(max(lib.affinity_multihop_workspace_bytes(c4.trace_L, c4.trace_N, c4.trace_E), 256), dtype=torch.uint8,
                             device=dev)
