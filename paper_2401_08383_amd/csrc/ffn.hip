@@ -638,8 +638,10 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
             const uint4 val = *reinterpret_cast<const uint4*>(region + r * S + c * 16);
             const int m = m_pass + r;
             const int n = n_wave + c * 8;
+            // streaming stores: the tile is not read again in this launch, and keeping it out of the
+            // write-back cache leaves that cache to the weight panels the neighbouring tiles share
             if (m < row_end && n < N)  // N % 8 == 0: a chunk is entirely inside or outside
-                *reinterpret_cast<uint4*>(out + static_cast<size_t>(dst[it]) * N + n) = val;
+                store_stream16(reinterpret_cast<uint4*>(out + static_cast<size_t>(dst[it]) * N + n), val);
         }
     }
 }
