@@ -14,6 +14,8 @@
 //                a unique permutation), writes both index maps and copies the slice's rows
 //                x_sorted[position] = x[assignment / k] as 16-byte vector copies.
 //                (Without rows to move, dispatch_scatter_kernel ranks whole chunks instead.)
+//   Index maps only and at most 16384 assignments: ONE workgroup of 1024 threads does all three steps
+//   in a single launch (dispatch_small_kernel) - at that size the launches, not the work, are the cost.
 // No step needs the host to know a data-dependent size.
 #include <mutex>
 
@@ -192,6 +194,108 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
             const int* earlier = &wave_cnt[0][0][e];
             const int n_earlier = round * kDispWaves + wave;
             for (int i = 0; i < n_earlier; ++i) pos += earlier[i * EXF_MAX_EXPERTS];
+            src_of_sorted[pos] = static_cast<int32_t>(a);
+            sorted_of_src[a] = pos;
+        } else if (a < A) {
+            sorted_of_src[a] = -1;
+        }
+    }
+}
+
+// Count, scan and scatter of a short assignment list in one workgroup of 16 wavefronts (index maps
+// only).  Thread t takes the assignments a = r*1024 + t, r < R.  A "segment" is what one wavefront
+// holds in one round; segments in (round, wavefront) order are ascending assignment order.  Every
+// segment counts its experts with the ballots of same_expert_lanes, a wavefront per expert scans the
+// R*16 segment counts into segment starts and the expert's total, one wavefront scans the totals into
+// the bucket starts: position = bucket start + segment start + lower lanes with the same expert - the
+// same stable permutation as the chunked kernels.
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallWaves = kSmallThreads / kWave;
+constexpr int kSmallMaxRounds = 16;
+template <int R>
+__global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(const int32_t* __restrict__ topk_idx,
+                                                                        const int32_t* __restrict__ expert_map, int64_t A, int E,
+                                                                        int E_local, int32_t* __restrict__ expert_counts,
+                                                                        int32_t* __restrict__ expert_offsets,
+                                                                        int32_t* __restrict__ src_of_sorted,
+                                                                        int32_t* __restrict__ sorted_of_src)
+{
+    constexpr int SEG = R * kSmallWaves;       // segments
+    constexpr int PER = SEG / kWave;           // consecutive segments a lane scans
+    static_assert(SEG % kWave == 0 && R <= kSmallMaxRounds, "segment scan layout");
+    __shared__ unsigned short seg[EXF_MAX_EXPERTS][SEG];  // count, then start, of a segment inside its expert's bucket (<= 16384)
+    __shared__ int total[EXF_MAX_EXPERTS];
+    __shared__ int bucket[EXF_MAX_EXPERTS];
+    const int lane = lane_id();
+    const int wave = threadIdx.x / kWave;
+
+    int g[R], e[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {  // all ids first, all map entries next: two memory round trips in total
+        const int64_t a = static_cast<int64_t>(r) * kSmallThreads + threadIdx.x;
+        g[r] = topk_idx[min(a, A - 1)];
+        if (a >= A) g[r] = -1;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const bool ok = g[r] >= 0 && g[r] < E;
+        if (expert_map != nullptr) {
+            const int m = expert_map[ok ? g[r] : 0];
+            e[r] = (ok && m >= 0 && m < E_local) ? m : -1;
+        } else {
+            e[r] = (ok && g[r] < E_local) ? g[r] : -1;
+        }
+    }
+    {
+        uint32_t* words = reinterpret_cast<uint32_t*>(&seg[0][0]);
+        for (int i = threadIdx.x; i < EXF_MAX_EXPERTS * SEG / 2; i += kSmallThreads) words[i] = 0u;
+    }
+    __syncthreads();
+
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int rank[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const unsigned long long m = same_expert_lanes(e[r], E_local);
+        rank[r] = __popcll(m & below);
+        if (e[r] >= 0 && (m & below) == 0ull) seg[e[r]][r * kSmallWaves + wave] = static_cast<unsigned short>(__popcll(m));
+    }
+    __syncthreads();
+
+    for (int q = wave; q < E_local; q += kSmallWaves) {
+        int c[PER], sum = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            c[j] = seg[q][lane * PER + j];
+            sum += c[j];
+        }
+        const int incl = wave_inclusive_scan(sum);
+        int run = incl - sum;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            seg[q][lane * PER + j] = static_cast<unsigned short>(run);
+            run += c[j];
+        }
+        if (lane == kWave - 1) total[q] = incl;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int t = lane < E_local ? total[lane] : 0;
+        const int incl = wave_inclusive_scan(t);
+        if (lane < E_local) {
+            bucket[lane] = incl - t;
+            expert_counts[lane] = t;
+            expert_offsets[lane] = incl - t;
+        }
+        if (lane == E_local - 1) expert_offsets[E_local] = incl;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t a = static_cast<int64_t>(r) * kSmallThreads + threadIdx.x;
+        if (e[r] >= 0) {
+            const int pos = bucket[e[r]] + seg[e[r]][r * kSmallWaves + wave] + rank[r];
             src_of_sorted[pos] = static_cast<int32_t>(a);
             sorted_of_src[a] = pos;
         } else if (a < A) {
@@ -418,6 +522,17 @@ static int dispatch_run(const void* x, const int32_t* topk_idx, const int32_t* e
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t* block_counts = static_cast<int32_t*>(workspace);
     const int n_blocks = static_cast<int>(dispatch_blocks(A));
+    if (A > 0 && x_sorted == nullptr && A <= static_cast<int64_t>(kSmallMaxRounds) * kSmallThreads) {
+        // index maps of a short list: one launch, the workspace stays untouched
+#define EXF_LAUNCH_SMALL(R)                                                                                                  \
+    hipLaunchKernelGGL(dispatch_small_kernel<R>, dim3(1), dim3(kSmallThreads), 0, s, topk_idx, expert_map, A, E, E_local, \
+                       expert_counts, expert_offsets, src_of_sorted, sorted_of_src)
+        if (A <= 4 * kSmallThreads) EXF_LAUNCH_SMALL(4);
+        else if (A <= 8 * kSmallThreads) EXF_LAUNCH_SMALL(8);
+        else EXF_LAUNCH_SMALL(16);
+#undef EXF_LAUNCH_SMALL
+        return check_launch("moe_dispatch");
+    }
     if (n_blocks > 0)
         hipLaunchKernelGGL(dispatch_count_kernel, dim3(n_blocks), dim3(kDispThreads), 0, s, topk_idx, expert_map, A, E, E_local,
                            block_counts);

@@ -19,9 +19,10 @@
 //     ends up with 4 consecutive output columns of one row; the epilogue transposes through LDS
 //     and stores 16-byte chunks of contiguous row segments.
 //   - workgroup -> tile order: consecutive ids go round-robin to the 8 XCDs, so id%8 selects the
-//     XCD and every XCD walks a contiguous range of tiles ordered (expert, column tile, row tile):
+//     XCD and every XCD walks contiguous ranges of tiles ordered (expert, column tile, row tile):
 //     the workgroups resident on one XCD share an expert's activation rows and a few weight
-//     panels in that XCD's L2.
+//     panels in that XCD's L2.  When that would leave an XCD much more work than the others (a
+//     short launch of tiles of different heights), every kind of tile is split evenly instead.
 //   - remainder ("tail") tiles of the second contraction are cut into K slices when there are few of
 //     them, and a small kernel adds the slices (see TileSchedule).
 // fp32 kernel: LDS-tiled 64x64x16, 4x4 outputs per thread (tiny configuration; latency bound).
@@ -112,14 +113,40 @@ constexpr int kSplitMax = 8;        // most K slices per tail tile
 // kernel that adds the slices (and applies GELU) cost more than the slices saved.
 constexpr bool kSplitFirstContraction = false;
 
-// Workgroup id -> tile index.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
-// id % 8 is the XCD and id / 8 the position in that XCD's queue; chunks of kXcdChunk consecutive
-// tiles (which share an expert's activation rows and a few weight panels) go to the same XCD and
-// therefore meet in the same L2.
-__device__ __forceinline__ int tile_index_of_workgroup(int wg)
+// Workgroup id -> work item.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, so id % 8
+// is the XCD and id / 8 the position in that XCD's queue; an XCD only ever runs its own queue.  Two
+// ways to fill the queues from the launch's list of work items (see locate_tile for its order):
+//   chunked : chunks of kXcdChunk consecutive items go to one XCD after the other.  The 32 compute
+//             units of an XCD then walk one block of tiles in step and meet its few activation and
+//             weight panels in their L2 - the faster way per tile (3 % at ten rounds of tiles).
+//   balanced: every kind of item (tall, full and tail tiles differ several-fold in duration) is split
+//             evenly over the XCDs: of the n items of a kind, XCD x takes a contiguous share of n/8,
+//             and the n%8 left over go one each to consecutive XCDs, continuing where the previous
+//             kind stopped.  With chunks, a launch of two or three rounds leaves some XCDs a whole
+//             chunk of long tiles more than others (700 against 580 us for the second contraction of
+//             a skewed 32-expert batch).
+// A launch is balanced when chunks would leave some XCD more than kChunkedMaxExcess (in 1/64) above
+// the mean work, counted in rows per item (a tail tile as half a full tile, shared by its K slices).
+constexpr int kChunkedMaxExcess = 10;  // 64/64 + 10/64 = 1.16 x the mean
+__device__ __forceinline__ int chunked_item_of_workgroup(int wg)
 {
     const int xcd = wg % kXcdCount, slot = wg / kXcdCount;
     return ((slot / kXcdChunk) * kXcdCount + xcd) * kXcdChunk + slot % kXcdChunk;
+}
+// Of the list positions [0, p), how many the chunked order gives to XCD `xcd`.
+__device__ __forceinline__ int chunked_positions_before(int p, int xcd)
+{
+    constexpr int round = kXcdCount * kXcdChunk;
+    return p / round * kXcdChunk + min(max(p % round - xcd * kXcdChunk, 0), kXcdChunk);
+}
+// Size of XCD `xcd`'s share of n items of one kind; `begin` receives its first item.
+__device__ __forceinline__ int xcd_share(int n, int xcd, int& rot, int& begin)
+{
+    const int b = n / kXcdCount, r = n % kXcdCount;
+    const int xr = (xcd - rot + kXcdCount) % kXcdCount;
+    begin = xr * b + min(xr, r);
+    rot = (rot + r) % kXcdCount;
+    return b + (xr < r ? 1 : 0);
 }
 
 // Per-expert tile counts (lane e = expert e) and their running sums; the same in every workgroup.
@@ -230,33 +257,61 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
     return true;
 }
 
-// Work item idx of a launch.  Few tail items (at most one per compute unit, K slices counted): they
-// go first, slice fastest, so that the launch ends with whole rounds of full tiles - behind the full
-// tiles the few compute units that get a tail tile at the very end would decide when the launch is
-// over.  Many tail items: they go last and fill the ragged end of the last round of full tiles.
+// Work item of workgroup `wg`.  Order of the list (of every XCD's queue, when balanced): the tall
+// tiles (longest work first); then - few tail items (at most one per compute unit, K slices counted) -
+// the tail items, slice fastest, so that the launch ends with whole rounds of full tiles (behind the
+// full tiles the few compute units that get a tail tile at the very end would decide when the launch
+// is over); then the full tiles; many tail items go last instead and fill the ragged end of the last round.
 __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles, int max_rows,
-                                            int nk, bool may_split, bool allow_tall, int idx, Tile2D& out)
+                                            int nk, bool may_split, bool allow_tall, int wg, Tile2D& out)
 {
     const TileSchedule sc = scan_experts(offsets, E_local, mt, n_tiles, max_rows, nk, may_split, allow_tall);
     out.kt_begin = 0;
     out.kt_end = nk;
     out.slot = -1;
-    if (idx < sc.total_tall) return decode_tile(sc, E_local, mt, n_tiles, kTileTall, idx, out);  // longest work first
-    idx -= sc.total_tall;
     const int tail_units = sc.total_tail * sc.split;
-    if (idx >= sc.total_full + tail_units) return false;
     const bool tails_first = tail_units <= kSplitUnits;
-    const bool tail = tails_first ? idx < tail_units : idx >= sc.total_full;
-    const int u = tails_first ? idx : idx - sc.total_full;
-    const int full_idx = tails_first ? idx - tail_units : idx;
-    if (!decode_tile(sc, E_local, mt, n_tiles, tail ? kTileTail : kTileFull, tail ? u / sc.split : full_idx, out)) return false;
-    if (tail && sc.split > 1) {
-        const int slice = u % sc.split;
-        out.kt_begin = __builtin_amdgcn_readfirstlane(slice * nk / sc.split);
-        out.kt_end = __builtin_amdgcn_readfirstlane((slice + 1) * nk / sc.split);
-        out.slot = __builtin_amdgcn_readfirstlane(u);
+    const int total = sc.total_tall + sc.total_full + tail_units;
+    const int xcd = wg % kXcdCount;
+    bool balanced = false;
+    if (total <= (1 << 20)) {  // (longer launches: a chunk more or less no longer matters, and the sums below stay in range)
+        // lane x < 8: work of XCD x under the chunked order
+        const int x = lane_id() % kXcdCount;
+        int load = 0, all = 0, p = 0;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const int kind = c == 0 ? kTileTall : ((tails_first ? c == 1 : c == 2) ? kTileTail : kTileFull);
+            const int n = kind == kTileTall ? sc.total_tall : (kind == kTileTail ? tail_units : sc.total_full);
+            const int w = kind == kTileTall ? mt + kTailRows : (kind == kTileTail ? max(mt / 2 / sc.split, 1) : mt);
+            load += w * (chunked_positions_before(p + n, x) - chunked_positions_before(p, x));
+            all += w * n;
+            p += n;
+        }
+        // some XCD above (1 + excess/64) * all/8 ?  (floats: the same rounding in every workgroup)
+        balanced = __ballot(static_cast<float>(load) * (64.0f * kXcdCount) > static_cast<float>(all) * (64.0f + kChunkedMaxExcess)) != 0ull;
     }
-    return true;
+    int pos = balanced ? wg / kXcdCount : chunked_item_of_workgroup(wg);  // in the XCD's queue / in the list
+    if (!balanced && pos >= total) return false;
+    int rot = 0, begin = 0;
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        const int kind = c == 0 ? kTileTall : ((tails_first ? c == 1 : c == 2) ? kTileTail : kTileFull);
+        const int n = kind == kTileTall ? sc.total_tall : (kind == kTileTail ? tail_units : sc.total_full);
+        const int share = balanced ? xcd_share(n, xcd, rot, begin) : n;
+        if (pos < share) {
+            const int u = begin + pos;
+            if (!decode_tile(sc, E_local, mt, n_tiles, kind, kind == kTileTail ? u / sc.split : u, out)) return false;
+            if (kind == kTileTail && sc.split > 1) {
+                const int slice = u % sc.split;
+                out.kt_begin = __builtin_amdgcn_readfirstlane(slice * nk / sc.split);
+                out.kt_end = __builtin_amdgcn_readfirstlane((slice + 1) * nk / sc.split);
+                out.slot = __builtin_amdgcn_readfirstlane(u);
+            }
+            return true;
+        }
+        pos -= share;
+    }
+    return false;
 }
 
 // ---------------------------------------------------------------------------- bf16 MFMA kernel
@@ -682,7 +737,7 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
     const int n_tiles = (N + NT - 1) / NT;
     constexpr bool TALL = tall_tiles_supported(MT, NT, KT, STAGES, WM);
     if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, K / KT, partial != nullptr && MT > kTailRows, TALL,
-                     tile_index_of_workgroup(blockIdx.x), tile))
+                     static_cast<int>(blockIdx.x), tile))
         return;
     timeline_stamp(map, 1);
     if (map.timeline != nullptr && threadIdx.x == 0 && static_cast<int>(blockIdx.x) < map.timeline_cap) {

@@ -132,6 +132,26 @@ def test_dispatch_expert_map_invalid_and_degenerate(oracle):
     _run_dispatch(oracle, x, tr[0].reshape(-1, 1).copy(), 32, 32, None, "bf16")
 
 
+@pytest.mark.parametrize("A,E,E_local", [(4096, 8, 8), (4097, 64, 64), (8192, 8, 8), (8193, 3, 3), (16384, 64, 8), (16385, 64, 8),
+                                         (65, 64, 64), (9000, 1, 1)])
+def test_dispatch_index_only_short_lists(oracle, A, E, E_local):
+    """Index-only dispatch around the sizes where the single-launch kernel changes its round count
+    and hands over to the chunked kernels: the same unique stable permutation on both sides."""
+    _say(f"dispatch index-only A={A} E={E} E_local={E_local}")
+    g = syn.rng(320 + A)
+    idx = g.integers(0, E, size=(A, 1)).astype(np.int32)
+    idx[g.integers(0, A, size=5)] = -3  # a few entries outside [0,E)
+    expert_map = None
+    if E_local < E:
+        expert_map = np.full(E, -1, dtype=np.int32)
+        expert_map[g.permutation(E)[:E_local]] = np.arange(E_local, dtype=np.int32)
+    ref = oracle.dispatch(idx, expert_map, E, E_local)
+    x = torch.zeros((A, 8), dtype=torch.bfloat16, device=DEV)
+    for _ in range(2):  # twice: nothing is carried from one call to the next
+        res = exf.moe_dispatch(x, dev_i32(idx), E, E_local, None if expert_map is None else dev_i32(expert_map), gather=False)
+        expected_dispatch_compare(res, ref, A)
+
+
 def test_dispatch_empty_batch():
     x = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
     idx = torch.empty((0, 1), dtype=torch.int32, device=DEV)
