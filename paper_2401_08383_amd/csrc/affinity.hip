@@ -13,9 +13,9 @@
 //             Workgroups of one token chunk are mapped to one XCD, so the column shared by two
 //             neighbouring pair groups is served by that XCD's L2.
 //   finalize: one wavefront per (pair, source expert) row sums the partials over the chunks
-//             into int64 counts, forms the row sum, the layer loads and the conditional
-//             probabilities; extra workgroups of the same launch derive the loads of the final layer
-//             and the invalid tally.
+//             into int64 counts, forms the row sum (a wavefront reduction: no LDS, no barrier), the
+//             layer loads and the conditional probabilities; extra workgroups of the same launch
+//             derive the loads of the final layer and the invalid tally.
 //   Entries outside [0,E) are tallied; a transition touching one is not binned, but the valid
 //   end still counts towards its layer's load through small "orphan" histograms.
 //
@@ -365,12 +365,14 @@ __global__ __launch_bounds__(kTraceThreads) void multihop_partial_kernel(const i
     }
 }
 
-// Workgroups of 256 threads.  The first (L-1)*E take one (pair l, source expert i) row each:
-// wavefront w sums the chunks c = w, w+4, ... of bin (i, p = lane), the four partial sums meet in
-// LDS -> counts, row sum, load of (l, i), conditional probabilities.  The next E workgroups take one
+// Workgroups of 256 threads.  The first ceil((L-1)*E / 4) give every wavefront one (pair l, source
+// expert i) row: lane p sums bin (i, p) over all chunks (16 independent loads in flight), the row sum
+// is a wavefront reduction -> counts, load of (l, i), conditional probabilities; nothing goes through
+// LDS and no workgroup barrier is needed.  The next E workgroups take one
 // expert p of the FINAL layer each: its load is the column sum of the last pair (taken from the
 // partials, so that no result of another workgroup is needed) plus the orphans.  One workgroup
 // adds up the invalid tally.  With a placement, L-1 more workgroups form the locality numerators.
+constexpr int kFinRowsPerWorkgroup = 4;
 __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* __restrict__ part_counts,
                                                                 const uint32_t* __restrict__ part_orphan_next,
                                                                 const uint32_t* __restrict__ part_orphan_last,
@@ -380,15 +382,17 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
                                                                 const uint32_t* __restrict__ part_local,  // [C][L-1] or null
                                                                 int64_t* __restrict__ local)              // [L-1] (with part_local)
 {
-    __shared__ long long red[4][kWave];
     __shared__ long long orphan_red[4];
     const int pairs = L - 1;
     const int p = lane_id();
     const int w = threadIdx.x / kWave;
-    const int row_blocks = pairs * E;
+    const int rows = pairs * E;
+    const int row_blocks = (rows + kFinRowsPerWorkgroup - 1) / kFinRowsPerWorkgroup;
     if (static_cast<int>(blockIdx.x) < row_blocks) {
-        const int l = blockIdx.x / E;
-        const int i = blockIdx.x % E;
+        const int row = static_cast<int>(blockIdx.x) * kFinRowsPerWorkgroup + w;
+        if (row >= rows) return;  // (whole wavefronts; no barrier follows)
+        const int l = row / E;
+        const int i = row % E;
         long long cnt = 0;
         if (p < E) {
             const int bin = i * E + p;
@@ -396,34 +400,27 @@ __global__ __launch_bounds__(256) void affinity_finalize_kernel(const uint32_t* 
             const uint32_t* src = part_counts + static_cast<size_t>(l) * words + (bin >> 1);
             const size_t step = static_cast<size_t>(pairs) * words;
             // 16 independent loads in flight (clamped, never branched around)
-            for (int c0 = w; c0 < C; c0 += 4 * 16) {
+            for (int c0 = 0; c0 < C; c0 += 16) {
                 uint32_t v[16];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) v[u] = src[min(c0 + 4 * u, C - 1) * step];
+                for (int u = 0; u < 16; ++u) v[u] = src[min(c0 + u, C - 1) * step];
 #pragma unroll
                 for (int u = 0; u < 16; ++u)
-                    if (c0 + 4 * u < C) cnt += (v[u] >> shift) & 0xffffu;
+                    if (c0 + u < C) cnt += (v[u] >> shift) & 0xffffu;
             }
         }
         long long orphan = 0;
         if (loads != nullptr)  // (the multi-hop statistic has no orphan tallies)
-            for (int c = threadIdx.x; c < C; c += 256) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
+            for (int c = p; c < C; c += kWave) orphan += part_orphan_next[(static_cast<size_t>(c) * pairs + l) * E + i];
         orphan = wave_sum(orphan);
-        red[w][p] = cnt;
-        if (p == 0) orphan_red[w] = orphan;
-        __syncthreads();
-        if (w == 0) {
-            cnt = red[0][p] + red[1][p] + red[2][p] + red[3][p];
-            const long long row = wave_sum(cnt);
-            if (p < E) {
-                const size_t o = (static_cast<size_t>(l) * E + i) * E + p;
-                counts[o] = cnt;
-                if (cond_prob != nullptr)
-                    cond_prob[o] = row > 0 ? static_cast<float>(static_cast<double>(cnt) / static_cast<double>(row)) : 0.0f;
-            }
-            if (loads != nullptr && p == 0)
-                loads[static_cast<size_t>(l) * E + i] = row + orphan_red[0] + orphan_red[1] + orphan_red[2] + orphan_red[3];
+        const long long row_sum = wave_sum(cnt);
+        if (p < E) {
+            const size_t o = (static_cast<size_t>(l) * E + i) * E + p;
+            counts[o] = cnt;
+            if (cond_prob != nullptr)
+                cond_prob[o] = row_sum > 0 ? static_cast<float>(static_cast<double>(cnt) / static_cast<double>(row_sum)) : 0.0f;
         }
+        if (loads != nullptr && p == 0) loads[static_cast<size_t>(l) * E + i] = row_sum + orphan;
     } else if (static_cast<int>(blockIdx.x) < row_blocks + E) {
         if (loads == nullptr) return;
         const int pe = blockIdx.x - row_blocks;  // expert of the final layer
@@ -668,7 +665,8 @@ static int run_affinity(const char* fn, const int32_t* trace, const int32_t* pla
     }
     // rows of all pairs, then the loads of the final layer, the invalid tally and (with a placement) the
     // locality numerators of all pairs
-    const unsigned fin_grid = static_cast<unsigned>((L - 1) * E + E + 1 + (placement != nullptr ? L - 1 : 0));
+    const unsigned fin_grid = static_cast<unsigned>(((L - 1) * E + kFinRowsPerWorkgroup - 1) / kFinRowsPerWorkgroup + E + 1 +
+                                                   (placement != nullptr ? L - 1 : 0));
     hipLaunchKernelGGL(affinity_finalize_kernel, dim3(fin_grid), dim3(256), 0, s, part_counts, part_orphan_next, part_orphan_last,
                        part_invalid, p.C, p.Q, L, E, p.words, counts, loads, cond_prob, n_invalid, part_local, local_per_pair);
     return check_launch(fn);
@@ -781,9 +779,9 @@ extern "C" int affinity_multihop(const int32_t* trace, int L, int64_t N, int E, 
                                p.g, p.Q, p.copies, p.words, p.chunk, p.C, part_counts);
         }
     }
-    // one workgroup per (pair, source expert) row: sums the chunks, forms the conditional probabilities
+    // one wavefront per (pair, source expert) row: sums the chunks, forms the conditional probabilities
     // (the finalize kernel of the one-hop statistic, told that there are pairs+1 "layers" and no loads)
-    const unsigned fin_grid = static_cast<unsigned>(p.pairs * E);
+    const unsigned fin_grid = static_cast<unsigned>((p.pairs * E + kFinRowsPerWorkgroup - 1) / kFinRowsPerWorkgroup);
     hipLaunchKernelGGL(affinity_finalize_kernel, dim3(fin_grid), dim3(256), 0, s, part_counts, nullptr, nullptr, nullptr, p.C, 1,
                        p.pairs + 1, E, p.words, counts, nullptr, cond_prob, nullptr, nullptr, nullptr);
     return check_launch("affinity_multihop");

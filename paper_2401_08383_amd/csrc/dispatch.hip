@@ -225,7 +225,6 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(const int
     static_assert(SEG % kWave == 0 && R <= kSmallMaxRounds, "segment scan layout");
     __shared__ unsigned short seg[EXF_MAX_EXPERTS][SEG];  // count, then start, of a segment inside its expert's bucket (<= 16384)
     __shared__ int total[EXF_MAX_EXPERTS];
-    __shared__ int bucket[EXF_MAX_EXPERTS];
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
 
@@ -234,11 +233,16 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(const int
     for (int r = 0; r < R; ++r) {  // all ids first, all map entries next: two memory round trips in total
         const int64_t a = static_cast<int64_t>(r) * kSmallThreads + threadIdx.x;
         g[r] = topk_idx[min(a, A - 1)];
-        if (a >= A) g[r] = -1;
     }
+    {   // (cleared while the ids are on their way)
+        uint32_t* words = reinterpret_cast<uint32_t*>(&seg[0][0]);
+        for (int i = threadIdx.x; i < EXF_MAX_EXPERTS * SEG / 2; i += kSmallThreads) words[i] = 0u;
+    }
+    __syncthreads();
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const bool ok = g[r] >= 0 && g[r] < E;
+        const int64_t a = static_cast<int64_t>(r) * kSmallThreads + threadIdx.x;
+        const bool ok = a < A && g[r] >= 0 && g[r] < E;
         if (expert_map != nullptr) {
             const int m = expert_map[ok ? g[r] : 0];
             e[r] = (ok && m >= 0 && m < E_local) ? m : -1;
@@ -246,11 +250,6 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(const int
             e[r] = (ok && g[r] < E_local) ? g[r] : -1;
         }
     }
-    {
-        uint32_t* words = reinterpret_cast<uint32_t*>(&seg[0][0]);
-        for (int i = threadIdx.x; i < EXF_MAX_EXPERTS * SEG / 2; i += kSmallThreads) words[i] = 0u;
-    }
-    __syncthreads();
 
     const unsigned long long below = (1ull << lane) - 1ull;
     int rank[R];
@@ -279,23 +278,24 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(const int
         if (lane == kWave - 1) total[q] = incl;
     }
     __syncthreads();
+    // every wavefront scans the totals for itself: lane q then holds the start of expert q's bucket
+    const int t = lane < E_local ? total[lane] : 0;
+    const int incl = wave_inclusive_scan(t);
+    const int bucket = incl - t;
     if (wave == 0) {
-        const int t = lane < E_local ? total[lane] : 0;
-        const int incl = wave_inclusive_scan(t);
         if (lane < E_local) {
-            bucket[lane] = incl - t;
             expert_counts[lane] = t;
-            expert_offsets[lane] = incl - t;
+            expert_offsets[lane] = bucket;
         }
         if (lane == E_local - 1) expert_offsets[E_local] = incl;
     }
-    __syncthreads();
 
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int64_t a = static_cast<int64_t>(r) * kSmallThreads + threadIdx.x;
+        const int start = __shfl(bucket, max(e[r], 0));  // (all lanes take part: a shuffle reads active lanes only)
         if (e[r] >= 0) {
-            const int pos = bucket[e[r]] + seg[e[r]][r * kSmallWaves + wave] + rank[r];
+            const int pos = start + seg[e[r]][r * kSmallWaves + wave] + rank[r];
             src_of_sorted[pos] = static_cast<int32_t>(a);
             sorted_of_src[a] = pos;
         } else if (a < A) {
