@@ -87,6 +87,20 @@ __host__ __device__ constexpr bool tall_tiles_supported(int mt, int nt, int kt, 
            stages * (mt + kTailRows + nt) * kt * 2 <= kLdsBytes;
 }
 
+// LDS of a launch: the ring of STAGES stages of the tallest tile, and behind it (two-stage rings, if it
+// still fits) a scratch area for the row ids of gathered activation rows: 256 bytes per wavefront-wide
+// load of the tallest tile.
+__host__ __device__ constexpr int ring_bytes(int mt, int nt, int kt, int stages, int wm)
+{
+    return stages * (mt + (tall_tiles_supported(mt, nt, kt, stages, wm) ? kTailRows : 0) + nt) * kt * 2;
+}
+__host__ __device__ constexpr int row_id_scratch_bytes(int mt, int nt, int kt, int stages, int wm, int waves)
+{
+    const int rows = mt + (tall_tiles_supported(mt, nt, kt, stages, wm) ? kTailRows : 0);
+    const int bytes = rows / (1024 / (kt * 2)) * 256;  // one 256-byte line per load of 1024/(2 kt) rows
+    return (stages == 2 && rows % (1024 / (kt * 2) * waves) == 0 && ring_bytes(mt, nt, kt, stages, wm) + bytes <= kLdsBytes) ? bytes : 0;
+}
+
 struct Tile2D {
     int expert;
     int row_begin, row_end;
@@ -348,6 +362,17 @@ __device__ __forceinline__ void lds_dma_16B(const unsigned char* base, uint32_t 
 #endif
 }
 
+// One wavefront-wide direct-to-LDS load of 4 bytes per lane: lane i fetches base + voff and the word
+// lands at LDS byte address lds_addr + 4*i.
+__device__ __forceinline__ void lds_dma_4B(const unsigned char* base, uint32_t voff, uint32_t lds_addr)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1\n" : : "v"(voff), "s"(base), "s"(lds_addr) : "memory");
+#else
+    (void)base; (void)voff; (void)lds_addr;
+#endif
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
@@ -396,7 +421,7 @@ template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int EPI, 
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const bf16_t* __restrict__ wexp,
                                           const bf16_t* __restrict__ bias_e, int row_begin, int row_end, int n0, int K, int N,
                                           bf16_t* __restrict__ out, unsigned char* smem, const RowMap& map, int kt_begin,
-                                          int kt_end, float4* __restrict__ partial)
+                                          int kt_end, float4* __restrict__ partial, int ids_off = -1)
 {
     constexpr int NWAVES = WM * WN;
     constexpr int RB = KT * 2;              // bytes per tile row
@@ -423,15 +448,25 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     // byte offsets from the two (uniform) base pointers.
     constexpr int LA = MT / RPI / NWAVES, LW = NT / RPI / NWAVES;
     static_assert(LA * RPI * NWAVES == MT && LW * RPI * NWAVES == NT, "tile rows must split evenly over the wavefronts");
+    // Gathered activation rows need their row ids first - a dependent load in front of the tile's
+    // first loads.  With a two-stage ring and a scratch area behind it (ids_off >= 0) the ids are
+    // fetched straight into LDS, the weight loads of both stages are issued behind them, and the ids
+    // are read back once only the weight loads are outstanding: ids and weights travel together.
+    // (Through a register the id load would be awaited with vmcnt(0), i.e. together with the weights.)
+    const bool ids_via_lds = STAGES == 2 && map.a_row != nullptr && ids_off >= 0;
     uint32_t off_a[LA], off_w[LW];
+    auto set_off_a = [&](bool from_lds) {
 #pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        const int row = (wave * LA + i) * RPI + lane / CPR;
-        const int chunk = (lane % CPR) ^ chunk_swizzle<KT, SWZ>(row);
-        int r = min(row_begin + row, row_end - 1);  // rows past the tile end re-read the last valid row
-        if (map.a_row != nullptr) r = map.a_row[r] / map.a_div;
-        off_a[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
-    }
+        for (int i = 0; i < LA; ++i) {
+            const int row = (wave * LA + i) * RPI + lane / CPR;
+            const int chunk = (lane % CPR) ^ chunk_swizzle<KT, SWZ>(row);
+            int r = min(row_begin + row, row_end - 1);  // rows past the tile end re-read the last valid row
+            if (from_lds) r = *reinterpret_cast<const int*>(smem + ids_off + (wave * LA + i) * 256 + lane * 4) / map.a_div;
+            else if (map.a_row != nullptr) r = map.a_row[r] / map.a_div;
+            off_a[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
+        }
+    };
+    if (!ids_via_lds) set_off_a(false);
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
         const int row = (wave * LW + i) * RPI + lane / CPR;
@@ -495,10 +530,40 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     // slots, and the (slow to issue) direct-to-LDS loads go one at a time behind the slots that
     // follow a hand-over.
     static_assert(KSTEPS % 2 == 0, "register double-buffering assumes an even number of K steps per K tile");
+    if (ids_via_lds) {
+        if constexpr (STAGES == 2) {
+            const int n_first = min(nk, 2);
+            const unsigned char* ids_b = uniform_ptr(reinterpret_cast<const unsigned char*>(map.a_row));
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const int row = (wave * LA + i) * RPI + lane / CPR;
+                lds_dma_4B(ids_b, static_cast<uint32_t>(min(row_begin + row, row_end - 1)) * 4u,
+                           smem_addr + static_cast<uint32_t>(ids_off) + (wave * LA + i) * 256);
+            }
+            for (int s = 0; s < n_first; ++s) {
+                const uint32_t stage = smem_addr + s * STAGE_BYTES;
+#pragma unroll
+                for (int i = 0; i < LW; ++i)
+                    lds_dma_16B(wgt_b + static_cast<size_t>(s) * (KT * 2), off_w[i], stage + MT * RB + (wave * LW + i) * 1024);
+            }
+            if (n_first == 2) wait_vmcnt<2 * LW>();  // loads land in order: the ids are in LDS
+            else wait_vmcnt<LW>();
+            set_off_a(true);
+            for (int s = 0; s < n_first; ++s) {
+                const uint32_t stage = smem_addr + s * STAGE_BYTES;
+#pragma unroll
+                for (int i = 0; i < LA; ++i)
+                    lds_dma_16B(act_b + static_cast<size_t>(s) * (KT * 2), off_a[i], stage + (wave * LA + i) * 1024);
+            }
+            if (n_first == 2) wait_vmcnt<LA>();  // K tile 0 complete; the activation rows of K tile 1 may be in flight
+            else wait_vmcnt<0>();
+        }
+    } else {
 #pragma unroll
     for (int s = 0; s < STAGES; ++s)
         if (s < nk) issue(s);
-    {
+    }
+    if (!ids_via_lds) {
         const int younger = min(nk, STAGES) - 1;
         static_assert(STAGES >= 2 && STAGES <= 8 && (STAGES - 1) * LPW < 64, "pipeline depth against the 6-bit vmcnt");
         if (STAGES >= 8 && younger >= 7) wait_vmcnt<(STAGES >= 8 ? 7 : 0) * LPW>();
@@ -736,6 +801,7 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
     Tile2D tile;
     const int n_tiles = (N + NT - 1) / NT;
     constexpr bool TALL = tall_tiles_supported(MT, NT, KT, STAGES, WM);
+    constexpr int kIdsOff = row_id_scratch_bytes(MT, NT, KT, STAGES, WM, WM * WN) > 0 ? ring_bytes(MT, NT, KT, STAGES, WM) : -1;
     if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, K / KT, partial != nullptr && MT > kTailRows, TALL,
                      static_cast<int>(blockIdx.x), tile))
         return;
@@ -758,10 +824,10 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
         if constexpr (TALL)
             gemm_tile<MT + kTailRows, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS, false>(act, wexp, bias_e, tile.row_begin, tile.row_end,
                                                                                      tile.n_tile * NT, K, N, out, smem, map, 0, K / KT,
-                                                                                     nullptr);
+                                                                                     nullptr, kIdsOff);
     } else if (!tile.tail || MT <= kTailRows) {
         gemm_tile<MT, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS, false>(act, wexp, bias_e, tile.row_begin, tile.row_end,
-                                                                     tile.n_tile * NT, K, N, out, smem, map, 0, K / KT, nullptr);
+                                                                     tile.n_tile * NT, K, N, out, smem, map, 0, K / KT, nullptr, kIdsOff);
     } else if constexpr (MT > kTailRows) {
         // remainder rows: the wavefronts side by side over the columns, kTailRows rows each (two rows
         // of wavefronts when a column strip would become narrower than one MFMA tile).  A
@@ -931,7 +997,7 @@ template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int OCC>
 static int launch_bf16(const void* act, const int32_t* offsets, const void* weight, const void* bias, int64_t A, int K, int N,
                        int E_local, int epi, void* out, hipStream_t stream, const RowMap& map = RowMap{}, void* partial = nullptr)
 {
-    constexpr size_t lds = static_cast<size_t>(STAGES) * (MT + (tall_tiles_supported(MT, NT, KT, STAGES, WM) ? kTailRows : 0) + NT) * KT * 2;
+    constexpr size_t lds = static_cast<size_t>(ring_bytes(MT, NT, KT, STAGES, WM)) + row_id_scratch_bytes(MT, NT, KT, STAGES, WM, WM * WN);
     static_assert(NT <= kSplitMaxCols, "a partial-sum slot holds kTailRows x kSplitMaxCols values");
     // worst case: A/MT unmasked row tiles plus, for every expert, its tail tiles or one masked tile;
     // cutting tail tiles into K slices adds fewer than kSplitUnits work items
