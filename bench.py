@@ -302,7 +302,7 @@ def timeline_report(syn, torch, B, index, dev):
             if not m.any():
                 continue
             nk = np.unique((r[m, 6] >> 48) & 0xffff).tolist()
-            ph = {"lookup": r[m, 1] - r[m, 0], "first K tile": r[m, 2] - r[m, 1], "K loop": r[m, 3] - r[m, 2], "epilogue": r[m, 4] - r[m, 3],
+            ph = {"row ranges": r[m, 7] - r[m, 0], "lookup": r[m, 1] - r[m, 0], "first K tile": r[m, 2] - r[m, 1], "K loop": r[m, 3] - r[m, 2], "epilogue": r[m, 4] - r[m, 3],
                   "total": r[m, 4] - r[m, 0]}
             print(f"  {kn} tiles: {int(m.sum())}, K tiles per work item {nk}, starts {(r[m, 0].min() - t0) * us:.1f}..{(r[m, 0].max() - t0) * us:.1f} us, "
                   f"ends {(r[m, 4].min() - t0) * us:.1f}..{(r[m, 4].max() - t0) * us:.1f} us")

@@ -36,7 +36,8 @@ extern "C" {
  *                   capacity write nothing): [0] start, [1] tile located, [2] first K tile landed,
  *                   [3] K loop done, [4] end or 0 if the workgroup had no tile - all in ticks of the
  *                   constant 100 MHz device clock -, [5] hardware id, [6] tile kind (0 full, 1 remainder,
- *                   2 tall) | expert << 8 | column tile << 16 | rows << 32 | K tiles << 48.
+ *                   2 tall) | expert << 8 | column tile << 16 | rows << 32 | K tiles << 48, [7] the experts'
+ *                   row ranges have arrived (same clock; between [0] and [1]).
  * ------------------------------------------------------------------------------------- */
 int exf_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 int exf_probe_mfma(int workgroups, int iters, float* out, void* stream);

@@ -87,6 +87,32 @@ __host__ __device__ constexpr bool tall_tiles_supported(int mt, int nt, int kt, 
            stages * (mt + kTailRows + nt) * kt * 2 <= kLdsBytes;
 }
 
+// Optional row indirections of the bf16 grouped GEMM; all members null / zero = sorted rows on both sides.
+// They let the contraction read the tokens where they lie (no sorted copy of the activations) and
+// let the second contraction of a top-1 layer write the gate-weighted result straight to the
+// token's own row (no sorted copy of the outputs, no separate combine pass).
+struct RowMap {
+    const int32_t* a_row;     // operand row of sorted row s is a_row[s] / a_div        (null: row s)
+    int a_div;
+    const int32_t* out_row;   // output row of sorted row s is out_row[s]; every output row is the
+    const float* out_scale;   //   target of at most one s and is scaled by out_scale[out_row[s]] in
+                              //   fp32 before the single rounding to bf16              (null: row s, no scale)
+    const int32_t* unrouted;  // [n_unrouted]: output row t with unrouted[t] < 0 is set to zero
+    int n_unrouted;
+    // Measurement only (exf_probe_ffn_timeline; null in every other call): workgroup b < timeline_cap
+    // writes eight 64-bit words - [0] start, [1] tile located, [2] first K tile landed, [3] K loop done,
+    // [4] end (all on the constant 100 MHz clock), [5] hardware id, [6] tile kind / expert / column tile /
+    // rows / K tiles, [7] the experts' row ranges have arrived (between [0] and [1]).
+    unsigned long long* timeline;
+    int timeline_cap;
+};
+
+__device__ __forceinline__ void timeline_stamp(const RowMap& map, int slot)
+{
+    if (map.timeline != nullptr && threadIdx.x == 0 && static_cast<int>(blockIdx.x) < map.timeline_cap)
+        map.timeline[static_cast<size_t>(blockIdx.x) * 8 + slot] = wall_clock64();
+}
+
 // LDS of a launch: the ring of STAGES stages of the tallest tile, and behind it (two-stage rings, if it
 // still fits) a scratch area for the row ids of gathered activation rows: 256 bytes per wavefront-wide
 // load of the tallest tile.
@@ -144,22 +170,23 @@ constexpr bool kSplitFirstContraction = false;
 constexpr int kChunkedMaxExcess = 10;  // 64/64 + 10/64 = 1.16 x the mean
 __device__ __forceinline__ int chunked_item_of_workgroup(int wg)
 {
-    const int xcd = wg % kXcdCount, slot = wg / kXcdCount;
-    return ((slot / kXcdChunk) * kXcdCount + xcd) * kXcdChunk + slot % kXcdChunk;
+    const unsigned xcd = static_cast<unsigned>(wg) % kXcdCount, slot = static_cast<unsigned>(wg) / kXcdCount;
+    return static_cast<int>(((slot / kXcdChunk) * kXcdCount + xcd) * kXcdChunk + slot % kXcdChunk);
 }
 // Of the list positions [0, p), how many the chunked order gives to XCD `xcd`.
 __device__ __forceinline__ int chunked_positions_before(int p, int xcd)
 {
-    constexpr int round = kXcdCount * kXcdChunk;
-    return p / round * kXcdChunk + min(max(p % round - xcd * kXcdChunk, 0), kXcdChunk);
+    constexpr unsigned round = kXcdCount * kXcdChunk;
+    const unsigned up = static_cast<unsigned>(p);
+    return static_cast<int>(up / round) * kXcdChunk + min(max(static_cast<int>(up % round) - xcd * kXcdChunk, 0), kXcdChunk);
 }
 // Size of XCD `xcd`'s share of n items of one kind; `begin` receives its first item.
 __device__ __forceinline__ int xcd_share(int n, int xcd, int& rot, int& begin)
 {
-    const int b = n / kXcdCount, r = n % kXcdCount;
-    const int xr = (xcd - rot + kXcdCount) % kXcdCount;
+    const int b = static_cast<int>(static_cast<unsigned>(n) / kXcdCount), r = static_cast<int>(static_cast<unsigned>(n) % kXcdCount);
+    const int xr = (xcd - rot) & (kXcdCount - 1);
     begin = xr * b + min(xr, r);
-    rot = (rot + r) % kXcdCount;
+    rot = (rot + r) & (kXcdCount - 1);
     return b + (xr < r ? 1 : 0);
 }
 
@@ -183,7 +210,8 @@ struct TileSchedule {
 };
 
 __device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles,
-                                                     int max_rows, int nk, bool may_split, bool allow_tall)
+                                                     int max_rows, int nk, bool may_split, bool allow_tall,
+                                                     const RowMap* probe = nullptr)
 {
     TileSchedule sc;
     const int lane = lane_id();
@@ -194,6 +222,9 @@ __device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__
         sc.hi = min(max(offsets[lane + 1], sc.lo), max_rows);
     }
     const int cnt = sc.hi - sc.lo;
+    if (probe != nullptr && probe->timeline != nullptr) {  // measurement only: when did the row ranges arrive?
+        if (__ballot(cnt >= 0) != 0ull) timeline_stamp(*probe, 7);
+    }
     const int q = cnt / mt;
     const int need = (cnt - q * mt + kTailRows - 1) / kTailRows;  // 64-row blocks of the remainder
     bool use_tall = false;
@@ -217,9 +248,31 @@ __device__ __forceinline__ TileSchedule scan_experts(const int32_t* __restrict__
         sc.total_tall = wave_read_lane(sc.tall_incl, kWave - 1);
     }
     int split = 1;
-    if (may_split && sc.total_tail > 0) split = max(1, min(min(kSplitUnits / sc.total_tail, nk / kSplitMinKTiles), kSplitMax));
+    if (may_split && sc.total_tail > 0) {  // the largest s <= kSplitMax with s * total_tail <= kSplitUnits and s * kSplitMinKTiles <= nk
+#pragma unroll
+        for (int c = 2; c <= kSplitMax; ++c)
+            if (c * sc.total_tail <= kSplitUnits && c * kSplitMinKTiles <= nk) split = c;
+    }
     sc.split = __builtin_amdgcn_readfirstlane(split);
     return sc;
+}
+
+// Quotient of two wavefront-uniform non-negative numbers.  A division by a run-time value costs a
+// reciprocal sequence of some twenty dependent instructions, and the lookup ran ten of them per tile;
+// the divisors here are powers of two in the common shapes (column tiles per row, rows left over).
+__device__ __forceinline__ unsigned uniform_udiv(unsigned a, unsigned d)
+{
+    if ((d & (d - 1u)) == 0u) return a >> (31 - __builtin_clz(d | 1u));  // d = 2^k (d = 0 never occurs)
+    return a / d;
+}
+// a / d for 1 <= d <= 8 and a < 8192: multiplication by ceil(2^16 / d), exact in that range.
+__device__ __forceinline__ unsigned udiv_small(unsigned a, unsigned d)
+{
+    const unsigned long long lo = (32768ull << 16) | (21846ull << 32) | (16384ull << 48);              // d = 2..4 (d = 1 is handled apart)
+    const unsigned long long hi = 13108ull | (10923ull << 16) | (9363ull << 32) | (8192ull << 48);     // d = 5..8
+    if (d <= 1u) return a;
+    const unsigned recip = static_cast<unsigned>(((d <= 4u ? lo : hi) >> (16u * ((d - 1u) & 3u))) & 0xffffull);
+    return (a * recip) >> 16;
 }
 
 // Tile j of one kind (kTileFull, kTileTail, kTileTall) -> expert, rows, column tile.
@@ -245,17 +298,18 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
     // follow each other.  Remaining row tiles (and small experts) run row tile fastest.
     constexpr int kBlockRows = 4, kBlockCols = kXcdChunk / kBlockRows;
     int row_tile, col_tile;
-    const int blocked_rows = (kind == kTileFull && n_tiles % kBlockCols == 0) ? e_rt / kBlockRows * kBlockRows : 0;
+    const int blocked_rows = (kind == kTileFull && (n_tiles & (kBlockCols - 1)) == 0) ? (e_rt & ~(kBlockRows - 1)) : 0;
     if (r < blocked_rows * n_tiles) {
-        const int per_row_block = kBlockRows * n_tiles;
-        const int rbk = r / per_row_block, in_rb = r - rbk * per_row_block;
-        const int cb = in_rb / (kBlockRows * kBlockCols), in_b = in_rb - cb * (kBlockRows * kBlockCols);
-        col_tile = cb * kBlockCols + in_b / kBlockRows;
-        row_tile = rbk * kBlockRows + in_b % kBlockRows;
+        const unsigned per_row_block = static_cast<unsigned>(kBlockRows * n_tiles);
+        const unsigned rbk = uniform_udiv(static_cast<unsigned>(r), per_row_block), in_rb = static_cast<unsigned>(r) - rbk * per_row_block;
+        const unsigned cb = in_rb / (kBlockRows * kBlockCols), in_b = in_rb % (kBlockRows * kBlockCols);
+        col_tile = static_cast<int>(cb * kBlockCols + in_b / kBlockRows);
+        row_tile = static_cast<int>(rbk * kBlockRows + in_b % kBlockRows);
     } else {
-        const int rr = r - blocked_rows * n_tiles, rows_left = e_rt - blocked_rows;
-        col_tile = rr / rows_left;
-        row_tile = blocked_rows + rr % rows_left;
+        const unsigned rr = static_cast<unsigned>(r - blocked_rows * n_tiles), rows_left = static_cast<unsigned>(e_rt - blocked_rows);
+        const unsigned c = uniform_udiv(rr, rows_left);
+        col_tile = static_cast<int>(c);
+        row_tile = blocked_rows + static_cast<int>(rr - c * rows_left);
     }
     // rows of an expert: its full tiles, then its tall tiles (or its tail tiles)
     const int begin = tail ? e_lo + e_full * mt + row_tile * kTailRows
@@ -277,16 +331,17 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
 // full tiles the few compute units that get a tail tile at the very end would decide when the launch
 // is over); then the full tiles; many tail items go last instead and fill the ragged end of the last round.
 __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets, int E_local, int mt, int n_tiles, int max_rows,
-                                            int nk, bool may_split, bool allow_tall, int wg, Tile2D& out)
+                                            int nk, bool may_split, bool allow_tall, int wg, Tile2D& out,
+                                            const RowMap* probe = nullptr)
 {
-    const TileSchedule sc = scan_experts(offsets, E_local, mt, n_tiles, max_rows, nk, may_split, allow_tall);
+    const TileSchedule sc = scan_experts(offsets, E_local, mt, n_tiles, max_rows, nk, may_split, allow_tall, probe);
     out.kt_begin = 0;
     out.kt_end = nk;
     out.slot = -1;
     const int tail_units = sc.total_tail * sc.split;
     const bool tails_first = tail_units <= kSplitUnits;
     const int total = sc.total_tall + sc.total_full + tail_units;
-    const int xcd = wg % kXcdCount;
+    const int xcd = static_cast<int>(static_cast<unsigned>(wg) % kXcdCount);
     bool balanced = false;
     if (total <= (1 << 20)) {  // (longer launches: a chunk more or less no longer matters, and the sums below stay in range)
         // lane x < 8: work of XCD x under the chunked order
@@ -304,7 +359,7 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
         // some XCD above (1 + excess/64) * all/8 ?  (floats: the same rounding in every workgroup)
         balanced = __ballot(static_cast<float>(load) * (64.0f * kXcdCount) > static_cast<float>(all) * (64.0f + kChunkedMaxExcess)) != 0ull;
     }
-    int pos = balanced ? wg / kXcdCount : chunked_item_of_workgroup(wg);  // in the XCD's queue / in the list
+    int pos = balanced ? static_cast<int>(static_cast<unsigned>(wg) / kXcdCount) : chunked_item_of_workgroup(wg);  // in the XCD's queue / in the list
     if (!balanced && pos >= total) return false;
     int rot = 0, begin = 0;
 #pragma unroll
@@ -314,9 +369,11 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
         const int share = balanced ? xcd_share(n, xcd, rot, begin) : n;
         if (pos < share) {
             const int u = begin + pos;
-            if (!decode_tile(sc, E_local, mt, n_tiles, kind, kind == kTileTail ? u / sc.split : u, out)) return false;
+            // (K slices exist only while tail_units <= kSplitUnits, the range udiv_small is exact in)
+            const int tail_tile = sc.split > 1 ? static_cast<int>(udiv_small(static_cast<unsigned>(u), static_cast<unsigned>(sc.split))) : u;
+            if (!decode_tile(sc, E_local, mt, n_tiles, kind, kind == kTileTail ? tail_tile : u, out)) return false;
             if (kind == kTileTail && sc.split > 1) {
-                const int slice = u % sc.split;
+                const int slice = u - tail_tile * sc.split;
                 out.kt_begin = __builtin_amdgcn_readfirstlane(slice * nk / sc.split);
                 out.kt_end = __builtin_amdgcn_readfirstlane((slice + 1) * nk / sc.split);
                 out.slot = __builtin_amdgcn_readfirstlane(u);
@@ -380,32 +437,6 @@ __device__ __forceinline__ void wait_vmcnt()
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 #endif
-}
-
-// Optional row indirections of the bf16 grouped GEMM; all members null / zero = sorted rows on both sides.
-// They let the contraction read the tokens where they lie (no sorted copy of the activations) and
-// let the second contraction of a top-1 layer write the gate-weighted result straight to the
-// token's own row (no sorted copy of the outputs, no separate combine pass).
-struct RowMap {
-    const int32_t* a_row;     // operand row of sorted row s is a_row[s] / a_div        (null: row s)
-    int a_div;
-    const int32_t* out_row;   // output row of sorted row s is out_row[s]; every output row is the
-    const float* out_scale;   //   target of at most one s and is scaled by out_scale[out_row[s]] in
-                              //   fp32 before the single rounding to bf16              (null: row s, no scale)
-    const int32_t* unrouted;  // [n_unrouted]: output row t with unrouted[t] < 0 is set to zero
-    int n_unrouted;
-    // Measurement only (exf_probe_ffn_timeline; null in every other call): workgroup b < timeline_cap
-    // writes eight 64-bit words - [0] start, [1] tile located, [2] first K tile landed, [3] K loop done,
-    // [4] end (all on the constant 100 MHz clock), [5] hardware id, [6] tile kind / expert / column tile /
-    // rows / K tiles, [7] unused.
-    unsigned long long* timeline;
-    int timeline_cap;
-};
-
-__device__ __forceinline__ void timeline_stamp(const RowMap& map, int slot)
-{
-    if (map.timeline != nullptr && threadIdx.x == 0 && static_cast<int>(blockIdx.x) < map.timeline_cap)
-        map.timeline[static_cast<size_t>(blockIdx.x) * 8 + slot] = wall_clock64();
 }
 
 // One output tile: rows [row_begin,row_end) (at most MT) x columns [n0, n0+NT) of expert weights wexp,
@@ -803,7 +834,7 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
     constexpr bool TALL = tall_tiles_supported(MT, NT, KT, STAGES, WM);
     constexpr int kIdsOff = row_id_scratch_bytes(MT, NT, KT, STAGES, WM, WM * WN) > 0 ? ring_bytes(MT, NT, KT, STAGES, WM) : -1;
     if (!locate_tile(offsets, E_local, MT, n_tiles, max_rows, K / KT, partial != nullptr && MT > kTailRows, TALL,
-                     static_cast<int>(blockIdx.x), tile))
+                     static_cast<int>(blockIdx.x), tile, &map))
         return;
     timeline_stamp(map, 1);
     if (map.timeline != nullptr && threadIdx.x == 0 && static_cast<int>(blockIdx.x) < map.timeline_cap) {
