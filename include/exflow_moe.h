@@ -152,8 +152,10 @@ int moe_dispatch_static(const void* x, const int32_t* topk_idx, const int32_t* e
  *   b1 [E_local,f] dt or NULL;  b2 [E_local,d] dt or NULL;  y_sorted [A,d] dt.
  * bf16: the hidden activations are rounded to bf16 once, between the two contractions.
  * Shapes: d, f multiples of 64 (bf16) / 4 (fp32); 1 <= E_local <= EXF_MAX_EXPERTS.
- * workspace: moe_expert_ffn_workspace_bytes(A, d, f, E_local, dt) bytes (the [A,f] hidden; bf16:
- * plus 16 MiB for the partial sums of remainder tiles that are cut along the reduction).
+ * workspace: moe_expert_ffn_workspace_bytes(A, d, f, E_local, dt) bytes (the hidden activations of
+ * A rows of f values; bf16: in a layout of the library's own in which every expert starts on a 32-row
+ * boundary - A + 32 E_local rows -, plus 16 MiB for the partial sums of remainder tiles that are cut
+ * along the reduction).
  * ------------------------------------------------------------------------------------- */
 size_t moe_expert_ffn_workspace_bytes(int64_t A, int d, int f, int E_local, int dt);
 int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offsets, const void* w1, const void* b1,

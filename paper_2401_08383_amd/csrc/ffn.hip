@@ -2,7 +2,8 @@
 //
 // Two launches of one grouped "NT" GEMM kernel  C[rows of e, N] = A[rows, K] * B_e[N, K]^T
 // (both operands have the reduction dimension contiguous): the first with the bias+GELU
-// epilogue writing the hidden activations [A,f] to the workspace, the second writing y.
+// epilogue writing the hidden activations of the A rows to the workspace (bf16: in a layout of their
+// own that the accumulators can be stored to without a transposition, see RowMap), the second writing y.
 // The per-expert row ranges are read from expert_offsets ON THE DEVICE: the grid is sized for
 // the worst case (ceil(A/MT) + E_local row tiles) and every workgroup locates its own
 // (expert, row tile, column tile) with a wavefront scan; surplus workgroups exit at once.
@@ -76,6 +77,14 @@ enum Epilogue { kEpiNone = 0, kEpiGeluErf = 1, kEpiGeluTanh = 2 };
 // same weight panel, so three or four of them cost more than the one masked tile).  Both kinds are
 // numbered (expert, column tile, row tile); locate_tile() says which kind a launch runs first.
 constexpr int kTailRows = 64;
+constexpr int kHiddenRowBlock = 32;  // rows whose 16-byte pieces are contiguous in the hidden layout
+constexpr uint32_t kHiddenPieceStride = kHiddenRowBlock * 16;  // bytes from piece c to piece c+1 of a row
+// byte offset of the 16-byte piece `piece` (8 columns) of hidden row h; pieces = pieces per row.  (A larger
+// distance between the pieces of a row - 4, 8, 32 KiB - measured the same.)
+__host__ __device__ inline size_t hidden_offset(uint32_t h, uint32_t piece, uint32_t pieces)
+{
+    return (static_cast<size_t>(h / kHiddenRowBlock) * pieces + piece) * kHiddenPieceStride + (h % kHiddenRowBlock) * 16;
+}
 __host__ __device__ constexpr int max_tail_tiles(int mt) { return mt / 2 >= kTailRows ? (mt / 2 + kTailRows - 1) / kTailRows : 1; }
 constexpr int kXcdChunk = 32;  // consecutive tiles handed to one XCD at a time: one per compute unit of the XCD
 constexpr int kLdsBytes = 160 * 1024;  // LDS of a compute unit
@@ -99,6 +108,16 @@ struct RowMap {
                               //   fp32 before the single rounding to bf16              (null: row s, no scale)
     const int32_t* unrouted;  // [n_unrouted]: output row t with unrouted[t] < 0 is set to zero
     int n_unrouted;
+    // The hidden activations between the two contractions live in a layout of their own (nobody else
+    // reads them): 16-byte pieces (8 columns) of 32 consecutive rows are contiguous,
+    //   byte address of (row h, column n) = ((h / 32) * (N / 8) + n / 8) * 512 + (h % 32) * 16 + (n % 8) * 2,
+    // and every expert starts on a 32-row boundary: sorted row m of expert e is hidden row
+    // m + 32 e - (first row of e) % 32.  The first contraction can then store its accumulators as they
+    // lie in the registers (a lane holds 4 consecutive columns of a row; one swap between the two halves
+    // of the wavefront makes that 8), 1 KiB per store instruction, without the transposition through
+    // LDS, and the second contraction's direct-to-LDS loads fetch whole 128-byte lines as before.
+    int hidden_out;           // != 0: `out` is the hidden buffer in that layout (first contraction)
+    int hidden_act;           // != 0: `act` is the hidden buffer in that layout (second contraction)
     // Measurement only (exf_probe_ffn_timeline; null in every other call): workgroup b < timeline_cap
     // writes eight 64-bit words - [0] start, [1] tile located, [2] first K tile landed, [3] K loop done,
     // [4] end (all on the constant 100 MHz clock), [5] hardware id, [6] tile kind / expert / column tile /
@@ -135,6 +154,7 @@ struct Tile2D {
     bool tall;             // a full tile extended by kTailRows rows (see TileSchedule)
     int kt_begin, kt_end;  // K tiles [kt_begin, kt_end) of the reduction this workgroup sums
     int slot;              // >= 0: the sum goes to partial-sum slot `slot` (a K slice of a tail tile)
+    int hid_shift;         // hidden row of sorted row m of this expert: m + hid_shift (see RowMap)
 };
 
 // Tail tiles hold a quarter of the rows of a full tile but walk the same reduction: one takes nearly
@@ -320,6 +340,7 @@ __device__ __forceinline__ bool decode_tile(const TileSchedule& sc, int E_local,
     out.n_tile = __builtin_amdgcn_readfirstlane(col_tile);
     out.row_begin = __builtin_amdgcn_readfirstlane(begin);
     out.row_end = __builtin_amdgcn_readfirstlane(min(begin + height, e_hi));
+    out.hid_shift = __builtin_amdgcn_readfirstlane(kHiddenRowBlock * src - (e_lo & (kHiddenRowBlock - 1)));
     out.tail = tail;
     out.tall = tall;
     return true;
@@ -452,7 +473,7 @@ template <int MT, int NT, int KT, int STAGES, int WM, int WN, int SWZ, int EPI, 
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const bf16_t* __restrict__ wexp,
                                           const bf16_t* __restrict__ bias_e, int row_begin, int row_end, int n0, int K, int N,
                                           bf16_t* __restrict__ out, unsigned char* smem, const RowMap& map, int kt_begin,
-                                          int kt_end, float4* __restrict__ partial, int ids_off = -1)
+                                          int kt_end, float4* __restrict__ partial, int ids_off = -1, int hid_shift = 0)
 {
     constexpr int NWAVES = WM * WN;
     constexpr int RB = KT * 2;              // bytes per tile row
@@ -494,7 +515,17 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
             int r = min(row_begin + row, row_end - 1);  // rows past the tile end re-read the last valid row
             if (from_lds) r = *reinterpret_cast<const int*>(smem + ids_off + (wave * LA + i) * 256 + lane * 4) / map.a_div;
             else if (map.a_row != nullptr) r = map.a_row[r] / map.a_div;
-            off_a[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
+            if (map.hidden_act != 0) {
+                // (never gathered)  Consecutive lanes take consecutive ROWS of one piece - consecutive 16-byte
+                // words of the hidden layout, which the memory pipeline merges into whole lines; the 1 KiB LDS
+                // group of this load then holds [piece][row] instead of [row][piece] (see frag_off_a).
+                const int row_t = (wave * LA + i) * RPI + lane % RPI;
+                const uint32_t h = static_cast<uint32_t>(min(row_begin + row_t, row_end - 1) + hid_shift);
+                // (odd groups hold their pieces pairwise exchanged: two groups that are read together then sit in different banks)
+                off_a[i] = static_cast<uint32_t>(hidden_offset(h, static_cast<uint32_t>((lane / RPI) ^ ((wave * LA + i) & 1)), static_cast<uint32_t>(K) / 8u));
+            } else {
+                off_a[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
+            }
         }
     };
     if (!ids_via_lds) set_off_a(false);
@@ -506,7 +537,9 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         off_w[i] = (static_cast<uint32_t>(r) * static_cast<uint32_t>(K) + chunk * 8) * 2u;
     }
     const size_t k_skip = static_cast<size_t>(kt_begin) * (KT * 2);  // bytes of a row in front of this K range
-    const unsigned char* act_b = uniform_ptr(reinterpret_cast<const unsigned char*>(act) + k_skip);
+    // bytes from one K tile of the activation operand to the next: KT columns of a row, or KT/8 pieces of a 32-row block
+    const size_t a_kstride = map.hidden_act != 0 ? static_cast<size_t>(KT / 8) * kHiddenPieceStride : static_cast<size_t>(KT * 2);
+    const unsigned char* act_b = uniform_ptr(reinterpret_cast<const unsigned char*>(act) + static_cast<size_t>(kt_begin) * a_kstride);
     const unsigned char* wgt_b = uniform_ptr(reinterpret_cast<const unsigned char*>(wexp) + k_skip);
 
     // ---- per-lane LDS byte offsets of the MFMA operand reads -------------------------------
@@ -517,6 +550,17 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         const int swz = chunk_swizzle<KT, SWZ>(row);
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) frag_off[ks] = row * RB + (((2 * ks + (lane >> 5)) ^ swz) * 16);
+    }
+    // activation operand from the hidden layout: LDS groups hold [piece][row] (no swizzle needed: the 8 lanes
+    // served together read 8 consecutive rows of one piece = 128 contiguous bytes)
+    int frag_off_a[KSTEPS];
+    {
+        const int row = lane & 31;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks)
+            frag_off_a[ks] = map.hidden_act != 0
+                                 ? (row / RPI) * 1024 + ((2 * ks + (lane >> 5)) ^ ((row / RPI) & 1)) * (RPI * 16) + (row % RPI) * 16
+                                 : frag_off[ks];
     }
     const int act_base = (wm * WTM) * RB;            // activation rows of this wavefront inside a stage
     const int wgt_base = (MT + wn * WTN) * RB;       // weight rows of this wavefront inside a stage
@@ -536,7 +580,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
         const uint32_t stage = smem_addr + (kt % STAGES) * STAGE_BYTES;
         const size_t kbyte = static_cast<size_t>(kt) * (KT * 2);
 #pragma unroll
-        for (int i = 0; i < LA; ++i) lds_dma_16B(act_b + kbyte, off_a[i], stage + (wave * LA + i) * 1024);
+        for (int i = 0; i < LA; ++i) lds_dma_16B(act_b + static_cast<size_t>(kt) * a_kstride, off_a[i], stage + (wave * LA + i) * 1024);
 #pragma unroll
         for (int i = 0; i < LW; ++i) lds_dma_16B(wgt_b + kbyte, off_w[i], stage + MT * RB + (wave * LW + i) * 1024);
     };
@@ -545,7 +589,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     auto issue_one = [&](int kt, int i) {
         const uint32_t stage = smem_addr + (kt % STAGES) * STAGE_BYTES;
         const size_t kbyte = static_cast<size_t>(kt) * (KT * 2);
-        if (i < LA) lds_dma_16B(act_b + kbyte, off_a[i < LA ? i : 0], stage + (wave * LA + i) * 1024);
+        if (i < LA) lds_dma_16B(act_b + static_cast<size_t>(kt) * a_kstride, off_a[i < LA ? i : 0], stage + (wave * LA + i) * 1024);
         else lds_dma_16B(wgt_b + kbyte, off_w[i >= LA ? i - LA : 0], stage + MT * RB + (wave * LW + (i - LA)) * 1024);
     };
 
@@ -584,7 +628,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
                 const uint32_t stage = smem_addr + s * STAGE_BYTES;
 #pragma unroll
                 for (int i = 0; i < LA; ++i)
-                    lds_dma_16B(act_b + static_cast<size_t>(s) * (KT * 2), off_a[i], stage + (wave * LA + i) * 1024);
+                    lds_dma_16B(act_b + static_cast<size_t>(s) * a_kstride, off_a[i], stage + (wave * LA + i) * 1024);
             }
             if (n_first == 2) wait_vmcnt<LA>();  // K tile 0 complete; the activation rows of K tile 1 may be in flight
             else wait_vmcnt<0>();
@@ -618,7 +662,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
     bf16x8_t fa[FD][TN], fb[FD][TM];
     auto fetch = [&](const unsigned char* stage, int ks, int r) {  // operand r of K step ks from a stage
         if (r < TN) fa[ks % FD][r] = *reinterpret_cast<const bf16x8_t*>(stage + wgt_base + r * 32 * RB + frag_off[ks]);
-        else fb[ks % FD][r - TN] = *reinterpret_cast<const bf16x8_t*>(stage + act_base + (r - TN) * 32 * RB + frag_off[ks]);
+        else fb[ks % FD][r - TN] = *reinterpret_cast<const bf16x8_t*>(stage + act_base + (r - TN) * 32 * RB + frag_off_a[ks]);
     };
     constexpr int NFRAG = TN + TM;
 #pragma unroll
@@ -734,6 +778,49 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ act, const 
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     bias_v[a][g][r] = bf16_to_f32(bexp[min(n_wave + a * 32 + g * 8 + (lane >> 5) * 4 + r, N - 1)]);
+    }
+    if (map.hidden_out != 0) {
+        // hidden layout: no transposition.  For a pair of column groups (g, g+1) the lower half of the
+        // wavefront gives its 4 columns of group g+1 to the upper half and receives the upper half's 4
+        // columns of group g: every lane then holds 8 consecutive columns of its row = one 16-byte piece,
+        // the lower half of group g, the upper half of group g+1 - 1 KiB contiguous per store.
+        const uint32_t pieces = static_cast<uint32_t>(N) / 8u;
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            const int m = row_begin + wm * WTM + b * 32 + (lane & 31);
+            const uint32_t h = static_cast<uint32_t>(m + hid_shift);
+            unsigned char* row_base = reinterpret_cast<unsigned char*>(out) + hidden_offset(h, 0u, pieces);
+#pragma unroll
+            for (int a = 0; a < TN; ++a) {
+#pragma unroll
+                for (int gp = 0; gp < 2; ++gp) {
+                    uint32_t w[2][2];
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const int g = 2 * gp + q;
+                        float v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float z = acc[a][b][g * 4 + r];
+                            if constexpr (BIAS) z += bias_v[a][g][r];
+                            if constexpr (EPI == kEpiGeluErf) z = gelu_erf_fast(z);
+                            if constexpr (EPI == kEpiGeluTanh) z = gelu_tanh_fast(z);
+                            v[r] = z;
+                        }
+                        w[q][0] = pack_bf16x2(v[0], v[1]);
+                        w[q][1] = pack_bf16x2(v[2], v[3]);
+                    }
+                    // w[0] lanes 32..63 <-> w[1] lanes 0..31
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                    const uint4 val = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+                    const int n = n_wave + a * 32 + gp * 16 + (lane >> 5) * 8;
+                    if (m < row_end && n < N)
+                        store_stream16(reinterpret_cast<uint4*>(row_base + static_cast<size_t>(n / 8) * kHiddenPieceStride), val);
+                }
+            }
+        }
+        return;
     }
     constexpr int NIT = BP * 32 / RPI_OUT;          // store instructions per pass
     const bool scatter = EPI == kEpiNone && map.out_row != nullptr;
@@ -855,10 +942,11 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
         if constexpr (TALL)
             gemm_tile<MT + kTailRows, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS, false>(act, wexp, bias_e, tile.row_begin, tile.row_end,
                                                                                      tile.n_tile * NT, K, N, out, smem, map, 0, K / KT,
-                                                                                     nullptr, kIdsOff);
+                                                                                     nullptr, kIdsOff, tile.hid_shift);
     } else if (!tile.tail || MT <= kTailRows) {
         gemm_tile<MT, NT, KT, STAGES, WM, WN, SWZ, EPI, BIAS, false>(act, wexp, bias_e, tile.row_begin, tile.row_end,
-                                                                     tile.n_tile * NT, K, N, out, smem, map, 0, K / KT, nullptr, kIdsOff);
+                                                                     tile.n_tile * NT, K, N, out, smem, map, 0, K / KT, nullptr, kIdsOff,
+                                                                     tile.hid_shift);
     } else if constexpr (MT > kTailRows) {
         // remainder rows: the wavefronts side by side over the columns, kTailRows rows each (two rows
         // of wavefronts when a column strip would become narrower than one MFMA tile).  A
@@ -871,7 +959,8 @@ __global__ __launch_bounds__(WM* WN * 64, OCC) void grouped_gemm_bf16_kernel(con
         constexpr int WM_T = NT / (WM * WN) >= 32 ? 1 : 2;
         float4* slot = tile.slot >= 0 ? partial + static_cast<size_t>(tile.slot) * (kTailRows * NT / 4) : nullptr;
         gemm_tile<kTailRows, NT, KT, STAGES_T, WM_T, WM * WN / WM_T, SWZ, EPI, BIAS, true>(
-            act, wexp, bias_e, tile.row_begin, tile.row_end, tile.n_tile * NT, K, N, out, smem, map, tile.kt_begin, tile.kt_end, slot);
+            act, wexp, bias_e, tile.row_begin, tile.row_end, tile.n_tile * NT, K, N, out, smem, map, tile.kt_begin, tile.kt_end, slot,
+            -1, tile.hid_shift);
     }
     timeline_stamp(map, 4);
 }
@@ -1120,14 +1209,22 @@ static int launch_second_contraction(const void* act, const int32_t* offsets, co
 }  // namespace exf
 
 
+namespace exf {
+// Bytes of the hidden activations of A sorted rows.  bf16: every expert starts on a 32-row boundary
+// (see RowMap), so up to 32 rows per expert are padding.
+static size_t hidden_bytes(int64_t A, int f, int E_local, int dt)
+{
+    size_t rows = static_cast<size_t>(A > 0 ? A : 1);
+    if (dt == EXF_BF16) rows = (rows + static_cast<size_t>(kHiddenRowBlock) * (E_local > 0 ? E_local : 1) + kHiddenRowBlock - 1) / kHiddenRowBlock * kHiddenRowBlock;
+    return align_up(rows * static_cast<size_t>(f) * (dt == EXF_BF16 ? 2 : 4), 256);
+}
+}  // namespace exf
+
 extern "C" size_t moe_expert_ffn_workspace_bytes(int64_t A, int d, int f, int E_local, int dt)
 {
     (void)d;
-    (void)E_local;
     if (A < 0 || f < 1 || (dt != EXF_F32 && dt != EXF_BF16)) return 0;
-    const size_t elem = dt == EXF_BF16 ? 2 : 4;
-    const size_t hidden = exf::align_up(static_cast<size_t>(A > 0 ? A : 1) * static_cast<size_t>(f) * elem, 256);
-    return hidden + (dt == EXF_BF16 ? exf::kSplitBytes : 0);  // bf16: + the partial sums of K-sliced tail tiles
+    return exf::hidden_bytes(A, f, E_local, dt) + (dt == EXF_BF16 ? exf::kSplitBytes : 0);  // bf16: + the partial sums of K-sliced tail tiles
 }
 
 extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offsets, const void* w1, const void* b1, const void* w2,
@@ -1145,9 +1242,10 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
         return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn: d = %d and f = %d must be positive multiples of %d", d, f, gran);
     if (dt == EXF_BF16) {  // the bf16 kernel addresses rows with 32-bit byte offsets
         const unsigned long long widest = static_cast<unsigned long long>(d > f ? d : f);
-        if (static_cast<unsigned long long>(A) * widest * 2ull >= (1ull << 32) ||
+        const unsigned long long rows = static_cast<unsigned long long>(A) + static_cast<unsigned long long>(kHiddenRowBlock) * (E_local + 1);
+        if (rows * widest * 2ull >= (1ull << 32) ||
             static_cast<unsigned long long>(d) * static_cast<unsigned long long>(f) * 2ull >= (1ull << 32))
-            return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn: A*max(d,f) and d*f must stay below 2^31 elements (bf16)");
+            return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn: (A + 32 (E_local + 1))*max(d,f) and d*f must stay below 2^31 elements (bf16)");
     }
     if (A == 0) return EXF_OK;
     EXF_REQUIRE_PTR(x_sorted);
@@ -1171,11 +1269,14 @@ extern "C" int moe_expert_ffn(const void* x_sorted, const int32_t* expert_offset
         rc = launch_f32(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s);
         if (rc == EXF_OK) rc = launch_f32(workspace, expert_offsets, w2, b2, A, f, d, E_local, kEpiNone, y_sorted, s);
     } else {
-        void* partial = static_cast<unsigned char*>(workspace) + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * 2, 256);
-        rc = launch_wide_tile(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s, RowMap{},
+        void* partial = static_cast<unsigned char*>(workspace) + hidden_bytes(A, f, E_local, dt);
+        RowMap first{}, second{};
+        first.hidden_out = 1;
+        second.hidden_act = 1;
+        rc = launch_wide_tile(x_sorted, expert_offsets, w1, b1, A, d, f, E_local, epi, workspace, s, first,
                               kSplitFirstContraction ? partial : nullptr);
         if (rc == EXF_OK)
-            rc = launch_second_contraction(workspace, expert_offsets, w2, b2, A, f, d, E_local, y_sorted, s, RowMap{}, partial);
+            rc = launch_second_contraction(workspace, expert_offsets, w2, b2, A, f, d, E_local, y_sorted, s, second, partial);
     }
     if (rc != EXF_OK) return rc;
     return check_launch("moe_expert_ffn");
@@ -1186,11 +1287,10 @@ extern "C" int moe_combine(const void* y_sorted, const int32_t* sorted_of_src, c
 
 extern "C" size_t moe_expert_ffn_fused_workspace_bytes(int64_t T, int k, int d, int f, int E_local, int dt)
 {
-    (void)E_local;
     if (T < 0 || k < 1 || k > EXF_MAX_TOPK || d < 1 || f < 1 || (dt != EXF_BF16 && dt != EXF_F32)) return 0;
     const size_t elem = dt == EXF_BF16 ? 2 : 4;
     const size_t A = static_cast<size_t>(T > 0 ? T : 1) * static_cast<size_t>(k);
-    size_t bytes = exf::align_up(A * static_cast<size_t>(f) * elem, 256);        // hidden activations [A,f]
+    size_t bytes = exf::hidden_bytes(static_cast<int64_t>(A), f, E_local, dt);  // hidden activations of A rows
     if (k > 1) bytes += exf::align_up(A * static_cast<size_t>(d) * elem, 256);   // sorted expert outputs [A,d]
     return bytes + (dt == EXF_BF16 ? exf::kSplitBytes : 0);                      // bf16: partial sums of K-sliced tail tiles
 }
@@ -1215,9 +1315,10 @@ static int ffn_fused_run(const char* fn, const void* x, const int32_t* src_of_so
     const int64_t A = T * k;
     if (dt == EXF_BF16) {  // the bf16 kernel addresses rows with 32-bit byte offsets
         const unsigned long long widest = static_cast<unsigned long long>(d > f ? d : f);
-        if (static_cast<unsigned long long>(A) * widest * 2ull >= (1ull << 32) ||
+        const unsigned long long rows = static_cast<unsigned long long>(A) + static_cast<unsigned long long>(kHiddenRowBlock) * (E_local + 1);
+        if (rows * widest * 2ull >= (1ull << 32) ||
             static_cast<unsigned long long>(d) * static_cast<unsigned long long>(f) * 2ull >= (1ull << 32))
-            return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: T*k*max(d,f) and d*f must stay below 2^31 elements");
+            return fail(EXF_ERR_BAD_SHAPE, "moe_expert_ffn_fused: (T*k + 32 (E_local + 1))*max(d,f) and d*f must stay below 2^31 elements");
     }
     if (T == 0) return EXF_OK;
     EXF_REQUIRE_PTR(x);
@@ -1255,7 +1356,11 @@ static int ffn_fused_run(const char* fn, const void* x, const int32_t* src_of_so
         scatter.unrouted = sorted_of_src;
         scatter.n_unrouted = static_cast<int>(T);
     }
-    unsigned char* y_sorted = hidden + align_up(static_cast<size_t>(A) * static_cast<size_t>(f) * elem, 256);
+    unsigned char* y_sorted = hidden + hidden_bytes(A, f, E_local, dt);
+    if (dt == EXF_BF16) {
+        gather.hidden_out = 1;
+        scatter.hidden_act = 1;
+    }
     void* second_out = k == 1 ? out : static_cast<void*>(y_sorted);
     int rc;
     if (dt == EXF_F32) {

@@ -125,10 +125,12 @@ def test_workspace_sizes():
     assert lib.moe_dispatch_workspace_bytes(0, 1, 8) >= 32
     assert lib.moe_dispatch_workspace_bytes(32768, 1, 8) % 256 == 0
     split = 256 * 64 * 256 * 4  # bf16: room for the partial sums of K-sliced remainder tiles
-    assert lib.moe_expert_ffn_workspace_bytes(8192, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2 + split
+    # bf16 hidden rows: every expert starts on a 32-row boundary (A + 32 E_local rows, rounded up to 32)
+    assert lib.moe_expert_ffn_workspace_bytes(8192, 1024, 4096, 8, B.EXF_BF16) == (8192 + 32 * 8) * 4096 * 2 + split
+    assert lib.moe_expert_ffn_workspace_bytes(8191, 1024, 4096, 8, B.EXF_BF16) == (8192 + 32 * 8) * 4096 * 2 + split
     assert lib.moe_expert_ffn_workspace_bytes(512, 64, 256, 8, B.EXF_F32) == 512 * 256 * 4
-    assert lib.moe_expert_ffn_fused_workspace_bytes(8192, 1, 1024, 4096, 8, B.EXF_BF16) == 8192 * 4096 * 2 + split
-    assert lib.moe_expert_ffn_fused_workspace_bytes(256, 2, 4096, 16384, 64, B.EXF_BF16) == 512 * (16384 + 4096) * 2 + split
+    assert lib.moe_expert_ffn_fused_workspace_bytes(8192, 1, 1024, 4096, 8, B.EXF_BF16) == (8192 + 32 * 8) * 4096 * 2 + split
+    assert lib.moe_expert_ffn_fused_workspace_bytes(256, 2, 4096, 16384, 64, B.EXF_BF16) == ((512 + 32 * 64) * 16384 + 512 * 4096) * 2 + split
     assert lib.moe_expert_ffn_fused_workspace_bytes(512, 1, 64, 256, 8, B.EXF_F32) == 512 * 256 * 4
     assert lib.moe_expert_ffn_fused_workspace_bytes(512, 1, 64, 256, 8, 7) == 0
     ws = lib.affinity_histogram_workspace_bytes(24, 1 << 20, 64)
