@@ -473,6 +473,20 @@ def test_affinity_invalid_ids_and_degenerate(oracle):
     _affinity_case(oracle, tr, 8, pl, 4)
 
 
+@pytest.mark.parametrize("L,N,E,G", [(6, 8000, 16, 4), (24, 5461, 64, 8), (3, 1000, 64, 8), (1, 131072, 8, 2), (2, 65536, 5, 5),
+                                     (2, 65537, 5, 5)])
+def test_affinity_short_traces_with_invalid_ids(oracle, L, N, E, G):
+    """Short traces (one or two token chunks, several groups of layer pairs at 64 experts, a single
+    layer) with ids outside [0,E) in every layer."""
+    _say(f"affinity short trace L={L} N={N} E={E} G={G}")
+    trace, _ = syn.planted_trace(L, N, E, 0.6, seed=730 + L + E)
+    g = syn.rng(731 + N)
+    bad = g.random((L, N)) < 0.02
+    trace[bad] = g.choice(np.array([-1, E, 1 << 20, -(1 << 31)]), size=int(bad.sum())).astype(np.int32)
+    pl = g.integers(0, G, size=(L, E)).astype(np.int32)
+    _affinity_case(oracle, trace, E, pl, G)
+
+
 def test_locality_paper_worked_example_on_gpu():
     # the 3-layer MoE-8 walk-through: default placement gpu = e // 2 keeps 2 of 4 transitions local
     trace = np.array([[0, 5], [4, 5], [2, 4]], dtype=np.int32)
