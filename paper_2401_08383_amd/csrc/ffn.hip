@@ -184,21 +184,19 @@ constexpr bool kSplitFirstContraction = false;
 //             and the n%8 left over go one each to consecutive XCDs, continuing where the previous
 //             kind stopped.  With chunks, a launch of two or three rounds leaves some XCDs a whole
 //             chunk of long tiles more than others (700 against 580 us for the second contraction of
-//             a skewed 32-expert batch).
-// A launch is balanced when chunks would leave some XCD more than kChunkedMaxExcess (in 1/64) above
-// the mean work, counted in rows per item (a tail tile as half a full tile, shared by its K slices).
-constexpr int kChunkedMaxExcess = 10;  // 64/64 + 10/64 = 1.16 x the mean
+//             a skewed 32-expert batch), and a one-round launch of 8 experts x 32 tiles puts halves of
+//             two experts on an XCD instead of one expert (L2 hit rate 0.71 against 0.78).
+// A launch of at most kBalancedMaxRounds rounds of work items, or of items of one kind only (contiguous shares
+// then cost nothing: all tiles take the same time), is balanced, a longer mixed one chunked: same-run
+// timings of the whole call (chunked / balanced, us): 8192 tokens (two rounds per launch) 157.2 / 153.8;
+// 256 tokens x 64 experts (two to four rounds of remainder tiles) 2997 / 2894; skewed 32 experts (ten and
+// 2.5 rounds) 1313 / 1225 with both launches balanced and as good with only the short one; 32768 tokens on
+// 8 experts (eight and two rounds) 549 / 564 on one box and equal on another.
+constexpr int kBalancedMaxRounds = 5;
 __device__ __forceinline__ int chunked_item_of_workgroup(int wg)
 {
     const unsigned xcd = static_cast<unsigned>(wg) % kXcdCount, slot = static_cast<unsigned>(wg) / kXcdCount;
     return static_cast<int>(((slot / kXcdChunk) * kXcdCount + xcd) * kXcdChunk + slot % kXcdChunk);
-}
-// Of the list positions [0, p), how many the chunked order gives to XCD `xcd`.
-__device__ __forceinline__ int chunked_positions_before(int p, int xcd)
-{
-    constexpr unsigned round = kXcdCount * kXcdChunk;
-    const unsigned up = static_cast<unsigned>(p);
-    return static_cast<int>(up / round) * kXcdChunk + min(max(static_cast<int>(up % round) - xcd * kXcdChunk, 0), kXcdChunk);
 }
 // Size of XCD `xcd`'s share of n items of one kind; `begin` receives its first item.
 __device__ __forceinline__ int xcd_share(int n, int xcd, int& rot, int& begin)
@@ -363,23 +361,8 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ offsets,
     const bool tails_first = tail_units <= kSplitUnits;
     const int total = sc.total_tall + sc.total_full + tail_units;
     const int xcd = static_cast<int>(static_cast<unsigned>(wg) % kXcdCount);
-    bool balanced = false;
-    if (total <= (1 << 20)) {  // (longer launches: a chunk more or less no longer matters, and the sums below stay in range)
-        // lane x < 8: work of XCD x under the chunked order
-        const int x = lane_id() % kXcdCount;
-        int load = 0, all = 0, p = 0;
-#pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            const int kind = c == 0 ? kTileTall : ((tails_first ? c == 1 : c == 2) ? kTileTail : kTileFull);
-            const int n = kind == kTileTall ? sc.total_tall : (kind == kTileTail ? tail_units : sc.total_full);
-            const int w = kind == kTileTall ? mt + kTailRows : (kind == kTileTail ? max(mt / 2 / sc.split, 1) : mt);
-            load += w * (chunked_positions_before(p + n, x) - chunked_positions_before(p, x));
-            all += w * n;
-            p += n;
-        }
-        // some XCD above (1 + excess/64) * all/8 ?  (floats: the same rounding in every workgroup)
-        balanced = __ballot(static_cast<float>(load) * (64.0f * kXcdCount) > static_cast<float>(all) * (64.0f + kChunkedMaxExcess)) != 0ull;
-    }
+    const int kinds = (sc.total_tall > 0 ? 1 : 0) + (sc.total_full > 0 ? 1 : 0) + (tail_units > 0 ? 1 : 0);
+    const bool balanced = total <= kBalancedMaxRounds * kSplitUnits || kinds <= 1;
     int pos = balanced ? static_cast<int>(static_cast<unsigned>(wg) / kXcdCount) : chunked_item_of_workgroup(wg);  // in the XCD's queue / in the list
     if (!balanced && pos >= total) return false;
     int rot = 0, begin = 0;
