@@ -228,8 +228,14 @@ def other_configs(syn, torch, MoELayerRun, dev):
             kw["expert_map"] = torch.from_numpy(map4_h).to(dev)
         run = MoELayerRun(x, wg, w1, w2, c.k, c.renormalize, fused=True, **kw)
         run.step()
-        ffn = _time_groups([run.ffn], groups=6, inner=3, warmup=3)
-        layer = _time_groups([run.step], groups=6, inner=3, warmup=2)
+        torch.cuda.synchronize()
+        t_w = time.perf_counter()  # the same fixed warm-up as the benchmark step: clocks and caches settle
+        while time.perf_counter() - t_w < WARM_SECONDS:
+            for _ in range(4):
+                run.step()
+            torch.cuda.synchronize()
+        ffn = _time_groups([run.ffn], groups=10, inner=4, warmup=4)
+        layer = _time_groups([run.step], groups=10, inner=4, warmup=4)
         A = c.T * c.k
         flops = 4.0 * A * c.d * c.f
         entry = {"workload": c.name, "tokens": c.T, "d_model": c.d, "d_ff": c.f, "local_experts": c.E_local, "top_k": c.k,
